@@ -1,0 +1,165 @@
+/*
+ * compactfusion.h -- C ABI of the MI355X (gfx950) residual codec.
+ *
+ * The codec is the per-layer, per-step hot path of CompactFusion
+ * (arxiv 2507.17511).  For every activation tensor X_t in R^{N x C} of a
+ * diffusion step it
+ *   a1  forms the residual against the stored reconstruction,
+ *         r = x_t - recon_{t-1}                               (Sec. 3.1; App. H, residual recursion)
+ *   a2  applies error feedback (see cf_ef_mode)               (Sec. 3.2; App. D "Residual Base and Error Feedback")
+ *   a3  reduces the scales of z                               (App. D "Quantization": v_j = mean_i |z_ij|)
+ *   a4  selects low-bit codes, a5 packs them                  (App. D: +-1; {-2,-0.5,+0.5,+2})
+ *   a6  decodes them, D = level(code) * scale                 (App. D: Q(X) = q(X) (.) scale)
+ *   a7  updates the sender's error buffer, e_t = z - D        (Sec. 3.2)
+ *   a8  updates the reconstruction, recon_t = recon_{t-1} + D (App. H: a~_t = a~_{t-1} + C(Delta a*_t))
+ * and a warm-up call seeds the state with an uncompressed step, recon_0 = x_0,
+ * e_0 = 0 (App. D "Warmup Implementation"; App. H.2).
+ *
+ * Memory and streams.  Every tensor pointer is a DEVICE pointer owned by the
+ * caller; the pointer *arrays* are HOST arrays of `count` device pointers.  The
+ * library allocates and frees no device memory: its scratch lives in the
+ * caller's workspace (cf_workspace_bytes), which it may overwrite on every
+ * call.  `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ * All calls enqueue work on it and return without synchronising; buffers must
+ * stay valid until the stream has passed that work.  A context is not
+ * thread-safe: use it from one host thread at a time, on one stream at a time.
+ *
+ * Layouts (all dense, row-major, C contiguous; base pointers 16-byte aligned):
+ *   x, recon : [N, C] of `dtype`
+ *   err      : [N, C] of `err_dtype`
+ *   codes    : [N, C*bits/8] bytes; byte k of a row holds channels
+ *              (8/bits)*k ... (8/bits)*k + 8/bits - 1, channel (8/bits)*k + m in
+ *              bits [bits*m, bits*m + bits)  (least significant first)
+ *   scales   : fp32 [C] (CF_SCALE_CHANNEL), fp32 [N, C/group] (CF_SCALE_GROUP),
+ *              fp32 v[C] followed by u[N] (CF_SCALE_RANK1)
+ * x must not alias recon or err; codes and scales must alias nothing.
+ *
+ * Codes.  1-bit: bit = 1 for z < 0.  2-bit: bit1 = sign, bit0 = magnitude
+ * (0 -> 0.5, 1 -> 2), magnitude bit set iff |z| > 1.25*scale.  4-bit (this
+ * library's extension; the paper defines no 4-bit activation code): q =
+ * round-half-even(z / scale) clamped to [-7, 7] as a two's-complement nibble,
+ * scale = max|z| / 7 over the column or the group.  All value arithmetic is
+ * IEEE fp32, one rounding per operation; channel sums use a balanced binary
+ * tree over the token index (padded with zeros to a power of two), so results
+ * do not depend on the launch shape.  NaN or Inf inputs give undefined values
+ * (never a fault).
+ *
+ * Errors.  Every entry point returns a cf_status; nothing is thrown.  On any
+ * error no work is enqueued and no state changes.
+ */
+#ifndef COMPACTFUSION_H
+#define COMPACTFUSION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cf_ctx cf_ctx; /* opaque; host memory owned by the library */
+
+typedef enum {
+    CF_OK = 0,
+    CF_ERR_INVALID_ARG = 1, /* null pointer, bad range, misaligned tensor pointer */
+    CF_ERR_SHAPE = 2,       /* N < 1, C < 8, C % 8 != 0, C % group != 0, group != 128 */
+    CF_ERR_UNSUPPORTED = 3, /* (bits, scale) pair, dtype or option outside the supported set */
+    CF_ERR_STATE = 4,       /* codec step on a tensor that was never warmed up */
+    CF_ERR_WORKSPACE = 5,   /* workspace null, too small or not 256-byte aligned */
+    CF_ERR_DEVICE = 6       /* a HIP call failed; see cf_last_hip_error */
+} cf_status;
+
+typedef enum { CF_F32 = 0, CF_BF16 = 1 } cf_dtype;
+
+/* What a scale spans.  CHANNEL: all N tokens of one channel (the paper's v_j
+ * with u = 1).  GROUP: `group` consecutive channels of one token (4-bit only).
+ * RANK1: the paper's u v^T, s_ij = u_i * v_j with u_i = rowmean|z| / mean|z|
+ * (1-/2-bit only). */
+typedef enum { CF_SCALE_CHANNEL = 0, CF_SCALE_GROUP = 1, CF_SCALE_RANK1 = 2 } cf_scale_kind;
+
+/* How the error buffer enters (a2) and is updated (a7).
+ *   CF_EF_RECON   z = x_t - recon_{t-1}; e_t = z - D.  The residual against the
+ *                 reconstruction already carries last step's error, so e is
+ *                 written every step and never read; recon_t + e_t = x_t.
+ *   CF_EF_LITERAL z = (x_t - recon_{t-1}) + e_{t-1}; e_t = z - D.
+ *   CF_EF_OFF     z = (x_t - recon_{t-1}) - e_{t-1} (the true residual
+ *                 x_t - x_{t-1}: the paper's no-feedback ablation);
+ *                 e_t = e_{t-1} + (z - D). */
+typedef enum { CF_EF_RECON = 0, CF_EF_LITERAL = 1, CF_EF_OFF = 2 } cf_ef_mode;
+
+typedef struct {
+    int64_t n_tokens;   /* N >= 1 */
+    int64_t n_channels; /* C >= 8, multiple of 8 (and of group for CF_SCALE_GROUP) */
+    int32_t dtype;      /* cf_dtype of x and recon */
+    int32_t bits;       /* 1, 2 or 4 */
+    int32_t scale;      /* cf_scale_kind; supported pairs: (1|2|4, CHANNEL), (4, GROUP), (1|2, RANK1) */
+    int32_t group;      /* 128 when scale == CF_SCALE_GROUP, ignored otherwise */
+} cf_tensor_desc;
+
+typedef struct {
+    int32_t ef;        /* cf_ef_mode */
+    int32_t err_dtype; /* cf_dtype of every error buffer; CF_F32 by default */
+    uint32_t flags;    /* CF_FLAG_* */
+    int32_t tile_rows; /* rows per workgroup tile: 0 = chosen by the library, else 8, 16, 32 or 64
+                          (a tuning knob: results do not depend on it) */
+} cf_options;
+
+/* Use only the separate-kernel path (scale reduction, finalise, encode) and
+ * never the single persistent kernel.  Results are bit-identical either way. */
+#define CF_FLAG_NO_PERSISTENT 0x1u
+
+/* Byte sizes of one tensor's buffers.  Any output pointer may be NULL.
+ * CF_ERR_SHAPE / CF_ERR_UNSUPPORTED as for cf_init. */
+cf_status cf_sizes(const cf_tensor_desc *desc, const cf_options *opts, size_t *codes_bytes,
+                   size_t *scales_bytes, size_t *recon_bytes, size_t *err_bytes);
+
+/* Bytes of workspace cf_init needs for these tensors (0 if they are invalid). */
+size_t cf_workspace_bytes(const cf_tensor_desc *descs, int32_t n_tensors, const cf_options *opts);
+
+/* Create a context for `n_tensors` layer tensors (App. H.2: state is kept per
+ * layer tensor).  Validates every descriptor, lays the workspace out and
+ * uploads the descriptor table to it on `stream`.  `opts` may be NULL
+ * (CF_EF_RECON, fp32 error).  The workspace must be device memory, 256-byte
+ * aligned, at least cf_workspace_bytes() long, and outlive the context.
+ * Uses the device that is current at the call. */
+cf_status cf_init(cf_ctx **out, const cf_tensor_desc *descs, int32_t n_tensors, const cf_options *opts,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* a0, warm-up of tensors [first, first+count): recon <- x0, err <- 0; the step
+ * counts as sent uncompressed (App. D "Warmup Implementation", option 1). */
+cf_status cf_warmup(cf_ctx *ctx, int32_t first, int32_t count, const void *const *x0,
+                    void *const *recon, void *const *err, void *stream);
+
+/* Declare tensors warm (or not) without touching memory: resuming from state
+ * buffers the caller restored, or a receiver whose base arrived elsewhere. */
+cf_status cf_set_warm(cf_ctx *ctx, int32_t first, int32_t count, int32_t warm);
+
+/* Sender half (a1-a7): reads x and recon, reads/writes err, writes codes and
+ * scales.  recon is not modified. */
+cf_status cf_compress(cf_ctx *ctx, int32_t first, int32_t count, const void *const *x,
+                      const void *const *recon, void *const *err, void *const *codes,
+                      void *const *scales, void *stream);
+
+/* Receiver half (a6, a8): reads codes and scales, updates recon in place. */
+cf_status cf_decompress(cf_ctx *ctx, int32_t first, int32_t count, const void *const *codes,
+                        const void *const *scales, void *const *recon, void *stream);
+
+/* One whole codec step (a1-a8) for tensors [first, first+count) in one batched
+ * launch: bit-identical, in every output, to cf_compress followed by
+ * cf_decompress on the same buffers. */
+cf_status cf_step_fused(cf_ctx *ctx, int32_t first, int32_t count, const void *const *x,
+                        void *const *recon, void *const *err, void *const *codes,
+                        void *const *scales, void *stream);
+
+/* Frees the host-side context (never device memory).  NULL is allowed. */
+void cf_destroy(cf_ctx *ctx);
+
+const char *cf_status_string(cf_status s);
+
+/* The hipError_t value of the last failed HIP call in this context (0 if none). */
+int32_t cf_last_hip_error(const cf_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

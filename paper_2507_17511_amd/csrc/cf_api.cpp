@@ -1,0 +1,435 @@
+// C-ABI layer of the residual codec: argument validation, workspace layout,
+// per-call pointer tables and kernel sequencing.  No arithmetic of the method
+// happens here; see cf_kernels.hip.  Declarations and their citations of
+// arxiv 2507.17511 are in include/compactfusion.h.
+#include "compactfusion.h"
+
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "cf_internal.h"
+
+using namespace cf;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+    size_t off_descs = 0, off_ptrs = 0, off_tile_prefix = 0, off_fin_prefix = 0, off_partials = 0;
+    size_t total = 0;
+    std::vector<TensorDev> dev;
+    std::vector<uint32_t> tile_prefix, fin_prefix;
+    bool any_channel = false;
+};
+
+cf_status check_opts(const cf_options *o, cf_options &out)
+{
+    out.ef = CF_EF_RECON;
+    out.err_dtype = CF_F32;
+    out.flags = 0;
+    out.tile_rows = 0;
+    if (!o) return CF_OK;
+    if (o->ef != CF_EF_RECON && o->ef != CF_EF_LITERAL && o->ef != CF_EF_OFF) return CF_ERR_UNSUPPORTED;
+    if (o->err_dtype != CF_F32 && o->err_dtype != CF_BF16) return CF_ERR_UNSUPPORTED;
+    if (o->flags & ~CF_FLAG_NO_PERSISTENT) return CF_ERR_UNSUPPORTED;
+    if (o->tile_rows != 0 && o->tile_rows != 8 && o->tile_rows != 16 && o->tile_rows != 32 && o->tile_rows != 64)
+        return CF_ERR_UNSUPPORTED;
+    out = *o;
+    return CF_OK;
+}
+
+cf_status check_desc(const cf_tensor_desc &d)
+{
+    if (d.n_tokens < 1 || d.n_channels < 8 || d.n_channels % 8 != 0) return CF_ERR_SHAPE;
+    if (d.n_channels > (int64_t)1 << 30 || d.n_tokens > (int64_t)1 << 40) return CF_ERR_SHAPE;
+    if (d.n_tokens > ((int64_t)1 << 46) / d.n_channels) return CF_ERR_SHAPE;
+    if (d.dtype != CF_F32 && d.dtype != CF_BF16) return CF_ERR_UNSUPPORTED;
+    if (d.bits != 1 && d.bits != 2 && d.bits != 4) return CF_ERR_UNSUPPORTED;
+    if (d.scale == CF_SCALE_CHANNEL) return CF_OK;
+    if (d.scale == CF_SCALE_GROUP) {
+        if (d.bits != 4) return CF_ERR_UNSUPPORTED;
+        if (d.group != 128 || d.n_channels % 128 != 0) return CF_ERR_SHAPE;
+        return CF_OK;
+    }
+    return CF_ERR_UNSUPPORTED;   // CF_SCALE_RANK1 is declared but not built yet
+}
+
+size_t dtype_size(int32_t dt) { return dt == CF_BF16 ? 2 : 4; }
+
+// Rows per tile: as large as still leaves the batched grid a few thousand
+// workgroups (256 CUs, several resident workgroups each).
+int pick_rb_rows(const cf_tensor_desc *descs, int32_t n, const cf_options &o)
+{
+    if (o.tile_rows) return o.tile_rows;
+    const int cands[] = {64, 32, 16, 8};
+    for (int rb : cands) {
+        uint64_t tiles = 0;
+        for (int32_t t = 0; t < n; ++t) {
+            uint64_t rbn = (uint64_t)((descs[t].n_tokens + rb - 1) / rb);
+            uint64_t cbn = (uint64_t)((descs[t].n_channels / kChunk + kTileThreads - 1) / kTileThreads);
+            tiles += rbn * cbn;
+        }
+        if (tiles >= 4096) return rb;
+    }
+    return 8;
+}
+
+cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &o, Layout &L)
+{
+    if (!descs || n < 1) return CF_ERR_INVALID_ARG;
+    for (int32_t t = 0; t < n; ++t) {
+        cf_status st = check_desc(descs[t]);
+        if (st != CF_OK) return st;
+    }
+    const int rb = pick_rb_rows(descs, n, o);
+    L.dev.resize(n);
+    L.tile_prefix.assign(n + 1, 0);
+    L.fin_prefix.assign(n + 1, 0);
+    uint64_t tiles = 0, fins = 0;
+    size_t partial_bytes = 0;
+    for (int32_t t = 0; t < n; ++t) {
+        const cf_tensor_desc &d = descs[t];
+        TensorDev &v = L.dev[t];
+        std::memset(&v, 0, sizeof v);
+        v.n_tokens = d.n_tokens;
+        v.n_channels = (int32_t)d.n_channels;
+        v.n_chunks = (int32_t)(d.n_channels / kChunk);
+        v.dtype = d.dtype;
+        v.bits = d.bits;
+        v.scale = d.scale;
+        v.rb_rows = rb;
+        v.n_rowblocks = (int32_t)((d.n_tokens + rb - 1) / rb);
+        v.n_colblocks = (v.n_chunks + kTileThreads - 1) / kTileThreads;
+        v.tile_begin = (uint32_t)tiles;
+        v.fin_begin = (uint32_t)fins;
+        L.tile_prefix[t] = (uint32_t)tiles;
+        L.fin_prefix[t] = (uint32_t)fins;
+        tiles += (uint64_t)v.n_rowblocks * (uint64_t)v.n_colblocks;
+        fins += (uint64_t)((d.n_channels + kFinalizeThreads - 1) / kFinalizeThreads);
+        if (tiles > 0x7fffffffull || fins > 0x7fffffffull) return CF_ERR_SHAPE;
+        if (d.scale == CF_SCALE_CHANNEL) {
+            L.any_channel = true;
+            v.partial_off = partial_bytes;   // relative; rebased below
+            partial_bytes += align_up((size_t)v.n_rowblocks * (size_t)d.n_channels * sizeof(float));
+        }
+    }
+    L.tile_prefix[n] = (uint32_t)tiles;
+    L.fin_prefix[n] = (uint32_t)fins;
+
+    size_t off = 0;
+    L.off_descs = off;        off = align_up(off + sizeof(TensorDev) * (size_t)n);
+    L.off_ptrs = off;         off = align_up(off + sizeof(TensorPtrs) * (size_t)n);
+    L.off_tile_prefix = off;  off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
+    L.off_fin_prefix = off;   off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
+    L.off_partials = off;     off = align_up(off + partial_bytes);
+    L.total = off;
+    for (int32_t t = 0; t < n; ++t)
+        if (descs[t].scale == CF_SCALE_CHANNEL) L.dev[t].partial_off += L.off_partials;
+    return CF_OK;
+}
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+struct cf_ctx {
+    std::vector<cf_tensor_desc> descs;
+    Layout L;
+    cf_options opts;
+    uint8_t *ws = nullptr;
+    size_t ws_bytes = 0;
+    std::vector<TensorPtrs> ptrs;      // what the workspace table currently holds
+    std::vector<uint8_t> warm;
+    int32_t last_hip = 0;
+    int device = 0;
+
+    BatchView view() const
+    {
+        BatchView v;
+        v.descs = reinterpret_cast<const TensorDev *>(ws + L.off_descs);
+        v.ptrs = reinterpret_cast<const TensorPtrs *>(ws + L.off_ptrs);
+        v.tile_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_tile_prefix);
+        v.fin_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_fin_prefix);
+        v.workspace = ws;
+        v.n_tensors = (int32_t)descs.size();
+        return v;
+    }
+
+    LaunchRange range(int32_t first, int32_t count) const
+    {
+        LaunchRange r;
+        r.first = first;
+        r.count = count;
+        r.tile_lo = L.tile_prefix[first];
+        r.tile_hi = L.tile_prefix[first + count];
+        r.fin_lo = L.fin_prefix[first];
+        r.fin_hi = L.fin_prefix[first + count];
+        return r;
+    }
+
+    bool range_has_channel(int32_t first, int32_t count) const
+    {
+        for (int32_t t = first; t < first + count; ++t)
+            if (descs[t].scale == CF_SCALE_CHANNEL) return true;
+        return false;
+    }
+};
+
+namespace {
+
+cf_status check_range(const cf_ctx *ctx, int32_t first, int32_t count)
+{
+    if (!ctx) return CF_ERR_INVALID_ARG;
+    if (first < 0 || count < 0 || (int64_t)first + count > (int64_t)ctx->descs.size()) return CF_ERR_INVALID_ARG;
+    return CF_OK;
+}
+
+cf_status check_warm(const cf_ctx *ctx, int32_t first, int32_t count)
+{
+    for (int32_t t = first; t < first + count; ++t)
+        if (!ctx->warm[t]) return CF_ERR_STATE;
+    return CF_OK;
+}
+
+// Validates one pointer array (host array of `count` device pointers).
+cf_status check_ptrs(const void *const *arr, int32_t count)
+{
+    if (!arr) return CF_ERR_INVALID_ARG;
+    for (int32_t k = 0; k < count; ++k)
+        if (!arr[k] || !aligned16(arr[k])) return CF_ERR_INVALID_ARG;
+    return CF_OK;
+}
+
+cf_status device_fail(cf_ctx *ctx, hipError_t e)
+{
+    ctx->last_hip = (int32_t)e;
+    return CF_ERR_DEVICE;
+}
+
+// Brings the workspace pointer table up to date for [first, first+count).
+// Arrays that an entry point does not take are passed as nullptr and keep
+// their last value.  Nothing is launched when no pointer changed.
+cf_status sync_ptrs(cf_ctx *ctx, int32_t first, int32_t count, const void *const *x, void *const *recon,
+                    void *const *err, void *const *codes, void *const *scales, hipStream_t s)
+{
+    bool changed = false;
+    for (int32_t k = 0; k < count; ++k) {
+        TensorPtrs &p = ctx->ptrs[first + k];
+        TensorPtrs q = p;
+        if (x) q.x = x[k];
+        if (recon) q.recon = recon[k];
+        if (err) q.err = err[k];
+        if (codes) q.codes = static_cast<uint8_t *>(codes[k]);
+        if (scales) q.scales = static_cast<float *>(scales[k]);
+        if (std::memcmp(&p, &q, sizeof p) != 0) {
+            p = q;
+            changed = true;
+        }
+    }
+    if (!changed) return CF_OK;
+    TensorPtrs *table = reinterpret_cast<TensorPtrs *>(ctx->ws + ctx->L.off_ptrs);
+    for (int32_t k0 = 0; k0 < count; k0 += kMaxUploadTensors) {
+        int n = count - k0 < kMaxUploadTensors ? count - k0 : kMaxUploadTensors;
+        PtrChunk chunk;
+        std::memset(&chunk, 0, sizeof chunk);
+        for (int k = 0; k < n; ++k) chunk.p[k] = ctx->ptrs[first + k0 + k];
+        hipError_t e = launch_upload_ptrs(chunk, table + first + k0, n, s);
+        if (e != hipSuccess) {
+            // the mirror no longer matches the device table: force a re-upload next time
+            for (int32_t k = 0; k < count; ++k) std::memset(&ctx->ptrs[first + k], 0xff, sizeof(TensorPtrs));
+            return device_fail(ctx, e);
+        }
+    }
+    return CF_OK;
+}
+
+cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *const *x, void *const *recon,
+                     void *const *err, void *const *codes, void *const *scales, void *stream, bool fused)
+{
+    cf_status st = check_range(ctx, first, count);
+    if (st != CF_OK) return st;
+    if (count == 0) return CF_OK;
+    if ((st = check_ptrs(x, count)) != CF_OK) return st;
+    if ((st = check_ptrs(recon, count)) != CF_OK) return st;
+    if ((st = check_ptrs(err, count)) != CF_OK) return st;
+    if ((st = check_ptrs(codes, count)) != CF_OK) return st;
+    if ((st = check_ptrs(reinterpret_cast<const void *const *>(scales), count)) != CF_OK) return st;
+    for (int32_t k = 0; k < count; ++k) {
+        const void *px = x[k], *pr = recon[k], *pe = err[k], *pc = codes[k], *ps = scales[k];
+        if (px == pr || px == pe || pr == pe) return CF_ERR_INVALID_ARG;
+        if (pc == px || pc == pr || pc == pe || ps == px || ps == pr || ps == pe || ps == pc) return CF_ERR_INVALID_ARG;
+    }
+    if ((st = check_warm(ctx, first, count)) != CF_OK) return st;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if ((st = sync_ptrs(ctx, first, count, x, recon, err, codes, scales, s)) != CF_OK) return st;
+    BatchView v = ctx->view();
+    LaunchRange r = ctx->range(first, count);
+    hipError_t e;
+    if (ctx->range_has_channel(first, count)) {
+        if ((e = launch_colreduce(v, r, ctx->opts.ef, ctx->opts.err_dtype, s)) != hipSuccess) return device_fail(ctx, e);
+        if ((e = launch_finalize(v, r, s)) != hipSuccess) return device_fail(ctx, e);
+    }
+    if ((e = launch_encode(v, r, ctx->opts.ef, ctx->opts.err_dtype, fused, s)) != hipSuccess) return device_fail(ctx, e);
+    return CF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *cf_status_string(cf_status s)
+{
+    switch (s) {
+    case CF_OK: return "ok";
+    case CF_ERR_INVALID_ARG: return "invalid argument";
+    case CF_ERR_SHAPE: return "unsupported shape";
+    case CF_ERR_UNSUPPORTED: return "unsupported configuration";
+    case CF_ERR_STATE: return "tensor not warmed up";
+    case CF_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case CF_ERR_DEVICE: return "HIP call failed";
+    }
+    return "unknown status";
+}
+
+cf_status cf_sizes(const cf_tensor_desc *desc, const cf_options *opts, size_t *codes_bytes, size_t *scales_bytes,
+                   size_t *recon_bytes, size_t *err_bytes)
+{
+    if (!desc) return CF_ERR_INVALID_ARG;
+    cf_options o;
+    cf_status st = check_opts(opts, o);
+    if (st != CF_OK) return st;
+    if ((st = check_desc(*desc)) != CF_OK) return st;
+    const size_t n = (size_t)desc->n_tokens, c = (size_t)desc->n_channels;
+    if (codes_bytes) *codes_bytes = n * (c * (size_t)desc->bits / 8);
+    if (scales_bytes) *scales_bytes = sizeof(float) * (desc->scale == CF_SCALE_GROUP ? n * (c / 128) : c);
+    if (recon_bytes) *recon_bytes = n * c * dtype_size(desc->dtype);
+    if (err_bytes) *err_bytes = n * c * dtype_size(o.err_dtype);
+    return CF_OK;
+}
+
+size_t cf_workspace_bytes(const cf_tensor_desc *descs, int32_t n_tensors, const cf_options *opts)
+{
+    cf_options o;
+    if (check_opts(opts, o) != CF_OK) return 0;
+    Layout L;
+    if (make_layout(descs, n_tensors, o, L) != CF_OK) return 0;
+    return L.total;
+}
+
+cf_status cf_init(cf_ctx **out, const cf_tensor_desc *descs, int32_t n_tensors, const cf_options *opts,
+                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!out) return CF_ERR_INVALID_ARG;
+    *out = nullptr;
+    cf_options o;
+    cf_status st = check_opts(opts, o);
+    if (st != CF_OK) return st;
+    cf_ctx *ctx = new (std::nothrow) cf_ctx;
+    if (!ctx) return CF_ERR_INVALID_ARG;
+    st = make_layout(descs, n_tensors, o, ctx->L);
+    if (st != CF_OK) { delete ctx; return st; }
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < ctx->L.total) {
+        delete ctx;
+        return CF_ERR_WORKSPACE;
+    }
+    ctx->descs.assign(descs, descs + n_tensors);
+    ctx->opts = o;
+    ctx->ws = static_cast<uint8_t *>(workspace);
+    ctx->ws_bytes = workspace_bytes;
+    ctx->ptrs.resize(n_tensors);
+    std::memset(ctx->ptrs.data(), 0, sizeof(TensorPtrs) * (size_t)n_tensors);
+    ctx->warm.assign(n_tensors, 0);
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipGetDevice(&ctx->device);
+    // The tables stay alive in the context (never modified), so the copies may complete late.
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(ctx->ws + ctx->L.off_descs, ctx->L.dev.data(), sizeof(TensorDev) * (size_t)n_tensors,
+                           hipMemcpyHostToDevice, s);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(ctx->ws + ctx->L.off_tile_prefix, ctx->L.tile_prefix.data(),
+                           sizeof(uint32_t) * (size_t)(n_tensors + 1), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(ctx->ws + ctx->L.off_fin_prefix, ctx->L.fin_prefix.data(),
+                           sizeof(uint32_t) * (size_t)(n_tensors + 1), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess)
+        e = hipMemsetAsync(ctx->ws + ctx->L.off_ptrs, 0, sizeof(TensorPtrs) * (size_t)n_tensors, s);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        delete ctx;
+        return CF_ERR_DEVICE;
+    }
+    *out = ctx;
+    return CF_OK;
+}
+
+void cf_destroy(cf_ctx *ctx) { delete ctx; }
+
+int32_t cf_last_hip_error(const cf_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+cf_status cf_set_warm(cf_ctx *ctx, int32_t first, int32_t count, int32_t warm)
+{
+    cf_status st = check_range(ctx, first, count);
+    if (st != CF_OK) return st;
+    for (int32_t t = first; t < first + count; ++t) ctx->warm[t] = warm ? 1 : 0;
+    return CF_OK;
+}
+
+cf_status cf_warmup(cf_ctx *ctx, int32_t first, int32_t count, const void *const *x0, void *const *recon,
+                    void *const *err, void *stream)
+{
+    cf_status st = check_range(ctx, first, count);
+    if (st != CF_OK) return st;
+    if (count == 0) return CF_OK;
+    if ((st = check_ptrs(x0, count)) != CF_OK) return st;
+    if ((st = check_ptrs(recon, count)) != CF_OK) return st;
+    if ((st = check_ptrs(err, count)) != CF_OK) return st;
+    for (int32_t k = 0; k < count; ++k)
+        if (x0[k] == recon[k] || x0[k] == err[k] || recon[k] == err[k]) return CF_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if ((st = sync_ptrs(ctx, first, count, x0, recon, err, nullptr, nullptr, s)) != CF_OK) return st;
+    hipError_t e = launch_warmup(ctx->view(), ctx->range(first, count), ctx->opts.err_dtype, s);
+    if (e != hipSuccess) return device_fail(ctx, e);
+    for (int32_t t = first; t < first + count; ++t) ctx->warm[t] = 1;
+    return CF_OK;
+}
+
+cf_status cf_compress(cf_ctx *ctx, int32_t first, int32_t count, const void *const *x, const void *const *recon,
+                      void *const *err, void *const *codes, void *const *scales, void *stream)
+{
+    return run_sender(ctx, first, count, x, const_cast<void *const *>(reinterpret_cast<const void *const *>(recon)), err,
+                      codes, scales, stream, false);
+}
+
+cf_status cf_step_fused(cf_ctx *ctx, int32_t first, int32_t count, const void *const *x, void *const *recon,
+                        void *const *err, void *const *codes, void *const *scales, void *stream)
+{
+    return run_sender(ctx, first, count, x, recon, err, codes, scales, stream, true);
+}
+
+cf_status cf_decompress(cf_ctx *ctx, int32_t first, int32_t count, const void *const *codes,
+                        const void *const *scales, void *const *recon, void *stream)
+{
+    cf_status st = check_range(ctx, first, count);
+    if (st != CF_OK) return st;
+    if (count == 0) return CF_OK;
+    if ((st = check_ptrs(codes, count)) != CF_OK) return st;
+    if ((st = check_ptrs(scales, count)) != CF_OK) return st;
+    if ((st = check_ptrs(recon, count)) != CF_OK) return st;
+    for (int32_t k = 0; k < count; ++k)
+        if (codes[k] == scales[k] || codes[k] == recon[k] || scales[k] == recon[k]) return CF_ERR_INVALID_ARG;
+    if ((st = check_warm(ctx, first, count)) != CF_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = sync_ptrs(ctx, first, count, nullptr, recon, nullptr, const_cast<void *const *>(codes),
+                   const_cast<void *const *>(scales), s);
+    if (st != CF_OK) return st;
+    hipError_t e = launch_decode(ctx->view(), ctx->range(first, count), s);
+    if (e != hipSuccess) return device_fail(ctx, e);
+    return CF_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,73 @@
+// Internal interface between the C-ABI layer (cf_api.cpp) and the gfx950
+// kernels (cf_kernels.hip).  Not installed; not part of the ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cf {
+
+// Every tile of the tiled kernels is TILE_ROWS(rb) x TILE_CHANNELS: 128 lanes
+// each own 8 consecutive channels (one 128-bit load of bf16).
+constexpr int kTileThreads = 128;
+constexpr int kChunk = 8;                                   // channels per lane
+constexpr int kTileChannels = kTileThreads * kChunk;        // 1024
+constexpr int kFinalizeThreads = 256;                       // columns per finalise block
+constexpr int kMaxUploadTensors = 64;                       // pointer sets per upload launch
+
+// Static description of one tensor; built at cf_init, lives in the workspace.
+struct alignas(16) TensorDev {
+    int64_t n_tokens;
+    int32_t n_channels;
+    int32_t n_chunks;       // C / 8
+    int32_t dtype;          // cf_dtype
+    int32_t bits;           // 1 | 2 | 4
+    int32_t scale;          // cf_scale_kind
+    int32_t rb_rows;        // rows per tile (power of two, multiple of 8)
+    int32_t n_rowblocks;    // ceil(N / rb_rows)
+    int32_t n_colblocks;    // ceil(n_chunks / 128)
+    uint32_t tile_begin;    // id of this tensor's first tile in the batched grids
+    uint32_t fin_begin;     // id of its first finalise block
+    uint64_t partial_off;   // byte offset in the workspace of partial[n_rowblocks][C] (channel scales)
+    uint64_t pad_;
+};
+
+// Per-call device pointers of one tensor; uploaded into the workspace.
+struct TensorPtrs {
+    const void *x;
+    void *recon;
+    void *err;
+    uint8_t *codes;
+    float *scales;
+};
+
+struct PtrChunk {
+    TensorPtrs p[kMaxUploadTensors];
+};
+
+// Device view of a context's workspace.
+struct BatchView {
+    const TensorDev *descs;     // [n_tensors]
+    const TensorPtrs *ptrs;     // [n_tensors]
+    const uint32_t *tile_prefix;    // [n_tensors + 1]
+    const uint32_t *fin_prefix;     // [n_tensors + 1]
+    uint8_t *workspace;
+    int32_t n_tensors;
+};
+
+struct LaunchRange {
+    int32_t first, count;       // tensors
+    uint32_t tile_lo, tile_hi;  // tiles of [first, first+count)
+    uint32_t fin_lo, fin_hi;    // finalise blocks
+};
+
+enum class Op { Compress, StepFused };
+
+hipError_t launch_upload_ptrs(const PtrChunk &chunk, TensorPtrs *dst, int n, hipStream_t s);
+hipError_t launch_warmup(const BatchView &v, const LaunchRange &r, int err_dtype, hipStream_t s);
+hipError_t launch_colreduce(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, hipStream_t s);
+hipError_t launch_finalize(const BatchView &v, const LaunchRange &r, hipStream_t s);
+hipError_t launch_encode(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, bool fused, hipStream_t s);
+hipError_t launch_decode(const BatchView &v, const LaunchRange &r, hipStream_t s);
+
+}  // namespace cf

@@ -1,0 +1,641 @@
+// gfx950 kernels of the residual codec (arxiv 2507.17511: Sec. 3.1, Sec. 3.2,
+// App. D "Quantization", App. H).  Everything here is bandwidth-bound
+// element-wise or reduction work: 128-bit loads, fp32 arithmetic in registers
+// with one rounding per operation (the file is compiled with
+// -ffp-contract=off), integer code packing, in-place state updates.  No MFMA:
+// nothing is a dense contraction.
+//
+// Tiled kernels: one workgroup of 128 lanes per tile of rb_rows x 1024
+// channels; lane l owns channels [8l, 8l+8) of the tile (one 128-bit bf16
+// load per row), so a wave reads 1 KiB of contiguous row per instruction.
+// A batched grid covers the tiles of many tensors; a workgroup finds its
+// tensor by binary search in a prefix array of tile counts.
+#include "cf_internal.h"
+
+namespace cf {
+namespace {
+
+constexpr int F32 = 0, BF16 = 1;
+constexpr int SCALE_CHANNEL = 0, SCALE_GROUP = 1;
+constexpr int EF_RECON = 0, EF_LITERAL = 1, EF_OFF = 2;
+
+// ---------------------------------------------------------------- element formats
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// fp32 -> bf16, round to nearest, ties to even, on the 16 dropped bits.
+__device__ __forceinline__ uint32_t bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+struct F8 {
+    float v[8];
+};
+
+// Raw 8-element vectors as they sit in memory.
+template <int DT> struct Raw8;
+template <> struct Raw8<BF16> {
+    uint4 w;
+    __device__ __forceinline__ void zero() { w = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ void load(const void *base, int64_t elem) { w = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + elem); }
+    __device__ __forceinline__ void store(void *base, int64_t elem) const { *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(base) + elem) = w; }
+    __device__ __forceinline__ F8 widen() const
+    {
+        F8 f;
+        f.v[0] = bf16_lo(w.x); f.v[1] = bf16_hi(w.x);
+        f.v[2] = bf16_lo(w.y); f.v[3] = bf16_hi(w.y);
+        f.v[4] = bf16_lo(w.z); f.v[5] = bf16_hi(w.z);
+        f.v[6] = bf16_lo(w.w); f.v[7] = bf16_hi(w.w);
+        return f;
+    }
+    __device__ __forceinline__ void narrow(const F8 &f)
+    {
+        w.x = bf16_rne(f.v[0]) | (bf16_rne(f.v[1]) << 16);
+        w.y = bf16_rne(f.v[2]) | (bf16_rne(f.v[3]) << 16);
+        w.z = bf16_rne(f.v[4]) | (bf16_rne(f.v[5]) << 16);
+        w.w = bf16_rne(f.v[6]) | (bf16_rne(f.v[7]) << 16);
+    }
+};
+template <> struct Raw8<F32> {
+    float4 a, b;
+    __device__ __forceinline__ void zero() { a = make_float4(0, 0, 0, 0); b = a; }
+    __device__ __forceinline__ void load(const void *base, int64_t elem)
+    {
+        const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(base) + elem);
+        a = p[0];
+        b = p[1];
+    }
+    __device__ __forceinline__ void store(void *base, int64_t elem) const
+    {
+        float4 *p = reinterpret_cast<float4 *>(static_cast<float *>(base) + elem);
+        p[0] = a;
+        p[1] = b;
+    }
+    __device__ __forceinline__ F8 widen() const
+    {
+        F8 f;
+        f.v[0] = a.x; f.v[1] = a.y; f.v[2] = a.z; f.v[3] = a.w;
+        f.v[4] = b.x; f.v[5] = b.y; f.v[6] = b.z; f.v[7] = b.w;
+        return f;
+    }
+    __device__ __forceinline__ void narrow(const F8 &f)
+    {
+        a = make_float4(f.v[0], f.v[1], f.v[2], f.v[3]);
+        b = make_float4(f.v[4], f.v[5], f.v[6], f.v[7]);
+    }
+};
+
+// ---------------------------------------------------------------- a1 + a2
+
+// z from the raw operands; the order of the two fp32 operations is fixed.
+template <int EF>
+__device__ __forceinline__ F8 residual8(const F8 &x, const F8 &b, const F8 &e)
+{
+    F8 z;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        float r = x.v[k] - b.v[k];
+        if (EF == EF_LITERAL) r = r + e.v[k];
+        if (EF == EF_OFF) r = r - e.v[k];
+        z.v[k] = r;
+    }
+    return z;
+}
+
+// ---------------------------------------------------------------- a4 + a5 + a6
+
+// Codes of 8 consecutive channels, packed least significant first, and their
+// decoded values.  BITS == 4 divides (IEEE) and rounds half to even.
+template <int BITS>
+__device__ __forceinline__ uint32_t quant8(const F8 &z, const F8 &s, F8 &d)
+{
+    uint32_t packed = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        float v = z.v[k], sc = s.v[k];
+        if (BITS == 1) {
+            bool neg = v < 0.0f;
+            packed |= (neg ? 1u : 0u) << k;
+            d.v[k] = neg ? -sc : sc;
+        } else if (BITS == 2) {
+            bool neg = v < 0.0f;
+            bool big = fabsf(v) > 1.25f * sc;
+            packed |= ((neg ? 2u : 0u) | (big ? 1u : 0u)) << (2 * k);
+            float m = big ? 2.0f * sc : 0.5f * sc;
+            d.v[k] = neg ? -m : m;
+        } else {
+            float t = v / sc;
+            float r = rintf(t);
+            r = fminf(fmaxf(r, -7.0f), 7.0f);
+            int q = (sc != 0.0f) ? (int)r : 0;
+            packed |= ((uint32_t)q & 0xFu) << (4 * k);
+            d.v[k] = (float)q * sc;
+        }
+    }
+    return packed;
+}
+
+template <int BITS>
+__device__ __forceinline__ void dequant8(uint32_t packed, const F8 &s, F8 &d)
+{
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        float sc = s.v[k];
+        if (BITS == 1) {
+            d.v[k] = ((packed >> k) & 1u) ? -sc : sc;
+        } else if (BITS == 2) {
+            uint32_t c = (packed >> (2 * k)) & 3u;
+            float m = (c & 1u) ? 2.0f * sc : 0.5f * sc;
+            d.v[k] = (c & 2u) ? -m : m;
+        } else {
+            int q = ((int)(packed << (28 - 4 * k))) >> 28;      // sign-extended nibble
+            d.v[k] = (float)q * sc;
+        }
+    }
+}
+
+template <int BITS> __device__ __forceinline__ void store_codes(uint8_t *row, int chunk, uint32_t packed)
+{
+    if (BITS == 1) row[chunk] = (uint8_t)packed;
+    else if (BITS == 2) reinterpret_cast<uint16_t *>(row)[chunk] = (uint16_t)packed;
+    else reinterpret_cast<uint32_t *>(row)[chunk] = packed;
+}
+
+template <int BITS> __device__ __forceinline__ uint32_t load_codes(const uint8_t *row, int chunk)
+{
+    if (BITS == 1) return row[chunk];
+    if (BITS == 2) return reinterpret_cast<const uint16_t *>(row)[chunk];
+    return reinterpret_cast<const uint32_t *>(row)[chunk];
+}
+
+// Max over the 16 lanes of a DPP row (16 lanes x 8 channels = one group of 128).
+// All 64 lanes must be active.
+__device__ __forceinline__ float row16_max(float m)
+{
+    int v;
+    v = __builtin_amdgcn_update_dpp(0, __float_as_int(m), 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+    m = fmaxf(m, __int_as_float(v));
+    v = __builtin_amdgcn_update_dpp(0, __float_as_int(m), 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+    m = fmaxf(m, __int_as_float(v));
+    v = __builtin_amdgcn_update_dpp(0, __float_as_int(m), 0x141, 0xF, 0xF, false);  // row_half_mirror
+    m = fmaxf(m, __int_as_float(v));
+    v = __builtin_amdgcn_update_dpp(0, __float_as_int(m), 0x140, 0xF, 0xF, false);  // row_mirror
+    m = fmaxf(m, __int_as_float(v));
+    return m;
+}
+
+// ---------------------------------------------------------------- tile lookup
+
+struct TileCtx {
+    const TensorDev *d;
+    const TensorPtrs *p;
+    int rowblock, colblock;
+};
+
+// Largest t in [lo, hi) with prefix[t] <= id.
+__device__ __forceinline__ int find_slot(const uint32_t *prefix, int lo, int hi, uint32_t id)
+{
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (prefix[mid] <= id) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ TileCtx locate_tile(const BatchView &v, const LaunchRange &r)
+{
+    uint32_t tile = r.tile_lo + blockIdx.x;
+    int t = find_slot(v.tile_prefix, r.first, r.first + r.count, tile);
+    TileCtx c;
+    c.d = v.descs + t;
+    c.p = v.ptrs + t;
+    uint32_t local = tile - c.d->tile_begin;
+    c.colblock = (int)(local % (uint32_t)c.d->n_colblocks);
+    c.rowblock = (int)(local / (uint32_t)c.d->n_colblocks);
+    return c;
+}
+
+// ---------------------------------------------------------------- a0 warm-up
+
+template <int DT, int ET>
+__device__ __forceinline__ void warmup_tile(const TileCtx &c)
+{
+    const TensorDev &d = *c.d;
+    int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
+    if (chunk >= d.n_chunks) return;
+    int64_t row0 = (int64_t)c.rowblock * d.rb_rows;
+    int64_t row1 = row0 + d.rb_rows < d.n_tokens ? row0 + d.rb_rows : d.n_tokens;
+    for (int64_t i = row0; i < row1; ++i) {
+        int64_t e = i * d.n_channels + (int64_t)chunk * kChunk;
+        Raw8<DT> x;
+        x.load(c.p->x, e);
+        x.store(c.p->recon, e);
+        Raw8<ET> zero;
+        zero.zero();
+        zero.store(c.p->err, e);
+    }
+}
+
+template <int ET>
+__global__ __launch_bounds__(kTileThreads) void k_warmup(BatchView v, LaunchRange r)
+{
+    TileCtx c = locate_tile(v, r);
+    if (c.d->dtype == BF16) warmup_tile<BF16, ET>(c); else warmup_tile<F32, ET>(c);
+}
+
+// ---------------------------------------------------------------- a3, first level: per-tile column partials
+
+template <bool IS_MAX> __device__ __forceinline__ float comb(float a, float b) { return IS_MAX ? fmaxf(a, b) : a + b; }
+
+// |z| of 8 consecutive rows, combined as a balanced tree:
+// ((r0+r1)+(r2+r3)) + ((r4+r5)+(r6+r7)).  Rows past the end count as +0, which
+// is exactly the zero padding of the tree.
+template <int DT, int EF, int ET, bool IS_MAX>
+__device__ __forceinline__ F8 rows8(const TensorDev &d, const TensorPtrs &p, int chunk, int64_t row)
+{
+    Raw8<DT> xr[8], br[8];
+    Raw8<ET> er[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        int64_t i = row + r;
+        if (i < d.n_tokens) {
+            int64_t e = i * d.n_channels + (int64_t)chunk * kChunk;
+            xr[r].load(p.x, e);
+            br[r].load(p.recon, e);
+            if (EF != EF_RECON) er[r].load(p.err, e); else er[r].zero();
+        } else {
+            xr[r].zero();
+            br[r].zero();
+            er[r].zero();
+        }
+    }
+    F8 a[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        F8 z = residual8<EF>(xr[r].widen(), br[r].widen(), er[r].widen());
+#pragma unroll
+        for (int k = 0; k < 8; ++k) a[r].v[k] = fabsf(z.v[k]);
+    }
+    F8 t;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        float s01 = comb<IS_MAX>(a[0].v[k], a[1].v[k]), s23 = comb<IS_MAX>(a[2].v[k], a[3].v[k]);
+        float s45 = comb<IS_MAX>(a[4].v[k], a[5].v[k]), s67 = comb<IS_MAX>(a[6].v[k], a[7].v[k]);
+        float s03 = comb<IS_MAX>(s01, s23), s47 = comb<IS_MAX>(s45, s67);
+        t.v[k] = comb<IS_MAX>(s03, s47);
+    }
+    return t;
+}
+
+template <int DT, int EF, int ET, bool IS_MAX>
+__device__ __forceinline__ void colreduce_tile(const TileCtx &c, uint8_t *ws)
+{
+    const TensorDev &d = *c.d;
+    int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
+    if (chunk >= d.n_chunks) return;
+    int64_t row = (int64_t)c.rowblock * d.rb_rows;
+    // Balanced tree over the tile's rb_rows = 8 * nb rows (nb in {1,2,4,8}) as three
+    // nested two-way loops: level k combines two results of level k-1.  The loops
+    // stay rolled so that only one batch of 16 row loads is in flight per lane.
+    const int nb = d.rb_rows >> 3;
+    const int n0 = nb >= 2 ? 2 : 1, n1 = nb >= 4 ? 2 : 1, n2 = nb >= 8 ? 2 : 1;
+    F8 s0, s1, s2;
+#pragma unroll 1
+    for (int h2 = 0; h2 < n2; ++h2) {
+#pragma unroll 1
+        for (int h1 = 0; h1 < n1; ++h1) {
+#pragma unroll 1
+            for (int h0 = 0; h0 < n0; ++h0) {
+                F8 t = rows8<DT, EF, ET, IS_MAX>(d, *c.p, chunk, row);
+                row += 8;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) s0.v[k] = (h0 == 0) ? t.v[k] : comb<IS_MAX>(s0.v[k], t.v[k]);
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) s1.v[k] = (h1 == 0) ? s0.v[k] : comb<IS_MAX>(s1.v[k], s0.v[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s2.v[k] = (h2 == 0) ? s1.v[k] : comb<IS_MAX>(s2.v[k], s1.v[k]);
+    }
+    float *partial = reinterpret_cast<float *>(ws + d.partial_off) + (int64_t)c.rowblock * d.n_channels + (int64_t)chunk * kChunk;
+    Raw8<F32> out;
+    out.narrow(s2);
+    out.store(partial, 0);
+}
+
+template <int EF, int ET>
+__global__ __launch_bounds__(kTileThreads) void k_colreduce(BatchView v, LaunchRange r)
+{
+    TileCtx c = locate_tile(v, r);
+    const TensorDev &d = *c.d;
+    if (d.scale != SCALE_CHANNEL) return;
+    if (d.dtype == BF16) {
+        if (d.bits == 4) colreduce_tile<BF16, EF, ET, true>(c, v.workspace);
+        else colreduce_tile<BF16, EF, ET, false>(c, v.workspace);
+    } else {
+        if (d.bits == 4) colreduce_tile<F32, EF, ET, true>(c, v.workspace);
+        else colreduce_tile<F32, EF, ET, false>(c, v.workspace);
+    }
+}
+
+// ---------------------------------------------------------------- a3, second level: tree over tile partials
+
+// One lane per column: continues the same binary tree over the n_rowblocks
+// partials (zero padded to a power of two), then s = sum / N or max / 7.
+__global__ __launch_bounds__(kFinalizeThreads) void k_finalize(BatchView v, LaunchRange r)
+{
+    uint32_t blk = r.fin_lo + blockIdx.x;
+    int t = find_slot(v.fin_prefix, r.first, r.first + r.count, blk);
+    const TensorDev &d = v.descs[t];
+    if (d.scale != SCALE_CHANNEL) return;
+    int col = (int)(blk - d.fin_begin) * kFinalizeThreads + (int)threadIdx.x;
+    if (col >= d.n_channels) return;
+    const float *partial = reinterpret_cast<const float *>(v.workspace + d.partial_off) + col;
+    const bool is_max = d.bits == 4;
+    constexpr int LV = 26;
+    float stack[LV];
+#pragma unroll
+    for (int l = 0; l < LV; ++l) stack[l] = 0.0f;
+    int n = d.n_rowblocks, npad = 1, lg = 0;
+    while (npad < n) { npad <<= 1; ++lg; }
+    for (int i = 0; i < npad; ++i) {
+        float val = (i < n) ? partial[(int64_t)i * d.n_channels] : 0.0f;
+        bool carry = true;
+#pragma unroll
+        for (int l = 0; l < LV; ++l) {
+            if (carry) {
+                if ((i >> l) & 1) {
+                    val = is_max ? fmaxf(stack[l], val) : stack[l] + val;
+                } else {
+                    stack[l] = val;
+                    carry = false;
+                }
+            }
+        }
+    }
+    float res = stack[0];
+#pragma unroll
+    for (int l = 1; l < LV; ++l)
+        if (l == lg) res = stack[l];
+    float s = is_max ? res / 7.0f : res / (float)d.n_tokens;
+    v.ptrs[t].scales[col] = s;
+}
+
+// ---------------------------------------------------------------- a4-a8: encode (+ fused state update)
+
+template <int ET> __device__ __forceinline__ void store_err(void *err, int64_t e, const F8 &val)
+{
+    Raw8<ET> out;
+    out.narrow(val);
+    out.store(err, e);
+}
+
+// MODE: 0 = channel scales read from memory, 1 = group scales computed in the wave.
+template <int DT, int BITS, int MODE, int EF, int ET, bool FUSED>
+__device__ __forceinline__ void encode_tile(const TileCtx &c)
+{
+    const TensorDev &d = *c.d;
+    int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
+    const bool cvalid = chunk < d.n_chunks;
+    if (MODE == 0 && !cvalid) return;           // group mode keeps every lane alive for the DPP reduction
+    int64_t row0 = (int64_t)c.rowblock * d.rb_rows;
+    int64_t row1 = row0 + d.rb_rows < d.n_tokens ? row0 + d.rb_rows : d.n_tokens;
+    const int64_t row_bytes = (int64_t)d.n_channels * BITS / 8;
+    const int n_groups = d.n_channels >> 7;
+
+    F8 s;
+    if (MODE == 0) {
+        Raw8<F32> sr;
+        sr.load(c.p->scales, (int64_t)chunk * kChunk);
+        s = sr.widen();
+    }
+
+    constexpr int U = 4;
+    for (int64_t i0 = row0; i0 < row1; i0 += U) {
+        Raw8<DT> xr[U], br[U];
+        Raw8<ET> er[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int64_t i = i0 + u;
+            if (i < row1 && cvalid) {
+                int64_t e = i * d.n_channels + (int64_t)chunk * kChunk;
+                xr[u].load(c.p->x, e);
+                br[u].load(c.p->recon, e);
+                if (EF != EF_RECON) er[u].load(c.p->err, e); else er[u].zero();
+            } else {
+                xr[u].zero();
+                br[u].zero();
+                er[u].zero();
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int64_t i = i0 + u;
+            if (i >= row1) break;               // uniform over the workgroup
+            F8 b = br[u].widen();
+            F8 eold = er[u].widen();
+            F8 z = residual8<EF>(xr[u].widen(), b, eold);
+            if (MODE == 1) {
+                float m = 0.0f;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) m = fmaxf(m, fabsf(z.v[k]));
+                m = row16_max(m);
+                float sg = m / 7.0f;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) s.v[k] = sg;
+                if (cvalid && (threadIdx.x & 15) == 0) c.p->scales[i * n_groups + (chunk >> 4)] = sg;
+            }
+            if (!cvalid) continue;
+            F8 dq;
+            uint32_t packed = quant8<BITS>(z, s, dq);
+            store_codes<BITS>(c.p->codes + i * row_bytes, chunk, packed);
+            int64_t e = i * d.n_channels + (int64_t)chunk * kChunk;
+            F8 enew;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                float lost = z.v[k] - dq.v[k];
+                if (EF == EF_OFF) lost = eold.v[k] + lost;
+                enew.v[k] = lost;
+            }
+            store_err<ET>(c.p->err, e, enew);
+            if (FUSED) {
+                F8 nb;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) nb.v[k] = b.v[k] + dq.v[k];
+                Raw8<DT> out;
+                out.narrow(nb);
+                out.store(c.p->recon, e);
+            }
+        }
+    }
+}
+
+template <int DT, int EF, int ET, bool FUSED>
+__device__ __forceinline__ void encode_dispatch(const TileCtx &c)
+{
+    const TensorDev &d = *c.d;
+    if (d.scale == SCALE_GROUP) { encode_tile<DT, 4, 1, EF, ET, FUSED>(c); return; }
+    if (d.bits == 1) encode_tile<DT, 1, 0, EF, ET, FUSED>(c);
+    else if (d.bits == 2) encode_tile<DT, 2, 0, EF, ET, FUSED>(c);
+    else encode_tile<DT, 4, 0, EF, ET, FUSED>(c);
+}
+
+template <int EF, int ET, bool FUSED>
+__global__ __launch_bounds__(kTileThreads) void k_encode(BatchView v, LaunchRange r)
+{
+    TileCtx c = locate_tile(v, r);
+    if (c.d->dtype == BF16) encode_dispatch<BF16, EF, ET, FUSED>(c);
+    else encode_dispatch<F32, EF, ET, FUSED>(c);
+}
+
+// ---------------------------------------------------------------- a6 + a8: receiver decode
+
+template <int DT, int BITS, int MODE>
+__device__ __forceinline__ void decode_tile(const TileCtx &c)
+{
+    const TensorDev &d = *c.d;
+    int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
+    if (chunk >= d.n_chunks) return;
+    int64_t row0 = (int64_t)c.rowblock * d.rb_rows;
+    int64_t row1 = row0 + d.rb_rows < d.n_tokens ? row0 + d.rb_rows : d.n_tokens;
+    const int64_t row_bytes = (int64_t)d.n_channels * BITS / 8;
+    const int n_groups = d.n_channels >> 7;
+    F8 s;
+    if (MODE == 0) {
+        Raw8<F32> sr;
+        sr.load(c.p->scales, (int64_t)chunk * kChunk);
+        s = sr.widen();
+    }
+    constexpr int U = 4;
+    for (int64_t i0 = row0; i0 < row1; i0 += U) {
+        Raw8<DT> br[U];
+        uint32_t pk[U];
+        float sg[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int64_t i = i0 + u;
+            if (i < row1) {
+                br[u].load(c.p->recon, i * d.n_channels + (int64_t)chunk * kChunk);
+                pk[u] = load_codes<BITS>(c.p->codes + i * row_bytes, chunk);
+                sg[u] = (MODE == 1) ? c.p->scales[i * n_groups + (chunk >> 4)] : 0.0f;
+            } else {
+                br[u].zero();
+                pk[u] = 0;
+                sg[u] = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int64_t i = i0 + u;
+            if (i >= row1) break;
+            if (MODE == 1) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) s.v[k] = sg[u];
+            }
+            F8 dq, b = br[u].widen(), nb;
+            dequant8<BITS>(pk[u], s, dq);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) nb.v[k] = b.v[k] + dq.v[k];
+            Raw8<DT> out;
+            out.narrow(nb);
+            out.store(c.p->recon, i * d.n_channels + (int64_t)chunk * kChunk);
+        }
+    }
+}
+
+template <int DT> __device__ __forceinline__ void decode_dispatch(const TileCtx &c)
+{
+    const TensorDev &d = *c.d;
+    if (d.scale == SCALE_GROUP) { decode_tile<DT, 4, 1>(c); return; }
+    if (d.bits == 1) decode_tile<DT, 1, 0>(c);
+    else if (d.bits == 2) decode_tile<DT, 2, 0>(c);
+    else decode_tile<DT, 4, 0>(c);
+}
+
+__global__ __launch_bounds__(kTileThreads) void k_decode(BatchView v, LaunchRange r)
+{
+    TileCtx c = locate_tile(v, r);
+    if (c.d->dtype == BF16) decode_dispatch<BF16>(c); else decode_dispatch<F32>(c);
+}
+
+// ---------------------------------------------------------------- pointer table upload
+
+// The per-call device pointers travel in the kernel arguments (captured at
+// launch, so the host arrays may be reused at once) and are written to the
+// workspace table by one small block.
+__global__ void k_upload_ptrs(PtrChunk chunk, TensorPtrs *dst, int n)
+{
+    int i = (int)threadIdx.x;
+    if (i < n) dst[i] = chunk.p[i];
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------- host-side launchers
+
+hipError_t launch_upload_ptrs(const PtrChunk &chunk, TensorPtrs *dst, int n, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_upload_ptrs, dim3(1), dim3(kMaxUploadTensors), 0, s, chunk, dst, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_warmup(const BatchView &v, const LaunchRange &r, int err_dtype, hipStream_t s)
+{
+    dim3 grid(r.tile_hi - r.tile_lo), block(kTileThreads);
+    if (grid.x == 0) return hipSuccess;
+    if (err_dtype == BF16) hipLaunchKernelGGL(k_warmup<BF16>, grid, block, 0, s, v, r);
+    else hipLaunchKernelGGL(k_warmup<F32>, grid, block, 0, s, v, r);
+    return hipGetLastError();
+}
+
+#define CF_DISPATCH_EF_ET(KERNEL, ...)                                                                  \
+    do {                                                                                                \
+        if (err_dtype == BF16) {                                                                        \
+            if (ef == EF_RECON) hipLaunchKernelGGL((KERNEL<EF_RECON, BF16 __VA_ARGS__>), grid, block, 0, s, v, r);      \
+            else if (ef == EF_LITERAL) hipLaunchKernelGGL((KERNEL<EF_LITERAL, BF16 __VA_ARGS__>), grid, block, 0, s, v, r); \
+            else hipLaunchKernelGGL((KERNEL<EF_OFF, BF16 __VA_ARGS__>), grid, block, 0, s, v, r);       \
+        } else {                                                                                        \
+            if (ef == EF_RECON) hipLaunchKernelGGL((KERNEL<EF_RECON, F32 __VA_ARGS__>), grid, block, 0, s, v, r);       \
+            else if (ef == EF_LITERAL) hipLaunchKernelGGL((KERNEL<EF_LITERAL, F32 __VA_ARGS__>), grid, block, 0, s, v, r);  \
+            else hipLaunchKernelGGL((KERNEL<EF_OFF, F32 __VA_ARGS__>), grid, block, 0, s, v, r);        \
+        }                                                                                               \
+    } while (0)
+
+hipError_t launch_colreduce(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, hipStream_t s)
+{
+    dim3 grid(r.tile_hi - r.tile_lo), block(kTileThreads);
+    if (grid.x == 0) return hipSuccess;
+    CF_DISPATCH_EF_ET(k_colreduce);
+    return hipGetLastError();
+}
+
+hipError_t launch_finalize(const BatchView &v, const LaunchRange &r, hipStream_t s)
+{
+    dim3 grid(r.fin_hi - r.fin_lo), block(kFinalizeThreads);
+    if (grid.x == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_finalize, grid, block, 0, s, v, r);
+    return hipGetLastError();
+}
+
+hipError_t launch_encode(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, bool fused, hipStream_t s)
+{
+    dim3 grid(r.tile_hi - r.tile_lo), block(kTileThreads);
+    if (grid.x == 0) return hipSuccess;
+    if (fused) CF_DISPATCH_EF_ET(k_encode, , true);
+    else CF_DISPATCH_EF_ET(k_encode, , false);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode(const BatchView &v, const LaunchRange &r, hipStream_t s)
+{
+    dim3 grid(r.tile_hi - r.tile_lo), block(kTileThreads);
+    if (grid.x == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_decode, grid, block, 0, s, v, r);
+    return hipGetLastError();
+}
+
+}  // namespace cf

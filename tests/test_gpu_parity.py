@@ -1,0 +1,303 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through
+the C ABI, on seeded inputs small enough for the oracle but spanning several
+tiles, ragged tails, every code width, scale kind, error-feedback mode and
+storage dtype.  Bars are stated in tests/helpers.py."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2507_17511_amd as cf
+from helpers import (OracleState, assert_same, compare_tensor, drift_stream, kind_of, oracle_config, run_parity)
+from paper_2507_17511_amd.session import CodecSession
+from workloads import CONFIGS, ActivationStream, as_numpy, cfg1_numpy
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+CH, GR = cf.CF_SCALE_CHANNEL, cf.CF_SCALE_GROUP
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+# (N, C): several row tiles with a ragged last one; C spans one full 1024-channel
+# column tile plus a partial one (1096 = 137 chunks), a single chunk, and 3072.
+SHAPES = [(203, 1096), (67, 3072), (9, 8), (1, 128), (130, 2176)]
+COMBOS = [(1, CH), (2, CH), (4, CH), (4, GR)]
+
+
+@pytest.mark.parametrize("bits,scale", COMBOS)
+@pytest.mark.parametrize("dtype", [cf.CF_BF16, cf.CF_F32])
+@pytest.mark.parametrize("mode", ["fused", "split"])
+def test_parity_shapes(bits, scale, dtype, mode):
+    for k, (n, c) in enumerate(SHAPES):
+        if scale == GR and c % 128:
+            continue
+        say(f"shapes bits={bits} scale={scale} dtype={dtype} mode={mode} N={n} C={c}")
+        d = cf.desc(n, c, dtype, bits, scale)
+        xs = drift_stream((n, c), dtype, steps=4, seed=100 + k, device=DEV)
+        run_parity([d], cf.options(), [[x] for x in xs], mode=mode, tag=f"N{n}C{c}")
+
+
+@pytest.mark.parametrize("ef", [cf.CF_EF_RECON, cf.CF_EF_LITERAL, cf.CF_EF_OFF])
+@pytest.mark.parametrize("err_dtype", [cf.CF_F32, cf.CF_BF16])
+def test_parity_ef_modes_and_err_dtypes(ef, err_dtype):
+    n, c = 203, 1152
+    for bits, scale in COMBOS:
+        for dtype in (cf.CF_BF16, cf.CF_F32):
+            say(f"ef={ef} err_dtype={err_dtype} bits={bits} scale={scale} dtype={dtype}")
+            d = cf.desc(n, c, dtype, bits, scale)
+            xs = drift_stream((n, c), dtype, steps=5, seed=7 * bits + ef, device=DEV)
+            run_parity([d], cf.options(ef=ef, err_dtype=err_dtype), [[x] for x in xs], mode="fused")
+
+
+@pytest.mark.parametrize("tile_rows", [8, 16, 32, 64])
+def test_parity_every_tile_height(tile_rows):
+    """The tree over rows is split differently for every tile height; scales must not move."""
+    n, c = 333, 1096
+    for bits in (1, 2, 4):
+        say(f"tile_rows={tile_rows} bits={bits}")
+        d = cf.desc(n, c, cf.CF_BF16, bits, CH)
+        xs = drift_stream((n, c), cf.CF_BF16, steps=3, seed=bits, device=DEV)
+        run_parity([d], cf.options(tile_rows=tile_rows), [[x] for x in xs])
+
+
+def _mixed_batch():
+    descs = [cf.desc(203, 1096, cf.CF_BF16, 1, CH), cf.desc(64, 3072, cf.CF_BF16, 2, CH),
+             cf.desc(100, 256, cf.CF_F32, 4, GR), cf.desc(77, 1024, cf.CF_BF16, 4, CH),
+             cf.desc(256, 64, cf.CF_F32, 2, CH), cf.desc(19, 384, cf.CF_BF16, 4, GR),
+             cf.desc(40, 8, cf.CF_F32, 1, CH)]
+    streams = [drift_stream((d.n_tokens, d.n_channels), d.dtype, steps=4, seed=40 + k, device=DEV)
+               for k, d in enumerate(descs)]
+    xs = [[streams[t][s] for t in range(len(descs))] for s in range(4)]
+    return descs, xs
+
+
+@pytest.mark.parametrize("mode", ["fused", "split"])
+def test_parity_batched_mixed_launch(mode):
+    """One call covers tensors of different shapes, dtypes, widths and scale kinds."""
+    say(f"mixed batch mode={mode}")
+    descs, xs = _mixed_batch()
+    run_parity(descs, cf.options(), xs, mode=mode)
+
+
+def test_subrange_calls_match_whole_batch():
+    """Calling [first, first+count) pieces, in any order, equals one whole-batch call."""
+    say("subrange")
+    descs, xs = _mixed_batch()
+    a = CodecSession(descs, device=DEV)
+    b = CodecSession(descs, device=DEV)
+    a.warmup(xs[0])
+    b.warmup(xs[0][4:], first=4, count=3)
+    b.warmup(xs[0][:4], first=0, count=4)
+    for s in range(1, 4):
+        a.step_fused(xs[s])
+        b.step_fused(xs[s][5:], first=5, count=2)
+        b.step_fused(xs[s][:2], first=0, count=2)
+        b.step_fused(xs[s][2:5], first=2, count=3)
+        torch.cuda.synchronize()
+        for t in range(len(descs)):
+            for name in ("codes", "scales", "recon", "err"):
+                assert torch.equal(getattr(a, name)[t].view(torch.uint8), getattr(b, name)[t].view(torch.uint8)), (s, t, name)
+    a.close(); b.close()
+
+
+def test_fused_is_bit_identical_to_compress_then_decompress():
+    say("fused == split")
+    descs, xs = _mixed_batch()
+    for opts in (cf.options(), cf.options(ef=cf.CF_EF_LITERAL, err_dtype=cf.CF_BF16), cf.options(ef=cf.CF_EF_OFF)):
+        a = CodecSession(descs, opts, device=DEV)
+        b = CodecSession(descs, opts, device=DEV)
+        a.warmup(xs[0]); b.warmup(xs[0])
+        for s in range(1, 4):
+            a.step_fused(xs[s])
+            b.compress(xs[s])
+            recon_before = [r.clone() for r in b.recon]
+            torch.cuda.synchronize()
+            for t in range(len(descs)):      # cf_compress leaves recon alone
+                assert torch.equal(b.recon[t].view(torch.uint8), recon_before[t].view(torch.uint8))
+            b.decompress()
+            torch.cuda.synchronize()
+            for t in range(len(descs)):
+                for name in ("codes", "scales", "recon", "err"):
+                    assert torch.equal(getattr(a, name)[t].view(torch.uint8), getattr(b, name)[t].view(torch.uint8)), (s, t, name)
+        a.close(); b.close()
+
+
+def test_receiver_tracks_sender_through_the_wire():
+    """A receiver that only ever sees codes and scales keeps the same reconstruction as the sender."""
+    say("receiver")
+    descs, xs = _mixed_batch()
+    snd = CodecSession(descs, device=DEV)
+    rcv = CodecSession(descs, device=DEV)
+    snd.warmup(xs[0]); rcv.warmup(xs[0])          # the warm-up step travels uncompressed
+    for s in range(1, 4):
+        snd.step_fused(xs[s])
+        for t in range(len(descs)):               # "the wire": the packed buffers
+            rcv.codes[t].copy_(snd.codes[t]); rcv.scales[t].copy_(snd.scales[t])
+        rcv.decompress()
+        torch.cuda.synchronize()
+        for t in range(len(descs)):
+            assert torch.equal(snd.recon[t].view(torch.uint8), rcv.recon[t].view(torch.uint8))
+    snd.close(); rcv.close()
+
+
+# ------------------------------------------------------------------ degenerate and edge inputs
+
+def test_zero_residual_and_exact_round_trip_on_gpu():
+    say("zero residual / representable")
+    rng = np.random.default_rng(3)
+    for bits, scale in COMBOS:
+        n, c = 384, 256
+        d = cf.desc(n, c, cf.CF_F32, bits, scale)
+        x0 = torch.from_numpy(np.round(rng.standard_normal((n, c)) * 4).astype(np.float32)).to(DEV)
+        s = CodecSession([d], device=DEV)
+        s.warmup([x0])
+        s.step_fused([x0])                        # x_t == recon_{t-1}
+        torch.cuda.synchronize()
+        assert not s.codes[0].any() and not s.scales[0].any() and not s.err[0].any()
+        assert torch.equal(s.recon[0], x0)
+        # representable residuals come back exactly
+        if bits == 1:
+            z = 0.375 * rng.choice([-1.0, 1.0], size=(n, c))
+        elif bits == 2:
+            z = np.where(np.arange(n)[:, None] % 3 == 0, 2.0, 0.5) * 0.25 * rng.choice([-1.0, 1.0], size=(n, c))
+        else:
+            k = rng.integers(-7, 8, size=(n, c)); k[:, ::128] = 7; k[0, :] = -7
+            z = k * 0.5
+        x1 = x0 + torch.from_numpy(z.astype(np.float32)).to(DEV)
+        s.step_fused([x1])
+        torch.cuda.synchronize()
+        assert torch.equal(s.recon[0], x1) and not s.err[0].any()
+        s.close()
+
+
+def test_extreme_values_stay_in_parity():
+    """Large dynamic range, exact ties of the 2-bit threshold and 4-bit half-way points, signed zeros."""
+    say("extremes")
+    rng = np.random.default_rng(5)
+    n, c = 64, 256
+    base = rng.standard_normal((n, c)).astype(np.float32)
+    scalecol = (10.0 ** rng.integers(-12, 12, size=c)).astype(np.float32)
+    x0 = np.zeros((n, c), dtype=np.float32)
+    x1 = base * scalecol[None, :]
+    x1[:, 0] = np.where(np.arange(n) % 4 == 1, 0.25, 1.25)          # mean 1.0 -> 1.25 is an exact tie
+    x1[:, 1] = 0.0
+    x1[:, 2] = -0.0
+    x1[::2, 3] = 3.5; x1[1::2, 3] = 7.0                              # 4-bit: 3.5/1.0 is a half-way point
+    x1[:, 4] = 2.0 ** -130                                           # denormal column
+    for bits, scale in COMBOS:
+        for dtype in (cf.CF_F32, cf.CF_BF16):
+            d = cf.desc(n, c, dtype, bits, scale)
+            conv = (lambda a: torch.from_numpy(a).to(DEV).to(torch.bfloat16)) if dtype == cf.CF_BF16 else (lambda a: torch.from_numpy(a).to(DEV))
+            run_parity([d], cf.options(), [[conv(x0)], [conv(x1)], [conv(x1 * 0.5)]], tag=f"extreme b{bits}s{scale}d{dtype}")
+
+
+# ------------------------------------------------------------------ argument and state errors (need a context)
+
+def test_argument_and_state_errors():
+    say("errors")
+    d = cf.desc(32, 128, cf.CF_BF16, 2, CH)
+    s = CodecSession([d, d], device=DEV)
+    x = [torch.zeros(32, 128, dtype=torch.bfloat16, device=DEV) for _ in range(2)]
+    with pytest.raises(cf.CFError) as ei:          # not warmed up
+        s.step_fused(x)
+    assert ei.value.status == cf.CF_ERR_STATE
+    with pytest.raises(cf.CFError) as ei:
+        s.decompress()
+    assert ei.value.status == cf.CF_ERR_STATE
+    s.warmup(x[:1], first=0, count=1)
+    with pytest.raises(cf.CFError) as ei:          # tensor 1 still cold
+        s.step_fused(x)
+    assert ei.value.status == cf.CF_ERR_STATE
+    s.step_fused(x[:1], first=0, count=1)
+    s.warmup(x)
+    P = cf.ptr_array
+    good = dict(x=P(x), recon=s.p_recon, err=s.p_err, codes=s.p_codes, scales=s.p_scales)
+
+    def call(**kw):
+        a = dict(good); a.update(kw)
+        cf.cf_step_fused(s.ctx, 0, 2, a["x"], a["recon"], a["err"], a["codes"], a["scales"], s.stream_handle)
+
+    for bad in (dict(x=None), dict(codes=P([s.codes[0], 0])), dict(x=P([x[0].data_ptr() + 2, x[1]])),
+                dict(x=s.p_recon), dict(scales=s.p_codes)):
+        with pytest.raises(cf.CFError) as ei:
+            call(**bad)
+        assert ei.value.status == cf.CF_ERR_INVALID_ARG
+    for first, count in ((-1, 1), (0, 3), (2, 1), (1, -1)):
+        with pytest.raises(cf.CFError) as ei:
+            cf.cf_step_fused(s.ctx, first, count, good["x"], good["recon"], good["err"], good["codes"], good["scales"], s.stream_handle)
+        assert ei.value.status == cf.CF_ERR_INVALID_ARG
+    cf.cf_step_fused(s.ctx, 1, 0, good["x"], good["recon"], good["err"], good["codes"], good["scales"], s.stream_handle)  # empty range: no-op
+    # nothing above may have changed state: a valid step still matches the oracle
+    torch.cuda.synchronize()
+    orc = OracleState([d, d], s.opts)
+    for t in range(2):
+        orc.warmup(t, as_numpy(x[t]))
+    x1 = drift_stream((32, 128), cf.CF_BF16, 2, seed=1, device=DEV)
+    s.step_fused([x1[0], x1[1]])
+    torch.cuda.synchronize()
+    for t in range(2):
+        orc.step(t, as_numpy(x1[t]))
+        compare_tensor("after errors", s, orc, t)
+    s.close()
+
+
+def test_resume_from_saved_state():
+    """State is only (recon, err): a new context handed the same buffers continues identically."""
+    say("resume")
+    d = cf.desc(100, 1096, cf.CF_BF16, 2, CH)
+    xs = drift_stream((100, 1096), cf.CF_BF16, 6, seed=9, device=DEV)
+    a = CodecSession([d], device=DEV)
+    a.warmup([xs[0]])
+    for s in range(1, 6):
+        a.step_fused([xs[s]])
+    b = CodecSession([d], device=DEV)
+    b.warmup([xs[0]])
+    for s in range(1, 3):
+        b.step_fused([xs[s]])
+    torch.cuda.synchronize()
+    c = CodecSession([d], device=DEV)
+    c.recon[0].copy_(b.recon[0]); c.err[0].copy_(b.err[0])
+    cf.cf_set_warm(c.ctx, 0, 1, True)
+    for s in range(3, 6):
+        c.step_fused([xs[s]])
+    torch.cuda.synchronize()
+    for name in ("codes", "scales", "recon", "err"):
+        assert torch.equal(getattr(a, name)[0].view(torch.uint8), getattr(c, name)[0].view(torch.uint8)), name
+    a.close(); b.close(); c.close()
+
+
+# ------------------------------------------------------------------ the five configurations, reduced
+
+def test_cfg1_tiny_exactly_as_stated():
+    """Config 1 at its real size: fp32 [256, 64], 5 steps, 2-bit per-channel, numpy seed 0."""
+    say("cfg1")
+    xs = cfg1_numpy(seed=0, steps=5)
+    d = cf.desc(256, 64, cf.CF_F32, 2, CH)
+    for mode in ("fused", "split"):
+        run_parity([d], cf.options(), [[torch.from_numpy(x).to(DEV)] for x in xs], mode=mode, tag="cfg1")
+
+
+@pytest.mark.parametrize("name,shrink", [
+    ("cfg2_flux_patch", dict(n_tensors=4, n_tokens=200, steps=5)),
+    ("cfg3_kv_fullseq", dict(n_tensors=4, n_tokens=520, steps=4)),
+    ("cfg4_video", dict(n_tensors=3, n_tokens=300, steps=6)),
+    ("cfg5_batched_mixed", dict(n_tensors=6, n_tokens=260, steps=4)),
+])
+def test_configs_reduced(name, shrink):
+    """The recipe of configs 2-5 (3072 channels, outliers, decaying drift, heavy tails, mixed widths)
+    at a token and layer count the oracle handles in seconds."""
+    say(name)
+    wl = CONFIGS[name].scaled(**shrink)
+    stream = ActivationStream(wl, device=DEV)
+    scale = GR if wl.scale == "group" else CH
+    descs = [cf.desc(wl.n_tokens, wl.n_channels, cf.CF_BF16, wl.bits_of(t), scale, wl.group) for t in range(wl.n_tensors)]
+    xs = [[x.clone() for x in stream.current]]
+    for _ in range(1, wl.steps):
+        xs.append([x.clone() for x in stream.advance()])
+    run_parity(descs, cf.options(), xs, mode="fused", tag=name)
