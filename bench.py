@@ -1,0 +1,313 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused residual codec on one MI355X.
+
+A step is one cf_step_fused call over ALL layer tensors of a workload (the whole
+hot path: residual, error feedback, scales, codes, packing, decode, error and
+reconstruction update), with the step's activations already resident in HBM.
+The metric is algorithmic GB/s through the codec: every input read once and
+every output written once, per element
+    x + recon(read) + recon(write) + err(write) + bits/8 + scales,
+divided by the wall time of a step; it is reported against the 8 TB/s HBM peak.
+
+Prints ONE JSON line (see README for the fields).  Inputs are seeded
+synthetic activation streams (workloads/), standing in for FLUX.1-dev and
+CogVideoX-2b activations.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
+
+DEFAULT_WORKLOAD = "cfg3_kv_fullseq"
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, help="one of workloads.CONFIGS, or 'all'")
+    ap.add_argument("--ef", type=int, default=0, help="cf_ef_mode (0 = RECON)")
+    ap.add_argument("--flags", type=int, default=0, help="cf_options.flags")
+    ap.add_argument("--tile-rows", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true")
+    ap.add_argument("--quiet", action="store_true")
+    return ap.parse_args()
+
+
+def log(args, *a):
+    if not args.quiet:
+        print(*a, file=sys.stderr, flush=True)
+
+
+# ------------------------------------------------------------------ HIP events (for per-kernel durations)
+
+class HipEvents:
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so.7")   # the runtime torch already loaded
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.all = []
+
+    def create(self, n):
+        out = []
+        for _ in range(n):
+            e = ctypes.c_void_p()
+            rc = self.hip.hipEventCreate(ctypes.byref(e))
+            if rc != 0:
+                raise RuntimeError(f"hipEventCreate failed: {rc}")
+            out.append(e.value)
+            self.all.append(e.value)
+        return out
+
+    def elapsed_ms(self, a, b) -> float:
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(ms.value)
+
+    def destroy(self):
+        for e in self.all:
+            self.hip.hipEventDestroy(e)
+        self.all = []
+
+
+# ------------------------------------------------------------------ workload accounting
+
+def bytes_per_element(wl, bits: int, ef: int, err_bytes: int = 4) -> float:
+    sx = 4 if wl.dtype == "f32" else 2
+    b = sx + sx + sx + err_bytes + bits / 8.0          # x, recon read, recon write, err write, codes
+    if ef != 0:
+        b += err_bytes                                  # LITERAL / OFF also read err
+    b += 4.0 / wl.group if wl.scale == "group" else 4.0 / wl.n_tokens
+    return b
+
+
+def step_bytes(wl, ef: int) -> float:
+    per_tensor = wl.n_tokens * wl.n_channels
+    return sum(per_tensor * bytes_per_element(wl, wl.bits_of(t), ef) for t in range(wl.n_tensors))
+
+
+def run_workload(name: str, args, events: HipEvents | None):
+    import torch
+
+    import paper_2507_17511_amd as cf
+    from paper_2507_17511_amd.session import CodecSession
+    from workloads import CONFIGS, ActivationStream
+
+    wl = CONFIGS[name]
+    dev = "cuda:0"
+    dt = cf.CF_F32 if wl.dtype == "f32" else cf.CF_BF16
+    scale = cf.CF_SCALE_GROUP if wl.scale == "group" else cf.CF_SCALE_CHANNEL
+    descs = [cf.desc(wl.n_tokens, wl.n_channels, dt, wl.bits_of(t), scale, wl.group) for t in range(wl.n_tensors)]
+    opts = cf.options(ef=args.ef, flags=args.flags, tile_rows=args.tile_rows)
+
+    t0 = time.time()
+    stream = ActivationStream(wl, device=dev)
+    x0 = [x.clone() for x in stream.current]
+    # a ring of consecutive stream states x_1..x_R; the timed loop walks it back and forth so that
+    # every step sees an input one drift step away from the last (real residual statistics)
+    R = 4
+    ring = [[x.clone() for x in stream.advance()] for _ in range(R)]
+    del stream
+    torch.cuda.synchronize()
+    log(args, f"[{name}] inputs ready in {time.time() - t0:.1f}s "
+              f"({wl.n_tensors} x [{wl.n_tokens},{wl.n_channels}] {wl.dtype}, bits {tuple(wl.bits)}, {wl.scale} scale)")
+
+    sess = CodecSession(descs, opts, device=dev)
+    p_ring = [cf.ptr_array(xs) for xs in ring]
+    order = list(range(R)) + list(range(R - 2, 0, -1))      # 0 1 2 3 2 1 | 0 1 ...
+
+    def step(k):
+        cf.cf_step_fused(sess.ctx, 0, sess.n, p_ring[order[k % len(order)]], sess.p_recon, sess.p_err,
+                         sess.p_codes, sess.p_scales, sess.stream_handle)
+
+    sess.warmup(x0)
+    k = 0
+    for _ in range(args.warmup):
+        step(k); k += 1
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step(k); k += 1
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    ms_per_step = wall * 1e3 / args.steps
+
+    nbytes = step_bytes(wl, args.ef)
+    act_bytes = wl.n_tensors * wl.n_tokens * wl.n_channels * (4 if wl.dtype == "f32" else 2)
+    res = {
+        "workload": name,
+        "ms_per_step": ms_per_step,
+        "algorithmic_bytes_per_step": nbytes,
+        "gbps": nbytes / (ms_per_step * 1e-3) / 1e9,
+        "activation_gbps": act_bytes / (ms_per_step * 1e-3) / 1e9,
+        "bytes_per_element": nbytes / (wl.n_tensors * wl.n_tokens * wl.n_channels),
+    }
+    res["frac_of_hbm_peak"] = res["gbps"] / HBM_PEAK_GBPS
+
+    # second, instrumented pass: HIP events around every kernel the library launches, on its stream
+    if events is not None:
+        n_prof = min(args.steps, 10)
+        sets = [events.create(16) for _ in range(n_prof)]
+        names = []
+        for s in range(n_prof):
+            cf.cf_profile_next_call(sess.ctx, sets[s], 8)
+            step(k); k += 1
+            n_launch = min(cf.cf_profile_launch_count(sess.ctx), 8)
+            names.append([cf.cf_profile_kernel_name(sess.ctx, i) for i in range(n_launch)])
+        torch.cuda.synchronize()
+        per_kernel = {}
+        for s in range(n_prof):
+            for i, nm in enumerate(names[s]):
+                per_kernel.setdefault(nm, []).append(events.elapsed_ms(sets[s][2 * i], sets[s][2 * i + 1]))
+        res["kernel_ms"] = {nm: sum(v) / len(v) for nm, v in per_kernel.items()}
+        res["kernel_launches_per_step"] = {nm: len(v) / n_prof for nm, v in per_kernel.items()}
+    sess.close()
+    del sess, ring, x0
+    torch.cuda.empty_cache()
+    return res, wl
+
+
+def dominant_kernel(res):
+    km = res.get("kernel_ms") or {}
+    if not km:
+        return None, None
+    nm = max(km, key=lambda n: km[n] * res["kernel_launches_per_step"][n])
+    return nm, km[nm]
+
+
+def kernel_algorithmic_bytes(nm: str, wl, ef: int) -> float:
+    """Algorithmic bytes one launch of kernel `nm` moves (every operand of that kernel once)."""
+    total = 0.0
+    for t in range(wl.n_tensors):
+        n = wl.n_tokens * wl.n_channels
+        sx = 4 if wl.dtype == "f32" else 2
+        bits = wl.bits_of(t)
+        scale_b = 4.0 / wl.group if wl.scale == "group" else 4.0 / wl.n_tokens
+        if nm == "k_colreduce":
+            per = 2 * sx + (4 if ef else 0)
+        elif nm == "k_encode":          # reads x, recon (+err); writes codes, err, recon
+            per = 3 * sx + 4 + bits / 8.0 + (4 if ef else 0) + scale_b
+        elif nm == "k_decode":
+            per = 2 * sx + bits / 8.0 + scale_b
+        else:                            # a kernel that does the whole step
+            per = bytes_per_element(wl, bits, ef)
+        total += n * per
+    return total
+
+
+def cpu_baseline(wl, ef: int, budget_s: float = 15.0):
+    """The oracle as it stands, single-threaded, on a bounded sample of the same workload."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from workloads import ActivationStream, as_numpy
+
+    small = wl.scaled(n_tensors=min(wl.n_tensors, 3))
+    stream = ActivationStream(small, device="cpu")
+    cfgs = [oracle.Config(wl.n_tokens, wl.n_channels, dtype=oracle.F32 if wl.dtype == "f32" else oracle.BF16,
+                          bits=wl.bits_of(t), scale=oracle.SCALE_GROUP if wl.scale == "group" else oracle.SCALE_CHANNEL,
+                          group=wl.group, ef=ef) for t in range(small.n_tensors)]
+    state = [oracle.warmup(cfgs[t], as_numpy(stream.current[t])) for t in range(small.n_tensors)]
+    done, spent, nbytes = 0, 0.0, 0.0
+    while spent < budget_s and done < 12:
+        xs = [as_numpy(x) for x in stream.advance()]
+        for t in range(small.n_tensors):
+            t0 = time.perf_counter()
+            oracle.step(cfgs[t], xs[t], state[t][0], state[t][1])
+            spent += time.perf_counter() - t0
+            nbytes += wl.n_tokens * wl.n_channels * bytes_per_element(wl, wl.bits_of(t), ef)
+            done += 1
+            if spent >= budget_s:
+                break
+    return {"value": nbytes / spent / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{done} tensor-steps of [{wl.n_tokens},{wl.n_channels}] {wl.dtype} from {wl.name} "
+                      f"(first {small.n_tensors} layers), {spent:.1f}s single-threaded C oracle",
+            "seconds_per_tensor_step": spent / done}
+
+
+def read_traffic(kernel: str, workload: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one for this pair."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{kernel}_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("hbm_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU only (the packed-code buffer in HBM stands in for the wire; "
+              "there is no multi-GPU path): run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2507_17511_amd as cf
+    from workloads import CONFIGS
+    cf.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    events = None if args.no_kernel_events else HipEvents()
+
+    names = list(CONFIGS) if args.workload == "all" else [args.workload]
+    results = {}
+    for nm in names:
+        r, wl = run_workload(nm, args, events)
+        results[nm] = (r, wl)
+        log(args, f"[{nm}] {r['ms_per_step']:.3f} ms/step  {r['gbps']:.0f} GB/s algorithmic "
+                  f"({100 * r['frac_of_hbm_peak']:.1f}% of {HBM_PEAK_GBPS:.0f})  kernels: {r.get('kernel_ms')}")
+    head = DEFAULT_WORKLOAD if args.workload == "all" else args.workload
+    r, wl = results[head]
+
+    kname, kms = dominant_kernel(r)
+    roofline = None
+    if kname is not None:
+        kb = kernel_algorithmic_bytes(kname, wl, args.ef)
+        achieved = kb / (kms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(kname, head),
+                    "algorithmic_bytes_per_launch": kb, "avg_launch_ms": kms}
+    cpu = None if args.no_cpu_baseline else cpu_baseline(wl, args.ef)
+    if events is not None:
+        events.destroy()
+
+    out = {
+        "metric": "activation GB/s through fused residual codec (% of MI355X HBM peak)",
+        "value": r["gbps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": head, "tensors": wl.n_tensors, "shape": [wl.n_tokens, wl.n_channels],
+                   "storage": wl.dtype, "bits": list(wl.bits), "scale": wl.scale, "ef_mode": args.ef,
+                   "launch": "one cf_step_fused call per step over all tensors"},
+        "pct_of_hbm_peak": 100.0 * r["frac_of_hbm_peak"],
+        "activation_gbps": r["activation_gbps"],
+        "bytes_per_element": r["bytes_per_element"],
+        "kernel_ms": r.get("kernel_ms"),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    if len(results) > 1:
+        out["all_workloads"] = {nm: {k: v for k, v in rr.items() if k != "workload"} for nm, (rr, _) in results.items()}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -159,6 +159,21 @@ const char *cf_status_string(cf_status s);
 /* The hipError_t value of the last failed HIP call in this context (0 if none). */
 int32_t cf_last_hip_error(const cf_ctx *ctx);
 
+/* Instrumentation for benchmarks (no part of the method).  With `events` set
+ * (a host array of 2*n_pairs hipEvent_t created by the caller), the NEXT
+ * cf_compress / cf_decompress / cf_step_fused call records events[2k] before
+ * and events[2k+1] after its k-th kernel launch on the call's stream, for as
+ * many launches as there are pairs, then switches itself off again.  The
+ * launches of a call are, in order: pointer-table uploads (only when a pointer
+ * changed), then the codec kernels named by cf_profile_kernel_name.  NULL/0
+ * switches it off. */
+cf_status cf_profile_next_call(cf_ctx *ctx, void *const *events, int32_t n_pairs);
+
+/* After a profiled call: how many launches it made, and the name of the k-th
+ * (a static string; NULL if k is out of range). */
+int32_t cf_profile_launch_count(const cf_ctx *ctx);
+const char *cf_profile_kernel_name(const cf_ctx *ctx, int32_t k);
+
 #ifdef __cplusplus
 }
 #endif

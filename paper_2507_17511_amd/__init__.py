@@ -28,7 +28,8 @@ CF_EF_RECON, CF_EF_LITERAL, CF_EF_OFF = 0, 1, 2
 CF_FLAG_NO_PERSISTENT = 0x1
 
 EXPORTS = ["cf_sizes", "cf_workspace_bytes", "cf_init", "cf_warmup", "cf_set_warm", "cf_compress",
-           "cf_decompress", "cf_step_fused", "cf_destroy", "cf_status_string", "cf_last_hip_error"]
+           "cf_decompress", "cf_step_fused", "cf_destroy", "cf_status_string", "cf_last_hip_error",
+           "cf_profile_next_call", "cf_profile_launch_count", "cf_profile_kernel_name"]
 
 
 class cf_tensor_desc(ctypes.Structure):
@@ -86,6 +87,12 @@ def lib() -> ctypes.CDLL:
         L.cf_status_string.argtypes = [i32]
         L.cf_last_hip_error.restype = i32
         L.cf_last_hip_error.argtypes = [vp]
+        L.cf_profile_next_call.restype = i32
+        L.cf_profile_next_call.argtypes = [vp, pp, i32]
+        L.cf_profile_launch_count.restype = i32
+        L.cf_profile_launch_count.argtypes = [vp]
+        L.cf_profile_kernel_name.restype = ctypes.c_char_p
+        L.cf_profile_kernel_name.argtypes = [vp, i32]
         _lib = L
     return _lib
 
@@ -193,3 +200,18 @@ def cf_decompress(ctx, first: int, count: int, codes, scales, recon, stream=None
 def cf_step_fused(ctx, first: int, count: int, x, recon, err, codes, scales, stream=None) -> None:
     _check(lib().cf_step_fused(ctx, first, count, _pa(x), _pa(recon), _pa(err), _pa(codes), _pa(scales),
                                _addr(stream)), "cf_step_fused", ctx)
+
+
+def cf_profile_next_call(ctx, events, n_pairs: int) -> None:
+    """events: sequence of 2*n_pairs hipEvent_t handles (ints) or None to switch off."""
+    _check(lib().cf_profile_next_call(ctx, _pa(events) if events is not None else None, n_pairs),
+           "cf_profile_next_call", ctx)
+
+
+def cf_profile_launch_count(ctx) -> int:
+    return int(lib().cf_profile_launch_count(ctx))
+
+
+def cf_profile_kernel_name(ctx, k: int) -> Optional[str]:
+    name = lib().cf_profile_kernel_name(ctx, k)
+    return name.decode() if name else None

@@ -146,6 +146,12 @@ struct cf_ctx {
     int32_t last_hip = 0;
     int device = 0;
 
+    // benchmark instrumentation (cf_profile_next_call)
+    std::vector<hipEvent_t> prof_events;
+    bool prof_armed = false;
+    int32_t prof_count = 0;
+    const char *prof_names[16] = {};
+
     BatchView view() const
     {
         BatchView v;
@@ -209,6 +215,27 @@ cf_status device_fail(cf_ctx *ctx, hipError_t e)
     return CF_ERR_DEVICE;
 }
 
+// Runs one launch; when the call is being profiled, brackets it with the caller's events.
+template <class F>
+hipError_t launch(cf_ctx *ctx, hipStream_t s, const char *name, F &&f)
+{
+    const int32_t k = ctx->prof_count;
+    const bool rec = ctx->prof_armed && (size_t)(2 * k + 1) < ctx->prof_events.size();
+    if (ctx->prof_armed && k < 16) ctx->prof_names[k] = name;
+    if (ctx->prof_armed) ctx->prof_count = k + 1;
+    hipError_t e = hipSuccess;
+    if (rec) e = hipEventRecord(ctx->prof_events[2 * k], s);
+    if (e == hipSuccess) e = f();
+    if (e == hipSuccess && rec) e = hipEventRecord(ctx->prof_events[2 * k + 1], s);
+    return e;
+}
+
+struct ProfileScope {      // a profiled call is exactly one entry-point call
+    cf_ctx *ctx;
+    explicit ProfileScope(cf_ctx *c) : ctx(c) { if (ctx->prof_armed) ctx->prof_count = 0; }
+    ~ProfileScope() { ctx->prof_armed = false; }
+};
+
 // Brings the workspace pointer table up to date for [first, first+count).
 // Arrays that an entry point does not take are passed as nullptr and keep
 // their last value.  Nothing is launched when no pointer changed.
@@ -236,7 +263,7 @@ cf_status sync_ptrs(cf_ctx *ctx, int32_t first, int32_t count, const void *const
         PtrChunk chunk;
         std::memset(&chunk, 0, sizeof chunk);
         for (int k = 0; k < n; ++k) chunk.p[k] = ctx->ptrs[first + k0 + k];
-        hipError_t e = launch_upload_ptrs(chunk, table + first + k0, n, s);
+        hipError_t e = launch(ctx, s, "k_upload_ptrs", [&] { return launch_upload_ptrs(chunk, table + first + k0, n, s); });
         if (e != hipSuccess) {
             // the mirror no longer matches the device table: force a re-upload next time
             for (int32_t k = 0; k < count; ++k) std::memset(&ctx->ptrs[first + k], 0xff, sizeof(TensorPtrs));
@@ -265,15 +292,20 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
     if ((st = check_warm(ctx, first, count)) != CF_OK) return st;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
+    ProfileScope prof(ctx);
     if ((st = sync_ptrs(ctx, first, count, x, recon, err, codes, scales, s)) != CF_OK) return st;
     BatchView v = ctx->view();
     LaunchRange r = ctx->range(first, count);
+    const int ef = ctx->opts.ef, et = ctx->opts.err_dtype;
     hipError_t e;
     if (ctx->range_has_channel(first, count)) {
-        if ((e = launch_colreduce(v, r, ctx->opts.ef, ctx->opts.err_dtype, s)) != hipSuccess) return device_fail(ctx, e);
-        if ((e = launch_finalize(v, r, s)) != hipSuccess) return device_fail(ctx, e);
+        e = launch(ctx, s, "k_colreduce", [&] { return launch_colreduce(v, r, ef, et, s); });
+        if (e != hipSuccess) return device_fail(ctx, e);
+        e = launch(ctx, s, "k_finalize", [&] { return launch_finalize(v, r, s); });
+        if (e != hipSuccess) return device_fail(ctx, e);
     }
-    if ((e = launch_encode(v, r, ctx->opts.ef, ctx->opts.err_dtype, fused, s)) != hipSuccess) return device_fail(ctx, e);
+    e = launch(ctx, s, "k_encode", [&] { return launch_encode(v, r, ef, et, fused, s); });
+    if (e != hipSuccess) return device_fail(ctx, e);
     return CF_OK;
 }
 
@@ -371,6 +403,27 @@ void cf_destroy(cf_ctx *ctx) { delete ctx; }
 
 int32_t cf_last_hip_error(const cf_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
 
+cf_status cf_profile_next_call(cf_ctx *ctx, void *const *events, int32_t n_pairs)
+{
+    if (!ctx || n_pairs < 0 || (n_pairs > 0 && !events)) return CF_ERR_INVALID_ARG;
+    ctx->prof_events.clear();
+    for (int32_t k = 0; k < 2 * n_pairs; ++k) {
+        if (!events[k]) { ctx->prof_events.clear(); return CF_ERR_INVALID_ARG; }
+        ctx->prof_events.push_back(static_cast<hipEvent_t>(events[k]));
+    }
+    ctx->prof_armed = n_pairs > 0;
+    ctx->prof_count = 0;
+    return CF_OK;
+}
+
+int32_t cf_profile_launch_count(const cf_ctx *ctx) { return ctx ? ctx->prof_count : 0; }
+
+const char *cf_profile_kernel_name(const cf_ctx *ctx, int32_t k)
+{
+    if (!ctx || k < 0 || k >= ctx->prof_count || k >= 16) return nullptr;
+    return ctx->prof_names[k];
+}
+
 cf_status cf_set_warm(cf_ctx *ctx, int32_t first, int32_t count, int32_t warm)
 {
     cf_status st = check_range(ctx, first, count);
@@ -424,10 +477,11 @@ cf_status cf_decompress(cf_ctx *ctx, int32_t first, int32_t count, const void *c
         if (codes[k] == scales[k] || codes[k] == recon[k] || scales[k] == recon[k]) return CF_ERR_INVALID_ARG;
     if ((st = check_warm(ctx, first, count)) != CF_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    ProfileScope prof(ctx);
     st = sync_ptrs(ctx, first, count, nullptr, recon, nullptr, const_cast<void *const *>(codes),
                    const_cast<void *const *>(scales), s);
     if (st != CF_OK) return st;
-    hipError_t e = launch_decode(ctx->view(), ctx->range(first, count), s);
+    hipError_t e = launch(ctx, s, "k_decode", [&] { return launch_decode(ctx->view(), ctx->range(first, count), s); });
     if (e != hipSuccess) return device_fail(ctx, e);
     return CF_OK;
 }
