@@ -159,6 +159,13 @@ const char *cf_status_string(cf_status s);
 /* The hipError_t value of the last failed HIP call in this context (0 if none). */
 int32_t cf_last_hip_error(const cf_ctx *ctx);
 
+/* Synchronises `stream` and reports whether any kernel of this context gave up
+ * on a bounded wait (the single-pass kernel's workgroups wait for each other;
+ * a wait that expires raises a flag in the workspace instead of hanging).
+ * CF_OK, or CF_ERR_DEVICE with cf_last_hip_error() == 0 for that flag; after
+ * it the outputs of that call are undefined and the context should be rebuilt. */
+cf_status cf_check_device(cf_ctx *ctx, void *stream);
+
 /* Instrumentation for benchmarks (no part of the method).  With `events` set
  * (a host array of 2*n_pairs hipEvent_t created by the caller), the NEXT
  * cf_compress / cf_decompress / cf_step_fused call records events[2k] before

@@ -29,7 +29,7 @@ CF_FLAG_NO_PERSISTENT = 0x1
 
 EXPORTS = ["cf_sizes", "cf_workspace_bytes", "cf_init", "cf_warmup", "cf_set_warm", "cf_compress",
            "cf_decompress", "cf_step_fused", "cf_destroy", "cf_status_string", "cf_last_hip_error",
-           "cf_profile_next_call", "cf_profile_launch_count", "cf_profile_kernel_name"]
+           "cf_profile_next_call", "cf_profile_launch_count", "cf_profile_kernel_name", "cf_check_device"]
 
 
 class cf_tensor_desc(ctypes.Structure):
@@ -87,6 +87,8 @@ def lib() -> ctypes.CDLL:
         L.cf_status_string.argtypes = [i32]
         L.cf_last_hip_error.restype = i32
         L.cf_last_hip_error.argtypes = [vp]
+        L.cf_check_device.restype = i32
+        L.cf_check_device.argtypes = [vp, vp]
         L.cf_profile_next_call.restype = i32
         L.cf_profile_next_call.argtypes = [vp, pp, i32]
         L.cf_profile_launch_count.restype = i32
@@ -215,3 +217,8 @@ def cf_profile_launch_count(ctx) -> int:
 def cf_profile_kernel_name(ctx, k: int) -> Optional[str]:
     name = lib().cf_profile_kernel_name(ctx, k)
     return name.decode() if name else None
+
+
+def cf_check_device(ctx, stream=None) -> None:
+    """Synchronises the stream; raises if a kernel of this context gave up on a bounded wait."""
+    _check(lib().cf_check_device(ctx, _addr(stream)), "cf_check_device", ctx)

@@ -19,6 +19,11 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
     size_t off_descs = 0, off_ptrs = 0, off_tile_prefix = 0, off_fin_prefix = 0, off_partials = 0;
+    size_t off_item_prefix = 0, off_counters = 0, off_error = 0, off_p_partials = 0;
+    std::vector<uint32_t> item_prefix, group_prefix;
+    uint32_t n_groups = 0;
+    int32_t max_group_items = 0;   // largest reduction group of the single-pass path
+    bool single_pass = false;      // every channel-scale tensor has single-pass geometry
     size_t total = 0;
     std::vector<TensorDev> dev;
     std::vector<uint32_t> tile_prefix, fin_prefix;
@@ -88,8 +93,11 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     L.dev.resize(n);
     L.tile_prefix.assign(n + 1, 0);
     L.fin_prefix.assign(n + 1, 0);
-    uint64_t tiles = 0, fins = 0;
-    size_t partial_bytes = 0;
+    uint64_t tiles = 0, fins = 0, items = 0, groups = 0;
+    size_t partial_bytes = 0, p_partial_bytes = 0;
+    L.item_prefix.assign(n + 1, 0);
+    L.group_prefix.assign(n + 1, 0);
+    L.single_pass = o.ef == CF_EF_RECON && !(o.flags & CF_FLAG_NO_PERSISTENT);
     for (int32_t t = 0; t < n; ++t) {
         const cf_tensor_desc &d = descs[t];
         TensorDev &v = L.dev[t];
@@ -115,9 +123,27 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
             v.partial_off = partial_bytes;   // relative; rebased below
             partial_bytes += align_up((size_t)v.n_rowblocks * (size_t)d.n_channels * sizeof(float));
         }
+        L.item_prefix[t] = (uint32_t)items;
+        L.group_prefix[t] = (uint32_t)groups;
+        if (d.scale == CF_SCALE_CHANNEL && L.single_pass) {
+            v.p_rows = d.dtype == CF_BF16 ? 128 : 64;        // 8 row-lanes x 16 (bf16) or 8 (fp32) rows
+            v.p_n_rb = (int32_t)((d.n_tokens + v.p_rows - 1) / v.p_rows);
+            v.p_n_stripes = (int32_t)((d.n_channels + kStripeChannels - 1) / kStripeChannels);
+            v.p_item_begin = (uint32_t)items;
+            v.p_group_begin = (uint32_t)groups;
+            v.p_partial_off = p_partial_bytes;               // relative; rebased below
+            p_partial_bytes += align_up((size_t)v.p_n_rb * (size_t)d.n_channels * sizeof(float));
+            items += (uint64_t)v.p_n_rb * (uint64_t)v.p_n_stripes;
+            groups += (uint64_t)v.p_n_stripes;
+            if (v.p_n_rb > L.max_group_items) L.max_group_items = v.p_n_rb;
+            if (items > 0x7fffffffull) return CF_ERR_SHAPE;
+        }
     }
     L.tile_prefix[n] = (uint32_t)tiles;
     L.fin_prefix[n] = (uint32_t)fins;
+    L.item_prefix[n] = (uint32_t)items;
+    L.group_prefix[n] = (uint32_t)groups;
+    L.n_groups = (uint32_t)groups;
 
     size_t off = 0;
     L.off_descs = off;        off = align_up(off + sizeof(TensorDev) * (size_t)n);
@@ -125,9 +151,16 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     L.off_tile_prefix = off;  off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
     L.off_fin_prefix = off;   off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
     L.off_partials = off;     off = align_up(off + partial_bytes);
+    L.off_item_prefix = off;  off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
+    L.off_counters = off;     off = align_up(off + sizeof(uint32_t) * (size_t)(groups + 1));
+    L.off_error = off;        off = align_up(off + sizeof(uint32_t));
+    L.off_p_partials = off;   off = align_up(off + p_partial_bytes);
     L.total = off;
     for (int32_t t = 0; t < n; ++t)
-        if (descs[t].scale == CF_SCALE_CHANNEL) L.dev[t].partial_off += L.off_partials;
+        if (descs[t].scale == CF_SCALE_CHANNEL) {
+            L.dev[t].partial_off += L.off_partials;
+            L.dev[t].p_partial_off += L.off_p_partials;
+        }
     return CF_OK;
 }
 
@@ -145,6 +178,7 @@ struct cf_ctx {
     std::vector<uint8_t> warm;
     int32_t last_hip = 0;
     int device = 0;
+    int persist_grid[2][2] = {{0, 0}, {0, 0}};   // co-resident workgroups of k_persistent<err dtype, fused>
 
     // benchmark instrumentation (cf_profile_next_call)
     std::vector<hipEvent_t> prof_events;
@@ -159,6 +193,9 @@ struct cf_ctx {
         v.ptrs = reinterpret_cast<const TensorPtrs *>(ws + L.off_ptrs);
         v.tile_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_tile_prefix);
         v.fin_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_fin_prefix);
+        v.item_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_item_prefix);
+        v.group_counters = reinterpret_cast<uint32_t *>(ws + L.off_counters);
+        v.error_flag = reinterpret_cast<uint32_t *>(ws + L.off_error);
         v.workspace = ws;
         v.n_tensors = (int32_t)descs.size();
         return v;
@@ -173,7 +210,19 @@ struct cf_ctx {
         r.tile_hi = L.tile_prefix[first + count];
         r.fin_lo = L.fin_prefix[first];
         r.fin_hi = L.fin_prefix[first + count];
+        r.item_lo = L.item_prefix[first];
+        r.item_hi = L.item_prefix[first + count];
+        r.group_lo = L.group_prefix[first];
+        r.group_hi = L.group_prefix[first + count];
+        r.only_group_scale = 0;
         return r;
+    }
+
+    bool range_has_group_scale(int32_t first, int32_t count) const
+    {
+        for (int32_t t = first; t < first + count; ++t)
+            if (descs[t].scale == CF_SCALE_GROUP) return true;
+        return false;
     }
 
     bool range_has_channel(int32_t first, int32_t count) const
@@ -298,6 +347,20 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
     LaunchRange r = ctx->range(first, count);
     const int ef = ctx->opts.ef, et = ctx->opts.err_dtype;
     hipError_t e;
+    const int grid = ctx->persist_grid[et == CF_BF16 ? 1 : 0][fused ? 1 : 0];
+    if (ctx->L.single_pass && grid >= ctx->L.max_group_items && r.item_hi > r.item_lo) {
+        // channel-scale tensors: one pass, x and recon stay in registers across the scale reduction
+        e = launch(ctx, s, "k_zero_counters", [&] { return launch_zero_counters(v, r, s); });
+        if (e != hipSuccess) return device_fail(ctx, e);
+        e = launch(ctx, s, "k_persistent", [&] { return launch_persistent(v, r, et, fused, grid, s); });
+        if (e != hipSuccess) return device_fail(ctx, e);
+        if (ctx->range_has_group_scale(first, count)) {
+            r.only_group_scale = 1;
+            e = launch(ctx, s, "k_encode", [&] { return launch_encode(v, r, ef, et, fused, s); });
+            if (e != hipSuccess) return device_fail(ctx, e);
+        }
+        return CF_OK;
+    }
     if (ctx->range_has_channel(first, count)) {
         e = launch(ctx, s, "k_colreduce", [&] { return launch_colreduce(v, r, ef, et, s); });
         if (e != hipSuccess) return device_fail(ctx, e);
@@ -389,7 +452,20 @@ cf_status cf_init(cf_ctx **out, const cf_tensor_desc *descs, int32_t n_tensors, 
         e = hipMemcpyAsync(ctx->ws + ctx->L.off_fin_prefix, ctx->L.fin_prefix.data(),
                            sizeof(uint32_t) * (size_t)(n_tensors + 1), hipMemcpyHostToDevice, s);
     if (e == hipSuccess)
+        e = hipMemcpyAsync(ctx->ws + ctx->L.off_item_prefix, ctx->L.item_prefix.data(),
+                           sizeof(uint32_t) * (size_t)(n_tensors + 1), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess)
         e = hipMemsetAsync(ctx->ws + ctx->L.off_ptrs, 0, sizeof(TensorPtrs) * (size_t)n_tensors, s);
+    if (e == hipSuccess)
+        e = hipMemsetAsync(ctx->ws + ctx->L.off_counters, 0, ctx->L.off_p_partials - ctx->L.off_counters, s);
+    if (e == hipSuccess && ctx->L.single_pass && ctx->L.max_group_items > 0) {
+        hipDeviceProp_t prop;
+        e = hipGetDeviceProperties(&prop, ctx->device);
+        if (e == hipSuccess)
+            for (int et = 0; et < 2; ++et)
+                for (int fu = 0; fu < 2; ++fu)
+                    ctx->persist_grid[et][fu] = persistent_max_blocks_per_cu(et, fu != 0) * prop.multiProcessorCount;
+    }
     if (e != hipSuccess) {
         (void)hipGetLastError();
         delete ctx;
@@ -413,6 +489,21 @@ cf_status cf_profile_next_call(cf_ctx *ctx, void *const *events, int32_t n_pairs
     }
     ctx->prof_armed = n_pairs > 0;
     ctx->prof_count = 0;
+    return CF_OK;
+}
+
+cf_status cf_check_device(cf_ctx *ctx, void *stream)
+{
+    if (!ctx) return CF_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipStreamSynchronize(s);
+    uint32_t flag = 0;
+    if (e == hipSuccess) e = hipMemcpy(&flag, ctx->ws + ctx->L.off_error, sizeof flag, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return device_fail(ctx, e);
+    if (flag) {
+        ctx->last_hip = 0;
+        return CF_ERR_DEVICE;
+    }
     return CF_OK;
 }
 

@@ -14,6 +14,14 @@ constexpr int kChunk = 8;                                   // channels per lane
 constexpr int kTileChannels = kTileThreads * kChunk;        // 1024
 constexpr int kFinalizeThreads = 256;                       // columns per finalise block
 constexpr int kMaxUploadTensors = 64;                       // pointer sets per upload launch
+// Single-pass path: one workgroup of 256 lanes keeps an item of p_rows x 256
+// channels (x and recon, raw) in registers between the scale reduction and the
+// encode; lanes are 32 chunks x 8 row-lanes.
+constexpr int kPersistThreads = 256;
+constexpr int kStripeChannels = 256;
+constexpr int kStripeChunks = kStripeChannels / kChunk;     // 32
+constexpr int kRowLanes = kPersistThreads / kStripeChunks;  // 8
+constexpr uint32_t kSpinLimit = 1u << 22;                   // bounded wait (about seconds), then the error flag
 
 // Static description of one tensor; built at cf_init, lives in the workspace.
 struct alignas(16) TensorDev {
@@ -29,7 +37,14 @@ struct alignas(16) TensorDev {
     uint32_t tile_begin;    // id of this tensor's first tile in the batched grids
     uint32_t fin_begin;     // id of its first finalise block
     uint64_t partial_off;   // byte offset in the workspace of partial[n_rowblocks][C] (channel scales)
-    uint64_t pad_;
+    // single-pass path (channel scales, CF_EF_RECON): items of p_rows x kStripeChannels
+    uint64_t p_partial_off; // byte offset of partial[p_n_rb][C]
+    int32_t p_rows;         // rows per item (128 for bf16, 64 for fp32); 0 = tensor not on this path
+    int32_t p_n_rb;         // ceil(N / p_rows): items per reduction group
+    int32_t p_n_stripes;    // ceil(C / kStripeChannels): reduction groups of this tensor
+    uint32_t p_item_begin;  // id of this tensor's first item
+    uint32_t p_group_begin; // index of its first group counter
+    uint32_t pad_[3];
 };
 
 // Per-call device pointers of one tensor; uploaded into the workspace.
@@ -51,6 +66,9 @@ struct BatchView {
     const TensorPtrs *ptrs;     // [n_tensors]
     const uint32_t *tile_prefix;    // [n_tensors + 1]
     const uint32_t *fin_prefix;     // [n_tensors + 1]
+    const uint32_t *item_prefix;    // [n_tensors + 1] items of the single-pass path
+    uint32_t *group_counters;       // one arrival counter per (tensor, stripe)
+    uint32_t *error_flag;           // set when a bounded wait expired
     uint8_t *workspace;
     int32_t n_tensors;
 };
@@ -59,6 +77,9 @@ struct LaunchRange {
     int32_t first, count;       // tensors
     uint32_t tile_lo, tile_hi;  // tiles of [first, first+count)
     uint32_t fin_lo, fin_hi;    // finalise blocks
+    uint32_t item_lo, item_hi;  // single-pass items
+    uint32_t group_lo, group_hi;
+    int32_t only_group_scale;   // tiled encode: skip tensors the single-pass kernel covers
 };
 
 enum class Op { Compress, StepFused };
@@ -69,5 +90,10 @@ hipError_t launch_colreduce(const BatchView &v, const LaunchRange &r, int ef, in
 hipError_t launch_finalize(const BatchView &v, const LaunchRange &r, hipStream_t s);
 hipError_t launch_encode(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, bool fused, hipStream_t s);
 hipError_t launch_decode(const BatchView &v, const LaunchRange &r, hipStream_t s);
+
+// Single-pass kernel (channel scales, CF_EF_RECON).  `grid` workgroups must be co-resident.
+int persistent_max_blocks_per_cu(int err_dtype, bool fused);
+hipError_t launch_persistent(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, int grid, hipStream_t s);
+hipError_t launch_zero_counters(const BatchView &v, const LaunchRange &r, hipStream_t s);
 
 }  // namespace cf

@@ -1,0 +1,285 @@
+// Single-pass kernel for channel scales (arxiv 2507.17511, App. D
+// "Quantization": v_j = mean_i |z_ij| needs every token of a channel before
+// any code of that channel can be chosen).
+//
+// A two-kernel design reads x and recon twice from HBM.  Here a workgroup
+// keeps its share of x and recon in registers across the reduction instead:
+//   item  = p_rows x 256 channels of one tensor (128 rows of bf16, 64 of fp32:
+//           128 VGPRs of raw data per lane), owned by one workgroup of 256 lanes
+//           (32 chunks of 8 channels x 8 row-lanes);
+//   group = the items of one 256-channel stripe of one tensor; only they have
+//           to agree on that stripe's scales, so there is no grid-wide barrier:
+//           a group synchronises through one arrival counter, and different
+//           groups drift apart, which keeps HBM busy while some workgroups wait.
+// Per item: load -> |z| tree over the lane's rows -> LDS tree over row-lanes
+// -> publish the item's partial (an aligned power-of-two block of the channel
+// tree) -> arrive -> wait for the group -> every workgroup of the group
+// finishes the tree over the group's partials itself -> scales -> codes,
+// error and reconstruction straight from the registers.
+//
+// The grid is persistent (items are dealt round-robin, group-major), must be
+// co-resident (cooperative launch) and at least as large as the largest group;
+// then the lowest unfinished item's group always has all its items in flight,
+// so every wait ends.  Waits are bounded all the same: on expiry the
+// workgroup raises the error flag and leaves.
+#include "cf_device.h"
+#include "cf_internal.h"
+
+namespace cf {
+namespace {
+
+using namespace dev;
+
+template <bool IS_MAX> __device__ __forceinline__ float comb(float a, float b) { return IS_MAX ? fmaxf(a, b) : a + b; }
+
+__device__ __forceinline__ void publish(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float fetch(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+struct alignas(16) Shared {
+    float red[kRowLanes][kStripeChannels];
+    float scale[kStripeChannels];
+    uint32_t ok;
+};
+
+template <int DT, int BITS, int ET, bool FUSED>
+__device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev &d, const TensorPtrs &p, int stripe,
+                                             int rb, uint32_t *counter, Shared &sh)
+{
+    constexpr int RPT = (DT == BF16) ? 16 : 8;      // rows per lane
+    constexpr bool IS_MAX = BITS == 4;
+    const int tid = (int)threadIdx.x, cl = tid & (kStripeChunks - 1), rl = tid >> 5;
+    const int chunk = stripe * kStripeChunks + cl;
+    const bool cvalid = chunk < d.n_chunks;
+    const int64_t row0 = (int64_t)rb * d.p_rows + rl * RPT;
+    const int64_t C = d.n_channels;
+
+    // ---- load the lane's rows (raw), all in flight at once
+    Raw8<DT> xr[RPT], br[RPT];
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+        const int64_t row = row0 + k;
+        if (cvalid && row < d.n_tokens) {
+            const int64_t e = row * C + (int64_t)chunk * kChunk;
+            xr[k].load(p.x, e);
+            br[k].load(p.recon, e);
+        } else {                                    // zero padding of the tree / masked lanes
+            xr[k].zero();
+            br[k].zero();
+        }
+    }
+
+    // ---- a3, level 1: balanced tree over the lane's RPT consecutive rows
+    // (a binary-counter stack: after row k the slots hold the partial trees of the rows seen so far;
+    // k is a compile-time constant after unrolling, so every branch below folds away)
+    constexpr int LVR = (RPT == 16) ? 5 : 4;
+    F8 st[LVR];
+    const F8 none = {};
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+        F8 z = residual8<EF_RECON>(xr[k].widen(), br[k].widen(), none);
+        F8 a;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a.v[j] = fabsf(z.v[j]);
+        bool carry = true;
+#pragma unroll
+        for (int l = 0; l < LVR; ++l) {
+            if (carry) {
+                if ((k >> l) & 1) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) a.v[j] = comb<IS_MAX>(st[l].v[j], a.v[j]);
+                } else {
+                    st[l] = a;
+                    carry = false;
+                }
+            }
+        }
+    }
+    {
+        const F8 &top = st[LVR - 1];
+        float4 *dst = reinterpret_cast<float4 *>(&sh.red[rl][cl * kChunk]);
+        dst[0] = make_float4(top.v[0], top.v[1], top.v[2], top.v[3]);
+        dst[1] = make_float4(top.v[4], top.v[5], top.v[6], top.v[7]);
+    }
+    __syncthreads();
+
+    // ---- level 2: tree over the 8 row-lanes (consecutive RPT-row blocks); one lane per channel
+    const int64_t col = (int64_t)stripe * kStripeChannels + tid;
+    float *partial = reinterpret_cast<float *>(v.workspace + d.p_partial_off);
+    {
+        float s01 = comb<IS_MAX>(sh.red[0][tid], sh.red[1][tid]), s23 = comb<IS_MAX>(sh.red[2][tid], sh.red[3][tid]);
+        float s45 = comb<IS_MAX>(sh.red[4][tid], sh.red[5][tid]), s67 = comb<IS_MAX>(sh.red[6][tid], sh.red[7][tid]);
+        float item = comb<IS_MAX>(comb<IS_MAX>(s01, s23), comb<IS_MAX>(s45, s67));
+        if (col < C) publish(partial + (int64_t)rb * C + col, item);
+    }
+    __threadfence();
+    __syncthreads();
+
+    // ---- arrive, then wait (bounded) for the rest of the group
+    if (tid == 0) {
+        const uint32_t need = (uint32_t)d.p_n_rb;
+        uint32_t seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+        uint32_t spins = 0;
+        while (seen < need && spins < kSpinLimit) {
+            __builtin_amdgcn_s_sleep(4);
+            seen = __hip_atomic_load(counter, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+            ++spins;
+        }
+        __atomic_thread_fence(__ATOMIC_ACQUIRE);
+        sh.ok = seen >= need ? 1u : 0u;
+        if (seen < need) __hip_atomic_store(v.error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!sh.ok) return false;
+
+    // ---- level 3: the same tree continued over the group's item partials, then the scale
+    if (col < C) {
+        constexpr int LV = 13;                      // groups of up to 4096 items
+        float stack[LV];
+#pragma unroll
+        for (int l = 0; l < LV; ++l) stack[l] = 0.0f;
+        const int n = d.p_n_rb;
+        int npad = 1, lg = 0;
+        while (npad < n) { npad <<= 1; ++lg; }
+        for (int i = 0; i < npad; ++i) {
+            float val = (i < n) ? fetch(partial + (int64_t)i * C + col) : 0.0f;
+            bool carry = true;
+#pragma unroll
+            for (int l = 0; l < LV; ++l) {
+                if (carry) {
+                    if ((i >> l) & 1) {
+                        val = comb<IS_MAX>(stack[l], val);
+                    } else {
+                        stack[l] = val;
+                        carry = false;
+                    }
+                }
+            }
+        }
+        float res = stack[0];
+#pragma unroll
+        for (int l = 1; l < LV; ++l)
+            if (l == lg) res = stack[l];
+        const float s = IS_MAX ? res / 7.0f : res / (float)d.n_tokens;
+        sh.scale[tid] = s;
+        if (rb == 0) p.scales[col] = s;
+    }
+    __syncthreads();
+
+    // ---- a4-a8 from the registers.  z is formed again from the raw operands: keeping the first
+    // phase's fp32 residuals alive across the wait would double the register footprint.
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+        xr[k].opaque();
+        br[k].opaque();
+    }
+    if (cvalid) {
+        F8 s;
+        {
+            const float4 *src = reinterpret_cast<const float4 *>(&sh.scale[cl * kChunk]);
+            float4 a = src[0], b = src[1];
+            s.v[0] = a.x; s.v[1] = a.y; s.v[2] = a.z; s.v[3] = a.w;
+            s.v[4] = b.x; s.v[5] = b.y; s.v[6] = b.z; s.v[7] = b.w;
+        }
+        const int64_t row_bytes = C * BITS / 8;
+#pragma unroll
+        for (int k = 0; k < RPT; ++k) {
+            const int64_t row = row0 + k;
+            __builtin_amdgcn_sched_barrier(0);      // one row at a time: keeps the live set inside the register budget
+            if (row < d.n_tokens) {
+                const int64_t e = row * C + (int64_t)chunk * kChunk;
+                F8 b = br[k].widen();
+                F8 z = residual8<EF_RECON>(xr[k].widen(), b, none);
+                F8 dq;
+                uint32_t packed = quant8<BITS>(z, s, dq);
+                store_codes<BITS>(p.codes + row * row_bytes, chunk, packed);
+                F8 enew;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) enew.v[j] = z.v[j] - dq.v[j];
+                Raw8<ET> eo;
+                eo.narrow(enew);
+                eo.store(p.err, e);
+                if (FUSED) {
+                    F8 nb;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) nb.v[j] = b.v[j] + dq.v[j];
+                    Raw8<DT> out;
+                    out.narrow(nb);
+                    out.store(p.recon, e);
+                }
+            }
+        }
+    }
+    return true;
+}
+
+template <int ET, bool FUSED>
+__global__ __launch_bounds__(kPersistThreads, 2) void k_persistent(BatchView v, LaunchRange r)
+{
+    __shared__ Shared sh;
+    for (uint32_t item = r.item_lo + blockIdx.x; item < r.item_hi; item += gridDim.x) {
+        const int t = find_slot(v.item_prefix, r.first, r.first + r.count, item);
+        const TensorDev &d = v.descs[t];
+        const TensorPtrs &p = v.ptrs[t];
+        const uint32_t local = item - d.p_item_begin;               // group-major: stripe, then row block
+        const int stripe = (int)(local / (uint32_t)d.p_n_rb);
+        const int rb = (int)(local % (uint32_t)d.p_n_rb);
+        uint32_t *counter = v.group_counters + d.p_group_begin + stripe;
+        bool ok;
+        if (d.dtype == BF16) {
+            if (d.bits == 1) ok = persist_item<BF16, 1, ET, FUSED>(v, d, p, stripe, rb, counter, sh);
+            else if (d.bits == 2) ok = persist_item<BF16, 2, ET, FUSED>(v, d, p, stripe, rb, counter, sh);
+            else ok = persist_item<BF16, 4, ET, FUSED>(v, d, p, stripe, rb, counter, sh);
+        } else {
+            if (d.bits == 1) ok = persist_item<F32, 1, ET, FUSED>(v, d, p, stripe, rb, counter, sh);
+            else if (d.bits == 2) ok = persist_item<F32, 2, ET, FUSED>(v, d, p, stripe, rb, counter, sh);
+            else ok = persist_item<F32, 4, ET, FUSED>(v, d, p, stripe, rb, counter, sh);
+        }
+        if (!ok) return;                                            // uniform over the workgroup
+    }
+}
+
+// Group counters start every call at zero (a fill kernel, so the call can be captured in a graph).
+__global__ void k_zero_counters(uint32_t *counters, uint32_t lo, uint32_t hi)
+{
+    for (uint32_t i = lo + blockIdx.x * blockDim.x + threadIdx.x; i < hi; i += gridDim.x * blockDim.x) counters[i] = 0u;
+}
+
+template <int ET, bool FUSED> const void *persistent_fn() { return reinterpret_cast<const void *>(&k_persistent<ET, FUSED>); }
+
+const void *pick(int err_dtype, bool fused)
+{
+    if (err_dtype == BF16) return fused ? persistent_fn<BF16, true>() : persistent_fn<BF16, false>();
+    return fused ? persistent_fn<F32, true>() : persistent_fn<F32, false>();
+}
+
+}  // namespace
+
+int persistent_max_blocks_per_cu(int err_dtype, bool fused)
+{
+    int n = 0;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, pick(err_dtype, fused), kPersistThreads, 0);
+    if (e != hipSuccess) { (void)hipGetLastError(); return 0; }
+    return n;
+}
+
+hipError_t launch_zero_counters(const BatchView &v, const LaunchRange &r, hipStream_t s)
+{
+    if (r.group_hi == r.group_lo) return hipSuccess;
+    uint32_t n = r.group_hi - r.group_lo;
+    hipLaunchKernelGGL(k_zero_counters, dim3((n + 255) / 256 < 64 ? (n + 255) / 256 : 64), dim3(256), 0, s,
+                       v.group_counters, r.group_lo, r.group_hi);
+    return hipGetLastError();
+}
+
+hipError_t launch_persistent(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, int grid, hipStream_t s)
+{
+    if (r.item_hi == r.item_lo) return hipSuccess;
+    uint32_t items = r.item_hi - r.item_lo;
+    if ((uint32_t)grid > items) grid = (int)items;
+    BatchView vv = v;
+    LaunchRange rr = r;
+    void *args[] = {&vv, &rr};
+    return hipLaunchCooperativeKernel(pick(err_dtype, fused), dim3(grid), dim3(kPersistThreads), args, 0, s);
+}
+
+}  // namespace cf

@@ -119,7 +119,7 @@ def run_parity(descs, opts, xs_per_step: List[List[torch.Tensor]], mode: str = "
                 else:
                     sess.compress(xs_per_step[s])
                     sess.decompress()
-                torch.cuda.synchronize()
+                cf.cf_check_device(sess.ctx, sess.stream_handle)     # synchronises; raises if a bounded wait expired
                 list(pool.map(lambda t: orc.step(t, as_numpy(xs_per_step[s][t])), orc.which))
                 for t in orc.which:
                     compare_tensor(f"{tag} step {s}", sess, orc, t)

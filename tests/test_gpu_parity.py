@@ -33,14 +33,18 @@ COMBOS = [(1, CH), (2, CH), (4, CH), (4, GR)]
 @pytest.mark.parametrize("bits,scale", COMBOS)
 @pytest.mark.parametrize("dtype", [cf.CF_BF16, cf.CF_F32])
 @pytest.mark.parametrize("mode", ["fused", "split"])
-def test_parity_shapes(bits, scale, dtype, mode):
+@pytest.mark.parametrize("flags", [0, cf.CF_FLAG_NO_PERSISTENT])
+def test_parity_shapes(bits, scale, dtype, mode, flags):
+    """flags: the single-pass kernel (default) and the separate-kernel path must both match the oracle."""
+    if scale == GR and flags:
+        pytest.skip("group scales never use the single-pass kernel")
     for k, (n, c) in enumerate(SHAPES):
         if scale == GR and c % 128:
             continue
-        say(f"shapes bits={bits} scale={scale} dtype={dtype} mode={mode} N={n} C={c}")
+        say(f"shapes bits={bits} scale={scale} dtype={dtype} mode={mode} flags={flags} N={n} C={c}")
         d = cf.desc(n, c, dtype, bits, scale)
         xs = drift_stream((n, c), dtype, steps=4, seed=100 + k, device=DEV)
-        run_parity([d], cf.options(), [[x] for x in xs], mode=mode, tag=f"N{n}C{c}")
+        run_parity([d], cf.options(flags=flags), [[x] for x in xs], mode=mode, tag=f"N{n}C{c}")
 
 
 @pytest.mark.parametrize("ef", [cf.CF_EF_RECON, cf.CF_EF_LITERAL, cf.CF_EF_OFF])
@@ -78,11 +82,24 @@ def _mixed_batch():
 
 
 @pytest.mark.parametrize("mode", ["fused", "split"])
-def test_parity_batched_mixed_launch(mode):
+@pytest.mark.parametrize("flags", [0, cf.CF_FLAG_NO_PERSISTENT])
+def test_parity_batched_mixed_launch(mode, flags):
     """One call covers tensors of different shapes, dtypes, widths and scale kinds."""
-    say(f"mixed batch mode={mode}")
+    say(f"mixed batch mode={mode} flags={flags}")
     descs, xs = _mixed_batch()
-    run_parity(descs, cf.options(), xs, mode=mode)
+    run_parity(descs, cf.options(flags=flags), xs, mode=mode)
+
+
+def test_single_pass_many_row_blocks_and_stripes():
+    """Reduction groups of many items (N = 1500: 12 row blocks of 128, ragged) over 5 stripes (C = 1096),
+    several tensors deep, so that workgroups take more than one item each."""
+    say("single pass, deep")
+    descs = [cf.desc(1500, 1096, cf.CF_BF16, (1, 2, 4)[t % 3], CH) for t in range(6)]
+    descs += [cf.desc(700, 520, cf.CF_F32, (2, 4, 1)[t % 3], CH) for t in range(3)]
+    streams = [drift_stream((d.n_tokens, d.n_channels), d.dtype, steps=3, seed=70 + k, device=DEV)
+               for k, d in enumerate(descs)]
+    xs = [[streams[t][s] for t in range(len(descs))] for s in range(3)]
+    sess, _ = run_parity(descs, cf.options(), xs, mode="fused")
 
 
 def test_subrange_calls_match_whole_batch():
@@ -300,4 +317,5 @@ def test_configs_reduced(name, shrink):
     xs = [[x.clone() for x in stream.current]]
     for _ in range(1, wl.steps):
         xs.append([x.clone() for x in stream.advance()])
-    run_parity(descs, cf.options(), xs, mode="fused", tag=name)
+    for flags in (0, cf.CF_FLAG_NO_PERSISTENT):
+        run_parity(descs, cf.options(flags=flags), xs, mode="fused", tag=f"{name} flags={flags}")
