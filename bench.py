@@ -40,6 +40,7 @@ def parse_args():
     ap.add_argument("--ef", type=int, default=0, help="cf_ef_mode (0 = RECON)")
     ap.add_argument("--flags", type=int, default=0, help="cf_options.flags")
     ap.add_argument("--tile-rows", type=int, default=0)
+    ap.add_argument("--tensors", type=int, default=0, help="override the workload's tensor count (exploration only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--quiet", action="store_true")
@@ -110,6 +111,8 @@ def run_workload(name: str, args, events: HipEvents | None):
     from workloads import CONFIGS, ActivationStream
 
     wl = CONFIGS[name]
+    if args.tensors:
+        wl = wl.scaled(n_tensors=args.tensors)
     dev = "cuda:0"
     dt = cf.CF_F32 if wl.dtype == "f32" else cf.CF_BF16
     scale = cf.CF_SCALE_GROUP if wl.scale == "group" else cf.CF_SCALE_CHANNEL

@@ -15,7 +15,7 @@ import os
 from typing import Iterable, Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libcompactfusion.so")
+LIB_PATH = os.environ.get("CF_LIBRARY") or os.path.join(_HERE, "libcompactfusion.so")   # override: developer builds
 
 # cf_status
 CF_OK, CF_ERR_INVALID_ARG, CF_ERR_SHAPE, CF_ERR_UNSUPPORTED, CF_ERR_STATE, CF_ERR_WORKSPACE, CF_ERR_DEVICE = range(7)

@@ -49,7 +49,7 @@ cf_status check_opts(const cf_options *o, cf_options &out)
 cf_status check_desc(const cf_tensor_desc &d)
 {
     if (d.n_tokens < 1 || d.n_channels < 8 || d.n_channels % 8 != 0) return CF_ERR_SHAPE;
-    if (d.n_channels > (int64_t)1 << 30 || d.n_tokens > (int64_t)1 << 40) return CF_ERR_SHAPE;
+    if (d.n_channels > (int64_t)1 << 30 || d.n_tokens > (int64_t)1 << 24) return CF_ERR_SHAPE;
     if (d.n_tokens > ((int64_t)1 << 46) / d.n_channels) return CF_ERR_SHAPE;
     if (d.dtype != CF_F32 && d.dtype != CF_BF16) return CF_ERR_UNSUPPORTED;
     if (d.bits != 1 && d.bits != 2 && d.bits != 4) return CF_ERR_UNSUPPORTED;

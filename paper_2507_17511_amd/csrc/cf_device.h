@@ -2,6 +2,9 @@
 // the residual (a1, a2), code selection / packing / decode (a4-a6) and a 16-lane
 // DPP maximum.  All value arithmetic is fp32 with one rounding per operation
 // (translation units including this are compiled with -ffp-contract=off).
+//
+// Memory access goes through global-address-space pointers to native vector
+// types, so that every load and store is a global_* instruction of 128 bits.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -13,6 +16,14 @@ namespace dev {
 constexpr int F32 = 0, BF16 = 1;
 constexpr int SCALE_CHANNEL = 0, SCALE_GROUP = 1;
 constexpr int EF_RECON = 0, EF_LITERAL = 1, EF_OFF = 2;
+
+#define CF_GLOBAL __attribute__((address_space(1)))
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <typename T> __device__ __forceinline__ const CF_GLOBAL T *gconst(const void *p) { return (const CF_GLOBAL T *)p; }
+template <typename T> __device__ __forceinline__ CF_GLOBAL T *gmut(void *p) { return (CF_GLOBAL T *)p; }
 
 // ---------------------------------------------------------------- element formats
 
@@ -31,15 +42,18 @@ struct F8 {
     float v[8];
 };
 
-// Raw 8-element vectors as they sit in memory.
+// Raw 8-element vectors as they sit in memory.  `elem` is an element index from
+// `base`.  load_stream / store_stream mark data that is touched once (they map
+// to the non-temporal forms).
 template <int DT> struct Raw8;
 template <> struct Raw8<BF16> {
-    uint4 w;
-    __device__ __forceinline__ void zero() { w = make_uint4(0, 0, 0, 0); }
+    u32x4 w;
+    __device__ __forceinline__ void zero() { w = (u32x4)(0u); }
+    __device__ __forceinline__ void load(const void *base, int64_t elem) { w = *gconst<u32x4>(static_cast<const uint16_t *>(base) + elem); }
+    __device__ __forceinline__ void load_stream(const void *base, int64_t elem) { w = __builtin_nontemporal_load(gconst<u32x4>(static_cast<const uint16_t *>(base) + elem)); }
+    __device__ __forceinline__ void store(void *base, int64_t elem) const { *gmut<u32x4>(static_cast<uint16_t *>(base) + elem) = w; }
     // Makes the registers opaque to the optimiser: values derived from them earlier are not reused.
-    __device__ __forceinline__ void opaque() { asm volatile("" : "+v"(w.x), "+v"(w.y), "+v"(w.z), "+v"(w.w)); }
-    __device__ __forceinline__ void load(const void *base, int64_t elem) { w = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + elem); }
-    __device__ __forceinline__ void store(void *base, int64_t elem) const { *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(base) + elem) = w; }
+    __device__ __forceinline__ void opaque() { asm volatile("" : "+v"(w)); }
     __device__ __forceinline__ F8 widen() const
     {
         F8 f;
@@ -58,24 +72,30 @@ template <> struct Raw8<BF16> {
     }
 };
 template <> struct Raw8<F32> {
-    float4 a, b;
-    __device__ __forceinline__ void zero() { a = make_float4(0, 0, 0, 0); b = a; }
-    __device__ __forceinline__ void opaque()
-    {
-        asm volatile("" : "+v"(a.x), "+v"(a.y), "+v"(a.z), "+v"(a.w));
-        asm volatile("" : "+v"(b.x), "+v"(b.y), "+v"(b.z), "+v"(b.w));
-    }
+    f32x4 a, b;
+    __device__ __forceinline__ void zero() { a = (f32x4)(0.0f); b = a; }
     __device__ __forceinline__ void load(const void *base, int64_t elem)
     {
-        const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(base) + elem);
+        const CF_GLOBAL f32x4 *p = gconst<f32x4>(static_cast<const float *>(base) + elem);
         a = p[0];
         b = p[1];
     }
+    __device__ __forceinline__ void load_stream(const void *base, int64_t elem)
+    {
+        const CF_GLOBAL f32x4 *p = gconst<f32x4>(static_cast<const float *>(base) + elem);
+        a = __builtin_nontemporal_load(p);
+        b = __builtin_nontemporal_load(p + 1);
+    }
     __device__ __forceinline__ void store(void *base, int64_t elem) const
     {
-        float4 *p = reinterpret_cast<float4 *>(static_cast<float *>(base) + elem);
+        CF_GLOBAL f32x4 *p = gmut<f32x4>(static_cast<float *>(base) + elem);
         p[0] = a;
         p[1] = b;
+    }
+    __device__ __forceinline__ void opaque()
+    {
+        asm volatile("" : "+v"(a));
+        asm volatile("" : "+v"(b));
     }
     __device__ __forceinline__ F8 widen() const
     {
@@ -86,8 +106,8 @@ template <> struct Raw8<F32> {
     }
     __device__ __forceinline__ void narrow(const F8 &f)
     {
-        a = make_float4(f.v[0], f.v[1], f.v[2], f.v[3]);
-        b = make_float4(f.v[4], f.v[5], f.v[6], f.v[7]);
+        a.x = f.v[0]; a.y = f.v[1]; a.z = f.v[2]; a.w = f.v[3];
+        b.x = f.v[4]; b.y = f.v[5]; b.z = f.v[6]; b.w = f.v[7];
     }
 };
 
@@ -160,18 +180,26 @@ __device__ __forceinline__ void dequant8(uint32_t packed, const F8 &s, F8 &d)
     }
 }
 
+// `row` points at the first code byte of the token; a lane owns `BITS` bytes of it.
 template <int BITS> __device__ __forceinline__ void store_codes(uint8_t *row, int chunk, uint32_t packed)
 {
-    if (BITS == 1) row[chunk] = (uint8_t)packed;
-    else if (BITS == 2) reinterpret_cast<uint16_t *>(row)[chunk] = (uint16_t)packed;
-    else reinterpret_cast<uint32_t *>(row)[chunk] = packed;
+    if (BITS == 1) gmut<uint8_t>(row)[chunk] = (uint8_t)packed;
+    else if (BITS == 2) gmut<uint16_t>(row)[chunk] = (uint16_t)packed;
+    else gmut<uint32_t>(row)[chunk] = packed;
 }
 
 template <int BITS> __device__ __forceinline__ uint32_t load_codes(const uint8_t *row, int chunk)
 {
-    if (BITS == 1) return row[chunk];
-    if (BITS == 2) return reinterpret_cast<const uint16_t *>(row)[chunk];
-    return reinterpret_cast<const uint32_t *>(row)[chunk];
+    if (BITS == 1) return gconst<uint8_t>(row)[chunk];
+    if (BITS == 2) return gconst<uint16_t>(row)[chunk];
+    return gconst<uint32_t>(row)[chunk];
+}
+
+__device__ __forceinline__ F8 load_scales8(const float *scales, int64_t first)
+{
+    Raw8<F32> r;
+    r.load(scales, first);
+    return r.widen();
 }
 
 // Max over the 16 lanes of a DPP row (16 lanes x 8 channels = one group of 128).
@@ -190,6 +218,69 @@ __device__ __forceinline__ float row16_max(float m)
     return m;
 }
 
+template <bool IS_MAX> __device__ __forceinline__ float comb(float a, float b) { return IS_MAX ? fmaxf(a, b) : a + b; }
+
+// Balanced binary tree over values pushed in index order 0, 1, 2, ...: slot l of
+// the stack holds the tree over an aligned block of 2^l indices.  After 2^k
+// pushes the total is in slot k and every other slot is empty (+0).  Every slot
+// is addressed statically.
+template <int LV, bool IS_MAX>
+__device__ __forceinline__ void tree_push(float (&stack)[LV], float val, int index, bool active = true)
+{
+    // Written with selects, not branches: the slots must stay in registers.
+    bool carry = active;
+#pragma unroll
+    for (int l = 0; l < LV; ++l) {
+        const bool bit = (index >> l) & 1;
+        const float merged = comb<IS_MAX>(stack[l], val);
+        stack[l] = carry ? (bit ? 0.0f : val) : stack[l];     // a merged slot is emptied (+0)
+        val = (carry && bit) ? merged : val;
+        carry = carry && bit;
+    }
+}
+
+// After a power-of-two number of pushes exactly one slot is occupied and the
+// others hold +0, so combining all slots (in any order) returns the total
+// unchanged: adding +0, or taking the maximum with +0, is exact for the
+// non-negative values reduced here.
+template <int LV, bool IS_MAX> __device__ __forceinline__ float tree_top(const float (&stack)[LV])
+{
+    float res = stack[0];
+#pragma unroll
+    for (int l = 1; l < LV; ++l) res = comb<IS_MAX>(res, stack[l]);
+    return res;
+}
+
+// Tree sum (or max) over n values `fetch(i)`, i = 0..n-1, zero padded to a power of
+// two.  Values are taken in aligned batches of 16 whose loads are issued
+// together; a batch is reduced as a 16-leaf tree in registers and the batch
+// results go through the stack (n <= 16 * 2^(LV-1)).  Padding is +0, which
+// leaves sums and maxima of non-negative values unchanged, so a short last
+// batch or n < 16 gives exactly the tree over the padded range.
+template <bool IS_MAX, int LV, class Fetch>
+__device__ __forceinline__ float tree_over(int n, Fetch fetch)
+{
+    constexpr int NB = 16;
+    float stack[LV];
+#pragma unroll
+    for (int l = 0; l < LV; ++l) stack[l] = 0.0f;
+    const int nbatch = (n + NB - 1) / NB;
+    int bpad = 1;
+    while (bpad < nbatch) bpad <<= 1;
+    for (int b = 0; b < bpad; ++b) {             // batches past the last are all padding (+0)
+        float vals[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) vals[u] = (b * NB + u < n) ? fetch(b * NB + u) : 0.0f;
+        float p2[8], p4[4];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) p2[u] = comb<IS_MAX>(vals[2 * u], vals[2 * u + 1]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) p4[u] = comb<IS_MAX>(p2[2 * u], p2[2 * u + 1]);
+        const float lo8 = comb<IS_MAX>(p4[0], p4[1]), hi8 = comb<IS_MAX>(p4[2], p4[3]);
+        tree_push<LV, IS_MAX>(stack, comb<IS_MAX>(lo8, hi8), b);
+    }
+    return tree_top<LV, IS_MAX>(stack);
+}
 
 // Largest t in [lo, hi) with prefix[t] <= id.
 __device__ __forceinline__ int find_slot(const uint32_t *prefix, int lo, int hi, uint32_t id)

@@ -9,7 +9,9 @@
 // channels; lane l owns channels [8l, 8l+8) of the tile (one 128-bit bf16
 // load per row), so a wave reads 1 KiB of contiguous row per instruction.
 // A batched grid covers the tiles of many tensors; a workgroup finds its
-// tensor by binary search in a prefix array of tile counts.
+// tensor by binary search in a prefix array of tile counts.  Each workgroup
+// copies its tensor's descriptor and pointers into registers once: nothing is
+// re-read from the tables after a store.
 #include "cf_device.h"
 #include "cf_internal.h"
 
@@ -21,8 +23,8 @@ using namespace dev;
 // ---------------------------------------------------------------- tile lookup
 
 struct TileCtx {
-    const TensorDev *d;
-    const TensorPtrs *p;
+    TensorDev d;        // by value: lives in scalar registers
+    TensorPtrs p;
     int rowblock, colblock;
 };
 
@@ -31,11 +33,11 @@ __device__ __forceinline__ TileCtx locate_tile(const BatchView &v, const LaunchR
     uint32_t tile = r.tile_lo + blockIdx.x;
     int t = find_slot(v.tile_prefix, r.first, r.first + r.count, tile);
     TileCtx c;
-    c.d = v.descs + t;
-    c.p = v.ptrs + t;
-    uint32_t local = tile - c.d->tile_begin;
-    c.colblock = (int)(local % (uint32_t)c.d->n_colblocks);
-    c.rowblock = (int)(local / (uint32_t)c.d->n_colblocks);
+    c.d = v.descs[t];
+    c.p = v.ptrs[t];
+    uint32_t local = tile - c.d.tile_begin;
+    c.colblock = (int)(local % (uint32_t)c.d.n_colblocks);
+    c.rowblock = (int)(local / (uint32_t)c.d.n_colblocks);
     return c;
 }
 
@@ -44,19 +46,26 @@ __device__ __forceinline__ TileCtx locate_tile(const BatchView &v, const LaunchR
 template <int DT, int ET>
 __device__ __forceinline__ void warmup_tile(const TileCtx &c)
 {
-    const TensorDev &d = *c.d;
+    const TensorDev &d = c.d;
     int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
     if (chunk >= d.n_chunks) return;
     int64_t row0 = (int64_t)c.rowblock * d.rb_rows;
     int64_t row1 = row0 + d.rb_rows < d.n_tokens ? row0 + d.rb_rows : d.n_tokens;
-    for (int64_t i = row0; i < row1; ++i) {
-        int64_t e = i * d.n_channels + (int64_t)chunk * kChunk;
-        Raw8<DT> x;
-        x.load(c.p->x, e);
-        x.store(c.p->recon, e);
-        Raw8<ET> zero;
-        zero.zero();
-        zero.store(c.p->err, e);
+    constexpr int U = 4;
+    for (int64_t i0 = row0; i0 < row1; i0 += U) {
+        Raw8<DT> x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (i0 + u < row1) x[u].load_stream(c.p.x, (i0 + u) * d.n_channels + (int64_t)chunk * kChunk);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (i0 + u >= row1) break;
+            int64_t e = (i0 + u) * d.n_channels + (int64_t)chunk * kChunk;
+            x[u].store(c.p.recon, e);
+            Raw8<ET> zero;
+            zero.zero();
+            zero.store(c.p.err, e);
+        }
     }
 }
 
@@ -64,12 +73,10 @@ template <int ET>
 __global__ __launch_bounds__(kTileThreads) void k_warmup(BatchView v, LaunchRange r)
 {
     TileCtx c = locate_tile(v, r);
-    if (c.d->dtype == BF16) warmup_tile<BF16, ET>(c); else warmup_tile<F32, ET>(c);
+    if (c.d.dtype == BF16) warmup_tile<BF16, ET>(c); else warmup_tile<F32, ET>(c);
 }
 
 // ---------------------------------------------------------------- a3, first level: per-tile column partials
-
-template <bool IS_MAX> __device__ __forceinline__ float comb(float a, float b) { return IS_MAX ? fmaxf(a, b) : a + b; }
 
 // |z| of 8 consecutive rows, combined as a balanced tree:
 // ((r0+r1)+(r2+r3)) + ((r4+r5)+(r6+r7)).  Rows past the end count as +0, which
@@ -114,7 +121,7 @@ __device__ __forceinline__ F8 rows8(const TensorDev &d, const TensorPtrs &p, int
 template <int DT, int EF, int ET, bool IS_MAX>
 __device__ __forceinline__ void colreduce_tile(const TileCtx &c, uint8_t *ws)
 {
-    const TensorDev &d = *c.d;
+    const TensorDev &d = c.d;
     int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
     if (chunk >= d.n_chunks) return;
     int64_t row = (int64_t)c.rowblock * d.rb_rows;
@@ -130,7 +137,7 @@ __device__ __forceinline__ void colreduce_tile(const TileCtx &c, uint8_t *ws)
         for (int h1 = 0; h1 < n1; ++h1) {
 #pragma unroll 1
             for (int h0 = 0; h0 < n0; ++h0) {
-                F8 t = rows8<DT, EF, ET, IS_MAX>(d, *c.p, chunk, row);
+                F8 t = rows8<DT, EF, ET, IS_MAX>(d, c.p, chunk, row);
                 row += 8;
 #pragma unroll
                 for (int k = 0; k < 8; ++k) s0.v[k] = (h0 == 0) ? t.v[k] : comb<IS_MAX>(s0.v[k], t.v[k]);
@@ -151,7 +158,7 @@ template <int EF, int ET>
 __global__ __launch_bounds__(kTileThreads) void k_colreduce(BatchView v, LaunchRange r)
 {
     TileCtx c = locate_tile(v, r);
-    const TensorDev &d = *c.d;
+    const TensorDev &d = c.d;
     if (d.scale != SCALE_CHANNEL) return;
     if (d.dtype == BF16) {
         if (d.bits == 4) colreduce_tile<BF16, EF, ET, true>(c, v.workspace);
@@ -170,69 +177,42 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_finalize(BatchView v, Laun
 {
     uint32_t blk = r.fin_lo + blockIdx.x;
     int t = find_slot(v.fin_prefix, r.first, r.first + r.count, blk);
-    const TensorDev &d = v.descs[t];
+    const TensorDev d = v.descs[t];
     if (d.scale != SCALE_CHANNEL) return;
     int col = (int)(blk - d.fin_begin) * kFinalizeThreads + (int)threadIdx.x;
     if (col >= d.n_channels) return;
-    const float *partial = reinterpret_cast<const float *>(v.workspace + d.partial_off) + col;
-    const bool is_max = d.bits == 4;
-    constexpr int LV = 26;
-    float stack[LV];
-#pragma unroll
-    for (int l = 0; l < LV; ++l) stack[l] = 0.0f;
-    int n = d.n_rowblocks, npad = 1, lg = 0;
-    while (npad < n) { npad <<= 1; ++lg; }
-    for (int i = 0; i < npad; ++i) {
-        float val = (i < n) ? partial[(int64_t)i * d.n_channels] : 0.0f;
-        bool carry = true;
-#pragma unroll
-        for (int l = 0; l < LV; ++l) {
-            if (carry) {
-                if ((i >> l) & 1) {
-                    val = is_max ? fmaxf(stack[l], val) : stack[l] + val;
-                } else {
-                    stack[l] = val;
-                    carry = false;
-                }
-            }
-        }
+    const CF_GLOBAL float *partial = gconst<float>(v.workspace + d.partial_off) + col;
+    const int64_t C = d.n_channels;
+    float res, s;
+    if (d.bits == 4) {
+        res = tree_over<true, 18>(d.n_rowblocks, [&](int i) { return partial[(int64_t)i * C]; });
+        s = res / 7.0f;
+    } else {
+        res = tree_over<false, 18>(d.n_rowblocks, [&](int i) { return partial[(int64_t)i * C]; });
+        s = res / (float)d.n_tokens;
     }
-    float res = stack[0];
-#pragma unroll
-    for (int l = 1; l < LV; ++l)
-        if (l == lg) res = stack[l];
-    float s = is_max ? res / 7.0f : res / (float)d.n_tokens;
-    v.ptrs[t].scales[col] = s;
+    gmut<float>(v.ptrs[t].scales)[col] = s;
 }
 
 // ---------------------------------------------------------------- a4-a8: encode (+ fused state update)
-
-template <int ET> __device__ __forceinline__ void store_err(void *err, int64_t e, const F8 &val)
-{
-    Raw8<ET> out;
-    out.narrow(val);
-    out.store(err, e);
-}
 
 // MODE: 0 = channel scales read from memory, 1 = group scales computed in the wave.
 template <int DT, int BITS, int MODE, int EF, int ET, bool FUSED>
 __device__ __forceinline__ void encode_tile(const TileCtx &c)
 {
-    const TensorDev &d = *c.d;
+    const TensorDev &d = c.d;
+    const TensorPtrs &p = c.p;
     int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
     const bool cvalid = chunk < d.n_chunks;
     if (MODE == 0 && !cvalid) return;           // group mode keeps every lane alive for the DPP reduction
     int64_t row0 = (int64_t)c.rowblock * d.rb_rows;
     int64_t row1 = row0 + d.rb_rows < d.n_tokens ? row0 + d.rb_rows : d.n_tokens;
-    const int64_t row_bytes = (int64_t)d.n_channels * BITS / 8;
+    const int64_t C = d.n_channels;
+    const int64_t row_bytes = C * BITS / 8;
     const int n_groups = d.n_channels >> 7;
 
     F8 s;
-    if (MODE == 0) {
-        Raw8<F32> sr;
-        sr.load(c.p->scales, (int64_t)chunk * kChunk);
-        s = sr.widen();
-    }
+    if (MODE == 0) s = load_scales8(p.scales, (int64_t)chunk * kChunk);
 
     constexpr int U = 4;
     for (int64_t i0 = row0; i0 < row1; i0 += U) {
@@ -242,10 +222,10 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
         for (int u = 0; u < U; ++u) {
             int64_t i = i0 + u;
             if (i < row1 && cvalid) {
-                int64_t e = i * d.n_channels + (int64_t)chunk * kChunk;
-                xr[u].load(c.p->x, e);
-                br[u].load(c.p->recon, e);
-                if (EF != EF_RECON) er[u].load(c.p->err, e); else er[u].zero();
+                int64_t e = i * C + (int64_t)chunk * kChunk;
+                xr[u].load_stream(p.x, e);      // last use of x
+                br[u].load(p.recon, e);
+                if (EF != EF_RECON) er[u].load(p.err, e); else er[u].zero();
             } else {
                 xr[u].zero();
                 br[u].zero();
@@ -267,13 +247,13 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
                 float sg = m / 7.0f;
 #pragma unroll
                 for (int k = 0; k < 8; ++k) s.v[k] = sg;
-                if (cvalid && (threadIdx.x & 15) == 0) c.p->scales[i * n_groups + (chunk >> 4)] = sg;
+                if (cvalid && (threadIdx.x & 15) == 0) gmut<float>(p.scales)[i * n_groups + (chunk >> 4)] = sg;
             }
             if (!cvalid) continue;
             F8 dq;
             uint32_t packed = quant8<BITS>(z, s, dq);
-            store_codes<BITS>(c.p->codes + i * row_bytes, chunk, packed);
-            int64_t e = i * d.n_channels + (int64_t)chunk * kChunk;
+            store_codes<BITS>(p.codes + i * row_bytes, chunk, packed);
+            int64_t e = i * C + (int64_t)chunk * kChunk;
             F8 enew;
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
@@ -281,14 +261,16 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
                 if (EF == EF_OFF) lost = eold.v[k] + lost;
                 enew.v[k] = lost;
             }
-            store_err<ET>(c.p->err, e, enew);
+            Raw8<ET> eo;
+            eo.narrow(enew);
+            eo.store(p.err, e);
             if (FUSED) {
                 F8 nb;
 #pragma unroll
                 for (int k = 0; k < 8; ++k) nb.v[k] = b.v[k] + dq.v[k];
                 Raw8<DT> out;
                 out.narrow(nb);
-                out.store(c.p->recon, e);
+                out.store(p.recon, e);
             }
         }
     }
@@ -297,7 +279,7 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
 template <int DT, int EF, int ET, bool FUSED>
 __device__ __forceinline__ void encode_dispatch(const TileCtx &c)
 {
-    const TensorDev &d = *c.d;
+    const TensorDev &d = c.d;
     if (d.scale == SCALE_GROUP) { encode_tile<DT, 4, 1, EF, ET, FUSED>(c); return; }
     if (d.bits == 1) encode_tile<DT, 1, 0, EF, ET, FUSED>(c);
     else if (d.bits == 2) encode_tile<DT, 2, 0, EF, ET, FUSED>(c);
@@ -308,8 +290,8 @@ template <int EF, int ET, bool FUSED>
 __global__ __launch_bounds__(kTileThreads) void k_encode(BatchView v, LaunchRange r)
 {
     TileCtx c = locate_tile(v, r);
-    if (r.only_group_scale && c.d->scale != SCALE_GROUP) return;    // covered by the single-pass kernel
-    if (c.d->dtype == BF16) encode_dispatch<BF16, EF, ET, FUSED>(c);
+    if (r.only_group_scale && c.d.scale != SCALE_GROUP) return;     // covered by the single-pass kernel
+    if (c.d.dtype == BF16) encode_dispatch<BF16, EF, ET, FUSED>(c);
     else encode_dispatch<F32, EF, ET, FUSED>(c);
 }
 
@@ -318,19 +300,17 @@ __global__ __launch_bounds__(kTileThreads) void k_encode(BatchView v, LaunchRang
 template <int DT, int BITS, int MODE>
 __device__ __forceinline__ void decode_tile(const TileCtx &c)
 {
-    const TensorDev &d = *c.d;
+    const TensorDev &d = c.d;
+    const TensorPtrs &p = c.p;
     int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
     if (chunk >= d.n_chunks) return;
     int64_t row0 = (int64_t)c.rowblock * d.rb_rows;
     int64_t row1 = row0 + d.rb_rows < d.n_tokens ? row0 + d.rb_rows : d.n_tokens;
-    const int64_t row_bytes = (int64_t)d.n_channels * BITS / 8;
+    const int64_t C = d.n_channels;
+    const int64_t row_bytes = C * BITS / 8;
     const int n_groups = d.n_channels >> 7;
     F8 s;
-    if (MODE == 0) {
-        Raw8<F32> sr;
-        sr.load(c.p->scales, (int64_t)chunk * kChunk);
-        s = sr.widen();
-    }
+    if (MODE == 0) s = load_scales8(p.scales, (int64_t)chunk * kChunk);
     constexpr int U = 4;
     for (int64_t i0 = row0; i0 < row1; i0 += U) {
         Raw8<DT> br[U];
@@ -340,9 +320,9 @@ __device__ __forceinline__ void decode_tile(const TileCtx &c)
         for (int u = 0; u < U; ++u) {
             int64_t i = i0 + u;
             if (i < row1) {
-                br[u].load(c.p->recon, i * d.n_channels + (int64_t)chunk * kChunk);
-                pk[u] = load_codes<BITS>(c.p->codes + i * row_bytes, chunk);
-                sg[u] = (MODE == 1) ? c.p->scales[i * n_groups + (chunk >> 4)] : 0.0f;
+                br[u].load(p.recon, i * C + (int64_t)chunk * kChunk);
+                pk[u] = load_codes<BITS>(p.codes + i * row_bytes, chunk);
+                sg[u] = (MODE == 1) ? gconst<float>(p.scales)[i * n_groups + (chunk >> 4)] : 0.0f;
             } else {
                 br[u].zero();
                 pk[u] = 0;
@@ -363,14 +343,14 @@ __device__ __forceinline__ void decode_tile(const TileCtx &c)
             for (int k = 0; k < 8; ++k) nb.v[k] = b.v[k] + dq.v[k];
             Raw8<DT> out;
             out.narrow(nb);
-            out.store(c.p->recon, i * d.n_channels + (int64_t)chunk * kChunk);
+            out.store(p.recon, i * C + (int64_t)chunk * kChunk);
         }
     }
 }
 
 template <int DT> __device__ __forceinline__ void decode_dispatch(const TileCtx &c)
 {
-    const TensorDev &d = *c.d;
+    const TensorDev &d = c.d;
     if (d.scale == SCALE_GROUP) { decode_tile<DT, 4, 1>(c); return; }
     if (d.bits == 1) decode_tile<DT, 1, 0>(c);
     else if (d.bits == 2) decode_tile<DT, 2, 0>(c);
@@ -380,7 +360,7 @@ template <int DT> __device__ __forceinline__ void decode_dispatch(const TileCtx 
 __global__ __launch_bounds__(kTileThreads) void k_decode(BatchView v, LaunchRange r)
 {
     TileCtx c = locate_tile(v, r);
-    if (c.d->dtype == BF16) decode_dispatch<BF16>(c); else decode_dispatch<F32>(c);
+    if (c.d.dtype == BF16) decode_dispatch<BF16>(c); else decode_dispatch<F32>(c);
 }
 
 // ---------------------------------------------------------------- pointer table upload

@@ -30,8 +30,6 @@ namespace {
 
 using namespace dev;
 
-template <bool IS_MAX> __device__ __forceinline__ float comb(float a, float b) { return IS_MAX ? fmaxf(a, b) : a + b; }
-
 __device__ __forceinline__ void publish(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ float fetch(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
@@ -60,7 +58,7 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
         const int64_t row = row0 + k;
         if (cvalid && row < d.n_tokens) {
             const int64_t e = row * C + (int64_t)chunk * kChunk;
-            xr[k].load(p.x, e);
+            xr[k].load_stream(p.x, e);              // x is read exactly once
             br[k].load(p.recon, e);
         } else {                                    // zero padding of the tree / masked lanes
             xr[k].zero();
@@ -96,9 +94,12 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
     }
     {
         const F8 &top = st[LVR - 1];
-        float4 *dst = reinterpret_cast<float4 *>(&sh.red[rl][cl * kChunk]);
-        dst[0] = make_float4(top.v[0], top.v[1], top.v[2], top.v[3]);
-        dst[1] = make_float4(top.v[4], top.v[5], top.v[6], top.v[7]);
+        f32x4 *dst = reinterpret_cast<f32x4 *>(&sh.red[rl][cl * kChunk]);
+        f32x4 lo, hi;
+        lo.x = top.v[0]; lo.y = top.v[1]; lo.z = top.v[2]; lo.w = top.v[3];
+        hi.x = top.v[4]; hi.y = top.v[5]; hi.z = top.v[6]; hi.w = top.v[7];
+        dst[0] = lo;
+        dst[1] = hi;
     }
     __syncthreads();
 
@@ -111,20 +112,22 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
         float item = comb<IS_MAX>(comb<IS_MAX>(s01, s23), comb<IS_MAX>(s45, s67));
         if (col < C) publish(partial + (int64_t)rb * C + col, item);
     }
-    __threadfence();
+    // The partials were stored with agent-scope atomic stores (written through to where the other
+    // XCDs read them), and the barrier below drains them; so the arrival needs no cache write-back,
+    // which would also flush every output line this CU's L2 still holds.
+    __builtin_amdgcn_s_waitcnt(0);                  // this lane's stores have completed
     __syncthreads();
 
     // ---- arrive, then wait (bounded) for the rest of the group
     if (tid == 0) {
         const uint32_t need = (uint32_t)d.p_n_rb;
-        uint32_t seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+        uint32_t seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
         uint32_t spins = 0;
         while (seen < need && spins < kSpinLimit) {
-            __builtin_amdgcn_s_sleep(4);
-            seen = __hip_atomic_load(counter, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_s_sleep(2);
+            seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             ++spins;
         }
-        __atomic_thread_fence(__ATOMIC_ACQUIRE);
         sh.ok = seen >= need ? 1u : 0u;
         if (seen < need) __hip_atomic_store(v.error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -133,35 +136,11 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
 
     // ---- level 3: the same tree continued over the group's item partials, then the scale
     if (col < C) {
-        constexpr int LV = 13;                      // groups of up to 4096 items
-        float stack[LV];
-#pragma unroll
-        for (int l = 0; l < LV; ++l) stack[l] = 0.0f;
-        const int n = d.p_n_rb;
-        int npad = 1, lg = 0;
-        while (npad < n) { npad <<= 1; ++lg; }
-        for (int i = 0; i < npad; ++i) {
-            float val = (i < n) ? fetch(partial + (int64_t)i * C + col) : 0.0f;
-            bool carry = true;
-#pragma unroll
-            for (int l = 0; l < LV; ++l) {
-                if (carry) {
-                    if ((i >> l) & 1) {
-                        val = comb<IS_MAX>(stack[l], val);
-                    } else {
-                        stack[l] = val;
-                        carry = false;
-                    }
-                }
-            }
-        }
-        float res = stack[0];
-#pragma unroll
-        for (int l = 1; l < LV; ++l)
-            if (l == lg) res = stack[l];
+        const float *mine = partial + col;
+        const float res = tree_over<IS_MAX, 9>(d.p_n_rb, [&](int i) { return fetch(mine + (int64_t)i * C); });
         const float s = IS_MAX ? res / 7.0f : res / (float)d.n_tokens;
         sh.scale[tid] = s;
-        if (rb == 0) p.scales[col] = s;
+        if (rb == 0) gmut<float>(p.scales)[col] = s;
     }
     __syncthreads();
 
@@ -175,8 +154,8 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
     if (cvalid) {
         F8 s;
         {
-            const float4 *src = reinterpret_cast<const float4 *>(&sh.scale[cl * kChunk]);
-            float4 a = src[0], b = src[1];
+            const f32x4 *src = reinterpret_cast<const f32x4 *>(&sh.scale[cl * kChunk]);
+            f32x4 a = src[0], b = src[1];
             s.v[0] = a.x; s.v[1] = a.y; s.v[2] = a.z; s.v[3] = a.w;
             s.v[4] = b.x; s.v[5] = b.y; s.v[6] = b.z; s.v[7] = b.w;
         }
@@ -218,8 +197,8 @@ __global__ __launch_bounds__(kPersistThreads, 2) void k_persistent(BatchView v, 
     __shared__ Shared sh;
     for (uint32_t item = r.item_lo + blockIdx.x; item < r.item_hi; item += gridDim.x) {
         const int t = find_slot(v.item_prefix, r.first, r.first + r.count, item);
-        const TensorDev &d = v.descs[t];
-        const TensorPtrs &p = v.ptrs[t];
+        const TensorDev d = v.descs[t];                             // by value: scalar registers, never re-read
+        const TensorPtrs p = v.ptrs[t];
         const uint32_t local = item - d.p_item_begin;               // group-major: stripe, then row block
         const int stripe = (int)(local / (uint32_t)d.p_n_rb);
         const int rb = (int)(local % (uint32_t)d.p_n_rb);
