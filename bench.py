@@ -40,7 +40,9 @@ def parse_args():
     ap.add_argument("--ef", type=int, default=0, help="cf_ef_mode (0 = RECON)")
     ap.add_argument("--flags", type=int, default=0, help="cf_options.flags")
     ap.add_argument("--tile-rows", type=int, default=0)
+    ap.add_argument("--encode-rows", type=int, default=0)
     ap.add_argument("--tensors", type=int, default=0, help="override the workload's tensor count (exploration only)")
+    ap.add_argument("--sub-batch", type=int, default=0, help="issue the step as calls over ranges of this many tensors (exploration only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--quiet", action="store_true")
@@ -117,7 +119,7 @@ def run_workload(name: str, args, events: HipEvents | None):
     dt = cf.CF_F32 if wl.dtype == "f32" else cf.CF_BF16
     scale = cf.CF_SCALE_GROUP if wl.scale == "group" else cf.CF_SCALE_CHANNEL
     descs = [cf.desc(wl.n_tokens, wl.n_channels, dt, wl.bits_of(t), scale, wl.group) for t in range(wl.n_tensors)]
-    opts = cf.options(ef=args.ef, flags=args.flags, tile_rows=args.tile_rows)
+    opts = cf.options(ef=args.ef, flags=args.flags, tile_rows=args.tile_rows, encode_rows=args.encode_rows)
 
     t0 = time.time()
     stream = ActivationStream(wl, device=dev)
@@ -135,7 +137,19 @@ def run_workload(name: str, args, events: HipEvents | None):
     p_ring = [cf.ptr_array(xs) for xs in ring]
     order = list(range(R)) + list(range(R - 2, 0, -1))      # 0 1 2 3 2 1 | 0 1 ...
 
+    sub = args.sub_batch
+    if sub:
+        def sl(arr, lo, hi):
+            return cf.ptr_array([arr[i] for i in range(lo, hi)])
+        ranges = [(lo, min(lo + sub, sess.n)) for lo in range(0, sess.n, sub)]
+        sub_ptrs = [[(lo, hi - lo, sl(pr, lo, hi), sl(sess.p_recon, lo, hi), sl(sess.p_err, lo, hi),
+                      sl(sess.p_codes, lo, hi), sl(sess.p_scales, lo, hi)) for lo, hi in ranges] for pr in p_ring]
+
     def step(k):
+        if sub:
+            for lo, cnt, px, pr, pe, pc, ps in sub_ptrs[order[k % len(order)]]:
+                cf.cf_step_fused(sess.ctx, lo, cnt, px, pr, pe, pc, ps, sess.stream_handle)
+            return
         cf.cf_step_fused(sess.ctx, 0, sess.n, p_ring[order[k % len(order)]], sess.p_recon, sess.p_err,
                          sess.p_codes, sess.p_scales, sess.stream_handle)
 

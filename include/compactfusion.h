@@ -100,13 +100,19 @@ typedef struct {
     int32_t ef;        /* cf_ef_mode */
     int32_t err_dtype; /* cf_dtype of every error buffer; CF_F32 by default */
     uint32_t flags;    /* CF_FLAG_* */
-    int32_t tile_rows; /* rows per workgroup tile: 0 = chosen by the library, else 8, 16, 32 or 64
-                          (a tuning knob: results do not depend on it) */
+    int32_t tile_rows; /* rows per workgroup tile of the scale reduction: 0 = chosen by the library,
+                          else 8, 16, 32 or 64 (a tuning knob: results do not depend on it) */
+    int32_t encode_rows; /* rows per workgroup of the element-wise kernels: 0 = chosen by the
+                            library, else 1..64 (a tuning knob as well) */
 } cf_options;
 
-/* Use only the separate-kernel path (scale reduction, finalise, encode) and
- * never the single persistent kernel.  Results are bit-identical either way. */
-#define CF_FLAG_NO_PERSISTENT 0x1u
+/* Channel scales are normally reduced by one kernel and the codes written by
+ * a second one, which reads x and recon again.  With this flag (CF_EF_RECON
+ * only) a single persistent kernel keeps them in registers across the
+ * reduction instead: half the reads, but workgroups wait for each other.
+ * Results are bit-identical either way; the two-kernel path is the faster one
+ * on MI355X as measured so far. */
+#define CF_FLAG_SINGLE_PASS 0x1u
 
 /* Byte sizes of one tensor's buffers.  Any output pointer may be NULL.
  * CF_ERR_SHAPE / CF_ERR_UNSUPPORTED as for cf_init. */

@@ -25,7 +25,7 @@ CF_F32, CF_BF16 = 0, 1
 CF_SCALE_CHANNEL, CF_SCALE_GROUP, CF_SCALE_RANK1 = 0, 1, 2
 # cf_ef_mode
 CF_EF_RECON, CF_EF_LITERAL, CF_EF_OFF = 0, 1, 2
-CF_FLAG_NO_PERSISTENT = 0x1
+CF_FLAG_SINGLE_PASS = 0x1
 
 EXPORTS = ["cf_sizes", "cf_workspace_bytes", "cf_init", "cf_warmup", "cf_set_warm", "cf_compress",
            "cf_decompress", "cf_step_fused", "cf_destroy", "cf_status_string", "cf_last_hip_error",
@@ -39,7 +39,7 @@ class cf_tensor_desc(ctypes.Structure):
 
 class cf_options(ctypes.Structure):
     _fields_ = [("ef", ctypes.c_int32), ("err_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
-                ("tile_rows", ctypes.c_int32)]
+                ("tile_rows", ctypes.c_int32), ("encode_rows", ctypes.c_int32)]
 
 
 class CFError(RuntimeError):
@@ -140,8 +140,9 @@ def desc(n_tokens: int, n_channels: int, dtype: int = CF_BF16, bits: int = 2, sc
     return cf_tensor_desc(n_tokens, n_channels, dtype, bits, scale, group)
 
 
-def options(ef: int = CF_EF_RECON, err_dtype: int = CF_F32, flags: int = 0, tile_rows: int = 0) -> cf_options:
-    return cf_options(ef, err_dtype, flags, tile_rows)
+def options(ef: int = CF_EF_RECON, err_dtype: int = CF_F32, flags: int = 0, tile_rows: int = 0,
+            encode_rows: int = 0) -> cf_options:
+    return cf_options(ef, err_dtype, flags, tile_rows, encode_rows)
 
 
 # ---------------------------------------------------------------- the C entry points

@@ -26,7 +26,8 @@ struct Layout {
     bool single_pass = false;      // every channel-scale tensor has single-pass geometry
     size_t total = 0;
     std::vector<TensorDev> dev;
-    std::vector<uint32_t> tile_prefix, fin_prefix;
+    std::vector<uint32_t> tile_prefix, fin_prefix, ew_prefix;
+    size_t off_ew_prefix = 0;
     bool any_channel = false;
 };
 
@@ -36,12 +37,14 @@ cf_status check_opts(const cf_options *o, cf_options &out)
     out.err_dtype = CF_F32;
     out.flags = 0;
     out.tile_rows = 0;
+    out.encode_rows = 0;
     if (!o) return CF_OK;
     if (o->ef != CF_EF_RECON && o->ef != CF_EF_LITERAL && o->ef != CF_EF_OFF) return CF_ERR_UNSUPPORTED;
     if (o->err_dtype != CF_F32 && o->err_dtype != CF_BF16) return CF_ERR_UNSUPPORTED;
-    if (o->flags & ~CF_FLAG_NO_PERSISTENT) return CF_ERR_UNSUPPORTED;
+    if (o->flags & ~CF_FLAG_SINGLE_PASS) return CF_ERR_UNSUPPORTED;
     if (o->tile_rows != 0 && o->tile_rows != 8 && o->tile_rows != 16 && o->tile_rows != 32 && o->tile_rows != 64)
         return CF_ERR_UNSUPPORTED;
+    if (o->encode_rows < 0 || o->encode_rows > 64) return CF_ERR_UNSUPPORTED;
     out = *o;
     return CF_OK;
 }
@@ -92,12 +95,14 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     const int rb = pick_rb_rows(descs, n, o);
     L.dev.resize(n);
     L.tile_prefix.assign(n + 1, 0);
+    L.ew_prefix.assign(n + 1, 0);
+    uint64_t ew_tiles = 0;
     L.fin_prefix.assign(n + 1, 0);
     uint64_t tiles = 0, fins = 0, items = 0, groups = 0;
     size_t partial_bytes = 0, p_partial_bytes = 0;
     L.item_prefix.assign(n + 1, 0);
     L.group_prefix.assign(n + 1, 0);
-    L.single_pass = o.ef == CF_EF_RECON && !(o.flags & CF_FLAG_NO_PERSISTENT);
+    L.single_pass = o.ef == CF_EF_RECON && (o.flags & CF_FLAG_SINGLE_PASS) != 0;
     for (int32_t t = 0; t < n; ++t) {
         const cf_tensor_desc &d = descs[t];
         TensorDev &v = L.dev[t];
@@ -116,6 +121,14 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
         L.tile_prefix[t] = (uint32_t)tiles;
         L.fin_prefix[t] = (uint32_t)fins;
         tiles += (uint64_t)v.n_rowblocks * (uint64_t)v.n_colblocks;
+        // element-wise kernels do best with short-lived workgroups: a lane never has to wait for
+        // its own stores before it can use its next loads
+        v.ew_rows = o.encode_rows ? o.encode_rows : 1;
+        v.ew_n_rowblocks = (int32_t)((d.n_tokens + v.ew_rows - 1) / v.ew_rows);
+        v.ew_tile_begin = (uint32_t)ew_tiles;
+        L.ew_prefix[t] = (uint32_t)ew_tiles;
+        ew_tiles += (uint64_t)v.ew_n_rowblocks * (uint64_t)v.n_colblocks;
+        if (ew_tiles > 0x7fffffffull) return CF_ERR_SHAPE;
         fins += (uint64_t)((d.n_channels + kFinalizeThreads - 1) / kFinalizeThreads);
         if (tiles > 0x7fffffffull || fins > 0x7fffffffull) return CF_ERR_SHAPE;
         if (d.scale == CF_SCALE_CHANNEL) {
@@ -140,6 +153,7 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
         }
     }
     L.tile_prefix[n] = (uint32_t)tiles;
+    L.ew_prefix[n] = (uint32_t)ew_tiles;
     L.fin_prefix[n] = (uint32_t)fins;
     L.item_prefix[n] = (uint32_t)items;
     L.group_prefix[n] = (uint32_t)groups;
@@ -150,6 +164,7 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     L.off_ptrs = off;         off = align_up(off + sizeof(TensorPtrs) * (size_t)n);
     L.off_tile_prefix = off;  off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
     L.off_fin_prefix = off;   off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
+    L.off_ew_prefix = off;    off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
     L.off_partials = off;     off = align_up(off + partial_bytes);
     L.off_item_prefix = off;  off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
     L.off_counters = off;     off = align_up(off + sizeof(uint32_t) * (size_t)(groups + 1));
@@ -193,6 +208,7 @@ struct cf_ctx {
         v.ptrs = reinterpret_cast<const TensorPtrs *>(ws + L.off_ptrs);
         v.tile_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_tile_prefix);
         v.fin_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_fin_prefix);
+        v.ew_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_ew_prefix);
         v.item_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_item_prefix);
         v.group_counters = reinterpret_cast<uint32_t *>(ws + L.off_counters);
         v.error_flag = reinterpret_cast<uint32_t *>(ws + L.off_error);
@@ -208,6 +224,8 @@ struct cf_ctx {
         r.count = count;
         r.tile_lo = L.tile_prefix[first];
         r.tile_hi = L.tile_prefix[first + count];
+        r.ew_lo = L.ew_prefix[first];
+        r.ew_hi = L.ew_prefix[first + count];
         r.fin_lo = L.fin_prefix[first];
         r.fin_hi = L.fin_prefix[first + count];
         r.item_lo = L.item_prefix[first];
@@ -215,6 +233,9 @@ struct cf_ctx {
         r.group_lo = L.group_prefix[first];
         r.group_hi = L.group_prefix[first + count];
         r.only_group_scale = 0;
+        r.dts = descs[first].dtype;
+        for (int32_t t = first; t < first + count; ++t)
+            if (descs[t].dtype != descs[first].dtype) r.dts = 2;
         return r;
     }
 
@@ -450,6 +471,9 @@ cf_status cf_init(cf_ctx **out, const cf_tensor_desc *descs, int32_t n_tensors, 
                            sizeof(uint32_t) * (size_t)(n_tensors + 1), hipMemcpyHostToDevice, s);
     if (e == hipSuccess)
         e = hipMemcpyAsync(ctx->ws + ctx->L.off_fin_prefix, ctx->L.fin_prefix.data(),
+                           sizeof(uint32_t) * (size_t)(n_tensors + 1), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(ctx->ws + ctx->L.off_ew_prefix, ctx->L.ew_prefix.data(),
                            sizeof(uint32_t) * (size_t)(n_tensors + 1), hipMemcpyHostToDevice, s);
     if (e == hipSuccess)
         e = hipMemcpyAsync(ctx->ws + ctx->L.off_item_prefix, ctx->L.item_prefix.data(),

@@ -188,6 +188,31 @@ template <int BITS> __device__ __forceinline__ void store_codes(uint8_t *row, in
     else gmut<uint32_t>(row)[chunk] = packed;
 }
 
+// The same, with the code bytes of neighbouring lanes gathered into one dword
+// first (sub-dword stores are slow): 1-bit, the four lanes of a quad; 2-bit,
+// two lanes.  `wide` (uniform over the wave) says that rows are a multiple of
+// four bytes long and that a tensor's lanes come in whole quads; all lanes of a
+// quad must be active.
+template <int BITS> __device__ __forceinline__ void store_codes_wide(uint8_t *row, int chunk, uint32_t packed, bool wide)
+{
+    if (BITS == 4 || !wide) {
+        store_codes<BITS>(row, chunk, packed);
+        return;
+    }
+    const int me = (int)packed;
+    if (BITS == 1) {
+        const uint32_t b1 = (uint32_t)__builtin_amdgcn_update_dpp(0, me, 0x55, 0xF, 0xF, false);   // quad_perm [1,1,1,1]
+        const uint32_t b2 = (uint32_t)__builtin_amdgcn_update_dpp(0, me, 0xAA, 0xF, 0xF, false);   // quad_perm [2,2,2,2]
+        const uint32_t b3 = (uint32_t)__builtin_amdgcn_update_dpp(0, me, 0xFF, 0xF, 0xF, false);   // quad_perm [3,3,3,3]
+        const uint32_t w = (packed & 0xFFu) | ((b1 & 0xFFu) << 8) | ((b2 & 0xFFu) << 16) | (b3 << 24);
+        if ((chunk & 3) == 0) *gmut<uint32_t>(row + chunk) = w;
+    } else {
+        const uint32_t h1 = (uint32_t)__builtin_amdgcn_update_dpp(0, me, 0xF5, 0xF, 0xF, false);   // quad_perm [1,1,3,3]
+        const uint32_t w = (packed & 0xFFFFu) | (h1 << 16);
+        if ((chunk & 1) == 0) *gmut<uint32_t>(row + 2 * chunk) = w;
+    }
+}
+
 template <int BITS> __device__ __forceinline__ uint32_t load_codes(const uint8_t *row, int chunk)
 {
     if (BITS == 1) return gconst<uint8_t>(row)[chunk];

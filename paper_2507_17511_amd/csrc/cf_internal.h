@@ -44,7 +44,10 @@ struct alignas(16) TensorDev {
     int32_t p_n_stripes;    // ceil(C / kStripeChannels): reduction groups of this tensor
     uint32_t p_item_begin;  // id of this tensor's first item
     uint32_t p_group_begin; // index of its first group counter
-    uint32_t pad_[3];
+    // element-wise kernels (warm-up, encode, decode): short tiles of ew_rows x 1024 channels
+    int32_t ew_rows;
+    int32_t ew_n_rowblocks; // ceil(N / ew_rows)
+    uint32_t ew_tile_begin;
 };
 
 // Per-call device pointers of one tensor; uploaded into the workspace.
@@ -64,7 +67,8 @@ struct PtrChunk {
 struct BatchView {
     const TensorDev *descs;     // [n_tensors]
     const TensorPtrs *ptrs;     // [n_tensors]
-    const uint32_t *tile_prefix;    // [n_tensors + 1]
+    const uint32_t *tile_prefix;    // [n_tensors + 1] reduction tiles
+    const uint32_t *ew_prefix;      // [n_tensors + 1] element-wise tiles
     const uint32_t *fin_prefix;     // [n_tensors + 1]
     const uint32_t *item_prefix;    // [n_tensors + 1] items of the single-pass path
     uint32_t *group_counters;       // one arrival counter per (tensor, stripe)
@@ -75,10 +79,12 @@ struct BatchView {
 
 struct LaunchRange {
     int32_t first, count;       // tensors
-    uint32_t tile_lo, tile_hi;  // tiles of [first, first+count)
+    uint32_t tile_lo, tile_hi;  // reduction tiles of [first, first+count)
+    uint32_t ew_lo, ew_hi;      // element-wise tiles
     uint32_t fin_lo, fin_hi;    // finalise blocks
     uint32_t item_lo, item_hi;  // single-pass items
     uint32_t group_lo, group_hi;
+    int32_t dts;                // storage dtype of every tensor in the range (cf_dtype), or 2 if mixed
     int32_t only_group_scale;   // tiled encode: skip tensors the single-pass kernel covers
 };
 

@@ -26,18 +26,26 @@ struct TileCtx {
     TensorDev d;        // by value: lives in scalar registers
     TensorPtrs p;
     int rowblock, colblock;
+    int rows;           // rows per tile of the kernel at hand
 };
 
+// DTS: the storage dtype of every tensor in the launch when it is uniform (F32 or BF16: the other
+// dtype's code is then not even compiled in, which keeps the register count down), 2 when mixed.
+template <int DTS> __device__ __forceinline__ bool is_bf16(const TensorDev &d) { return DTS == 2 ? d.dtype == BF16 : DTS == BF16; }
+
+// EW: element-wise tiling (short tiles), else the reduction tiling.
+template <bool EW>
 __device__ __forceinline__ TileCtx locate_tile(const BatchView &v, const LaunchRange &r)
 {
-    uint32_t tile = r.tile_lo + blockIdx.x;
-    int t = find_slot(v.tile_prefix, r.first, r.first + r.count, tile);
+    uint32_t tile = (EW ? r.ew_lo : r.tile_lo) + blockIdx.x;
+    int t = find_slot(EW ? v.ew_prefix : v.tile_prefix, r.first, r.first + r.count, tile);
     TileCtx c;
     c.d = v.descs[t];
     c.p = v.ptrs[t];
-    uint32_t local = tile - c.d.tile_begin;
+    uint32_t local = tile - (EW ? c.d.ew_tile_begin : c.d.tile_begin);
     c.colblock = (int)(local % (uint32_t)c.d.n_colblocks);
     c.rowblock = (int)(local / (uint32_t)c.d.n_colblocks);
+    c.rows = EW ? c.d.ew_rows : c.d.rb_rows;
     return c;
 }
 
@@ -49,8 +57,8 @@ __device__ __forceinline__ void warmup_tile(const TileCtx &c)
     const TensorDev &d = c.d;
     int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
     if (chunk >= d.n_chunks) return;
-    int64_t row0 = (int64_t)c.rowblock * d.rb_rows;
-    int64_t row1 = row0 + d.rb_rows < d.n_tokens ? row0 + d.rb_rows : d.n_tokens;
+    int64_t row0 = (int64_t)c.rowblock * c.rows;
+    int64_t row1 = row0 + c.rows < d.n_tokens ? row0 + c.rows : d.n_tokens;
     constexpr int U = 4;
     for (int64_t i0 = row0; i0 < row1; i0 += U) {
         Raw8<DT> x[U];
@@ -69,11 +77,11 @@ __device__ __forceinline__ void warmup_tile(const TileCtx &c)
     }
 }
 
-template <int ET>
+template <int ET, int DTS>
 __global__ __launch_bounds__(kTileThreads) void k_warmup(BatchView v, LaunchRange r)
 {
-    TileCtx c = locate_tile(v, r);
-    if (c.d.dtype == BF16) warmup_tile<BF16, ET>(c); else warmup_tile<F32, ET>(c);
+    TileCtx c = locate_tile<true>(v, r);
+    if (is_bf16<DTS>(c.d)) warmup_tile<BF16, ET>(c); else warmup_tile<F32, ET>(c);
 }
 
 // ---------------------------------------------------------------- a3, first level: per-tile column partials
@@ -91,8 +99,8 @@ __device__ __forceinline__ F8 rows8(const TensorDev &d, const TensorPtrs &p, int
         int64_t i = row + r;
         if (i < d.n_tokens) {
             int64_t e = i * d.n_channels + (int64_t)chunk * kChunk;
-            xr[r].load(p.x, e);
-            br[r].load(p.recon, e);
+            xr[r].load_stream(p.x, e);       // streaming: the batch is far larger than any cache
+            br[r].load_stream(p.recon, e);
             if (EF != EF_RECON) er[r].load(p.err, e); else er[r].zero();
         } else {
             xr[r].zero();
@@ -154,13 +162,13 @@ __device__ __forceinline__ void colreduce_tile(const TileCtx &c, uint8_t *ws)
     out.store(partial, 0);
 }
 
-template <int EF, int ET>
+template <int EF, int ET, int DTS>
 __global__ __launch_bounds__(kTileThreads) void k_colreduce(BatchView v, LaunchRange r)
 {
-    TileCtx c = locate_tile(v, r);
+    TileCtx c = locate_tile<false>(v, r);
     const TensorDev &d = c.d;
     if (d.scale != SCALE_CHANNEL) return;
-    if (d.dtype == BF16) {
+    if (is_bf16<DTS>(d)) {
         if (d.bits == 4) colreduce_tile<BF16, EF, ET, true>(c, v.workspace);
         else colreduce_tile<BF16, EF, ET, false>(c, v.workspace);
     } else {
@@ -205,11 +213,12 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
     int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
     const bool cvalid = chunk < d.n_chunks;
     if (MODE == 0 && !cvalid) return;           // group mode keeps every lane alive for the DPP reduction
-    int64_t row0 = (int64_t)c.rowblock * d.rb_rows;
-    int64_t row1 = row0 + d.rb_rows < d.n_tokens ? row0 + d.rb_rows : d.n_tokens;
+    int64_t row0 = (int64_t)c.rowblock * c.rows;
+    int64_t row1 = row0 + c.rows < d.n_tokens ? row0 + c.rows : d.n_tokens;
     const int64_t C = d.n_channels;
     const int64_t row_bytes = C * BITS / 8;
     const int n_groups = d.n_channels >> 7;
+    const bool wide = (d.n_channels & 31) == 0;
 
     F8 s;
     if (MODE == 0) s = load_scales8(p.scales, (int64_t)chunk * kChunk);
@@ -223,7 +232,7 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
             int64_t i = i0 + u;
             if (i < row1 && cvalid) {
                 int64_t e = i * C + (int64_t)chunk * kChunk;
-                xr[u].load_stream(p.x, e);      // last use of x
+                xr[u].load(p.x, e);
                 br[u].load(p.recon, e);
                 if (EF != EF_RECON) er[u].load(p.err, e); else er[u].zero();
             } else {
@@ -252,7 +261,7 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
             if (!cvalid) continue;
             F8 dq;
             uint32_t packed = quant8<BITS>(z, s, dq);
-            store_codes<BITS>(p.codes + i * row_bytes, chunk, packed);
+            store_codes_wide<BITS>(p.codes + i * row_bytes, chunk, packed, wide);
             int64_t e = i * C + (int64_t)chunk * kChunk;
             F8 enew;
 #pragma unroll
@@ -286,12 +295,12 @@ __device__ __forceinline__ void encode_dispatch(const TileCtx &c)
     else encode_tile<DT, 4, 0, EF, ET, FUSED>(c);
 }
 
-template <int EF, int ET, bool FUSED>
+template <int EF, int ET, bool FUSED, int DTS>
 __global__ __launch_bounds__(kTileThreads) void k_encode(BatchView v, LaunchRange r)
 {
-    TileCtx c = locate_tile(v, r);
+    TileCtx c = locate_tile<true>(v, r);
     if (r.only_group_scale && c.d.scale != SCALE_GROUP) return;     // covered by the single-pass kernel
-    if (c.d.dtype == BF16) encode_dispatch<BF16, EF, ET, FUSED>(c);
+    if (is_bf16<DTS>(c.d)) encode_dispatch<BF16, EF, ET, FUSED>(c);
     else encode_dispatch<F32, EF, ET, FUSED>(c);
 }
 
@@ -304,8 +313,8 @@ __device__ __forceinline__ void decode_tile(const TileCtx &c)
     const TensorPtrs &p = c.p;
     int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
     if (chunk >= d.n_chunks) return;
-    int64_t row0 = (int64_t)c.rowblock * d.rb_rows;
-    int64_t row1 = row0 + d.rb_rows < d.n_tokens ? row0 + d.rb_rows : d.n_tokens;
+    int64_t row0 = (int64_t)c.rowblock * c.rows;
+    int64_t row1 = row0 + c.rows < d.n_tokens ? row0 + c.rows : d.n_tokens;
     const int64_t C = d.n_channels;
     const int64_t row_bytes = C * BITS / 8;
     const int n_groups = d.n_channels >> 7;
@@ -357,10 +366,11 @@ template <int DT> __device__ __forceinline__ void decode_dispatch(const TileCtx 
     else decode_tile<DT, 4, 0>(c);
 }
 
+template <int DTS>
 __global__ __launch_bounds__(kTileThreads) void k_decode(BatchView v, LaunchRange r)
 {
-    TileCtx c = locate_tile(v, r);
-    if (c.d.dtype == BF16) decode_dispatch<BF16>(c); else decode_dispatch<F32>(c);
+    TileCtx c = locate_tile<true>(v, r);
+    if (is_bf16<DTS>(c.d)) decode_dispatch<BF16>(c); else decode_dispatch<F32>(c);
 }
 
 // ---------------------------------------------------------------- pointer table upload
@@ -384,33 +394,41 @@ hipError_t launch_upload_ptrs(const PtrChunk &chunk, TensorPtrs *dst, int n, hip
     return hipGetLastError();
 }
 
-hipError_t launch_warmup(const BatchView &v, const LaunchRange &r, int err_dtype, hipStream_t s)
-{
-    dim3 grid(r.tile_hi - r.tile_lo), block(kTileThreads);
-    if (grid.x == 0) return hipSuccess;
-    if (err_dtype == BF16) hipLaunchKernelGGL(k_warmup<BF16>, grid, block, 0, s, v, r);
-    else hipLaunchKernelGGL(k_warmup<F32>, grid, block, 0, s, v, r);
-    return hipGetLastError();
-}
+// Launches KERNEL<ARGS..., DTS> for the range's dtype selector.
+#define CF_LAUNCH_DTS(KERNEL, ...)                                                                      \
+    do {                                                                                                \
+        if (r.dts == 0) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 0>), grid, block, 0, s, v, r);          \
+        else if (r.dts == 1) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 1>), grid, block, 0, s, v, r);     \
+        else hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 2>), grid, block, 0, s, v, r);                     \
+    } while (0)
 
-#define CF_DISPATCH_EF_ET(KERNEL, ...)                                                                  \
+#define CF_LAUNCH_EF_ET(KERNEL, ...)                                                                    \
     do {                                                                                                \
         if (err_dtype == BF16) {                                                                        \
-            if (ef == EF_RECON) hipLaunchKernelGGL((KERNEL<EF_RECON, BF16 __VA_ARGS__>), grid, block, 0, s, v, r);      \
-            else if (ef == EF_LITERAL) hipLaunchKernelGGL((KERNEL<EF_LITERAL, BF16 __VA_ARGS__>), grid, block, 0, s, v, r); \
-            else hipLaunchKernelGGL((KERNEL<EF_OFF, BF16 __VA_ARGS__>), grid, block, 0, s, v, r);       \
+            if (ef == EF_RECON) CF_LAUNCH_DTS(KERNEL, EF_RECON, BF16 __VA_ARGS__);                      \
+            else if (ef == EF_LITERAL) CF_LAUNCH_DTS(KERNEL, EF_LITERAL, BF16 __VA_ARGS__);             \
+            else CF_LAUNCH_DTS(KERNEL, EF_OFF, BF16 __VA_ARGS__);                                       \
         } else {                                                                                        \
-            if (ef == EF_RECON) hipLaunchKernelGGL((KERNEL<EF_RECON, F32 __VA_ARGS__>), grid, block, 0, s, v, r);       \
-            else if (ef == EF_LITERAL) hipLaunchKernelGGL((KERNEL<EF_LITERAL, F32 __VA_ARGS__>), grid, block, 0, s, v, r);  \
-            else hipLaunchKernelGGL((KERNEL<EF_OFF, F32 __VA_ARGS__>), grid, block, 0, s, v, r);        \
+            if (ef == EF_RECON) CF_LAUNCH_DTS(KERNEL, EF_RECON, F32 __VA_ARGS__);                       \
+            else if (ef == EF_LITERAL) CF_LAUNCH_DTS(KERNEL, EF_LITERAL, F32 __VA_ARGS__);              \
+            else CF_LAUNCH_DTS(KERNEL, EF_OFF, F32 __VA_ARGS__);                                        \
         }                                                                                               \
     } while (0)
+
+hipError_t launch_warmup(const BatchView &v, const LaunchRange &r, int err_dtype, hipStream_t s)
+{
+    dim3 grid(r.ew_hi - r.ew_lo), block(kTileThreads);
+    if (grid.x == 0) return hipSuccess;
+    if (err_dtype == BF16) CF_LAUNCH_DTS(k_warmup, BF16);
+    else CF_LAUNCH_DTS(k_warmup, F32);
+    return hipGetLastError();
+}
 
 hipError_t launch_colreduce(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, hipStream_t s)
 {
     dim3 grid(r.tile_hi - r.tile_lo), block(kTileThreads);
     if (grid.x == 0) return hipSuccess;
-    CF_DISPATCH_EF_ET(k_colreduce);
+    CF_LAUNCH_EF_ET(k_colreduce);
     return hipGetLastError();
 }
 
@@ -424,18 +442,20 @@ hipError_t launch_finalize(const BatchView &v, const LaunchRange &r, hipStream_t
 
 hipError_t launch_encode(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, bool fused, hipStream_t s)
 {
-    dim3 grid(r.tile_hi - r.tile_lo), block(kTileThreads);
+    dim3 grid(r.ew_hi - r.ew_lo), block(kTileThreads);
     if (grid.x == 0) return hipSuccess;
-    if (fused) CF_DISPATCH_EF_ET(k_encode, , true);
-    else CF_DISPATCH_EF_ET(k_encode, , false);
+    if (fused) CF_LAUNCH_EF_ET(k_encode, , true);
+    else CF_LAUNCH_EF_ET(k_encode, , false);
     return hipGetLastError();
 }
 
 hipError_t launch_decode(const BatchView &v, const LaunchRange &r, hipStream_t s)
 {
-    dim3 grid(r.tile_hi - r.tile_lo), block(kTileThreads);
+    dim3 grid(r.ew_hi - r.ew_lo), block(kTileThreads);
     if (grid.x == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_decode, grid, block, 0, s, v, r);
+    if (r.dts == 0) hipLaunchKernelGGL(k_decode<0>, grid, block, 0, s, v, r);
+    else if (r.dts == 1) hipLaunchKernelGGL(k_decode<1>, grid, block, 0, s, v, r);
+    else hipLaunchKernelGGL(k_decode<2>, grid, block, 0, s, v, r);
     return hipGetLastError();
 }
 

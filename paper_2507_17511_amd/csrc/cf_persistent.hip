@@ -58,7 +58,7 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
         const int64_t row = row0 + k;
         if (cvalid && row < d.n_tokens) {
             const int64_t e = row * C + (int64_t)chunk * kChunk;
-            xr[k].load_stream(p.x, e);              // x is read exactly once
+            xr[k].load(p.x, e);
             br[k].load(p.recon, e);
         } else {                                    // zero padding of the tree / masked lanes
             xr[k].zero();
@@ -160,6 +160,7 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
             s.v[4] = b.x; s.v[5] = b.y; s.v[6] = b.z; s.v[7] = b.w;
         }
         const int64_t row_bytes = C * BITS / 8;
+        const bool wide = (d.n_channels & 31) == 0;
 #pragma unroll
         for (int k = 0; k < RPT; ++k) {
             const int64_t row = row0 + k;
@@ -170,7 +171,7 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
                 F8 z = residual8<EF_RECON>(xr[k].widen(), b, none);
                 F8 dq;
                 uint32_t packed = quant8<BITS>(z, s, dq);
-                store_codes<BITS>(p.codes + row * row_bytes, chunk, packed);
+                store_codes_wide<BITS>(p.codes + row * row_bytes, chunk, packed, wide);
                 F8 enew;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) enew.v[j] = z.v[j] - dq.v[j];

@@ -33,9 +33,9 @@ COMBOS = [(1, CH), (2, CH), (4, CH), (4, GR)]
 @pytest.mark.parametrize("bits,scale", COMBOS)
 @pytest.mark.parametrize("dtype", [cf.CF_BF16, cf.CF_F32])
 @pytest.mark.parametrize("mode", ["fused", "split"])
-@pytest.mark.parametrize("flags", [0, cf.CF_FLAG_NO_PERSISTENT])
+@pytest.mark.parametrize("flags", [0, cf.CF_FLAG_SINGLE_PASS])
 def test_parity_shapes(bits, scale, dtype, mode, flags):
-    """flags: the single-pass kernel (default) and the separate-kernel path must both match the oracle."""
+    """flags: the two-kernel path (default) and the single-pass kernel must both match the oracle."""
     if scale == GR and flags:
         pytest.skip("group scales never use the single-pass kernel")
     for k, (n, c) in enumerate(SHAPES):
@@ -70,6 +70,21 @@ def test_parity_every_tile_height(tile_rows):
         run_parity([d], cf.options(tile_rows=tile_rows), [[x] for x in xs])
 
 
+@pytest.mark.parametrize("encode_rows", [1, 2, 3, 8, 64])
+def test_parity_every_encode_height(encode_rows):
+    """Rows per workgroup of the element-wise kernels, on channel counts with (1152, 3072) and
+    without (1096, 8) whole quads of lanes (the gathered code stores need them)."""
+    for k, (n, c) in enumerate([(67, 1152), (130, 1096), (9, 8), (33, 3072)]):
+        for bits, scale in COMBOS:
+            if scale == GR and c % 128:
+                continue
+            say(f"encode_rows={encode_rows} N={n} C={c} bits={bits} scale={scale}")
+            d = cf.desc(n, c, cf.CF_BF16, bits, scale)
+            xs = drift_stream((n, c), cf.CF_BF16, steps=3, seed=11 * k + bits, device=DEV)
+            for mode in ("fused", "split"):
+                run_parity([d], cf.options(encode_rows=encode_rows), [[x] for x in xs], mode=mode)
+
+
 def _mixed_batch():
     descs = [cf.desc(203, 1096, cf.CF_BF16, 1, CH), cf.desc(64, 3072, cf.CF_BF16, 2, CH),
              cf.desc(100, 256, cf.CF_F32, 4, GR), cf.desc(77, 1024, cf.CF_BF16, 4, CH),
@@ -82,7 +97,7 @@ def _mixed_batch():
 
 
 @pytest.mark.parametrize("mode", ["fused", "split"])
-@pytest.mark.parametrize("flags", [0, cf.CF_FLAG_NO_PERSISTENT])
+@pytest.mark.parametrize("flags", [0, cf.CF_FLAG_SINGLE_PASS])
 def test_parity_batched_mixed_launch(mode, flags):
     """One call covers tensors of different shapes, dtypes, widths and scale kinds."""
     say(f"mixed batch mode={mode} flags={flags}")
@@ -99,7 +114,8 @@ def test_single_pass_many_row_blocks_and_stripes():
     streams = [drift_stream((d.n_tokens, d.n_channels), d.dtype, steps=3, seed=70 + k, device=DEV)
                for k, d in enumerate(descs)]
     xs = [[streams[t][s] for t in range(len(descs))] for s in range(3)]
-    sess, _ = run_parity(descs, cf.options(), xs, mode="fused")
+    run_parity(descs, cf.options(flags=cf.CF_FLAG_SINGLE_PASS), xs, mode="fused")
+    run_parity(descs, cf.options(), xs, mode="fused")
 
 
 def test_subrange_calls_match_whole_batch():
@@ -317,5 +333,5 @@ def test_configs_reduced(name, shrink):
     xs = [[x.clone() for x in stream.current]]
     for _ in range(1, wl.steps):
         xs.append([x.clone() for x in stream.advance()])
-    for flags in (0, cf.CF_FLAG_NO_PERSISTENT):
+    for flags in (0, cf.CF_FLAG_SINGLE_PASS):
         run_parity(descs, cf.options(flags=flags), xs, mode="fused", tag=f"{name} flags={flags}")
