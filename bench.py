@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, help="one of workloads.CONFIGS, or 'all'")
+    ap.add_argument("--workload", default="all", help="one of workloads.CONFIGS, or all (every config; the headline is cfg3_kv_fullseq)")
     ap.add_argument("--ef", type=int, default=0, help="cf_ef_mode (0 = RECON)")
     ap.add_argument("--flags", type=int, default=0, help="cf_options.flags")
     ap.add_argument("--tile-rows", type=int, default=0)
