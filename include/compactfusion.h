@@ -73,8 +73,10 @@ typedef enum { CF_F32 = 0, CF_BF16 = 1 } cf_dtype;
 
 /* What a scale spans.  CHANNEL: all N tokens of one channel (the paper's v_j
  * with u = 1).  GROUP: `group` consecutive channels of one token (4-bit only).
- * RANK1: the paper's u v^T, s_ij = u_i * v_j with u_i = rowmean|z| / mean|z|
- * (1-/2-bit only). */
+ * RANK1: the paper's u v^T (App. D "Quantization"), s_ij = u_i * v_j with v_j as
+ * for CHANNEL and u_i = rowmean_i|z| / mean|z| (0 when z is all zero); 1-/2-bit
+ * only, C <= 131072 (CF_ERR_SHAPE beyond), two-kernel path only (the
+ * single-pass flag is ignored for a context that holds such a tensor). */
 typedef enum { CF_SCALE_CHANNEL = 0, CF_SCALE_GROUP = 1, CF_SCALE_RANK1 = 2 } cf_scale_kind;
 
 /* How the error buffer enters (a2) and is updated (a7).

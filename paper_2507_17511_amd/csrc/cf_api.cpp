@@ -28,7 +28,7 @@ struct Layout {
     std::vector<TensorDev> dev;
     std::vector<uint32_t> tile_prefix, fin_prefix, ew_prefix;
     size_t off_ew_prefix = 0;
-    bool any_channel = false;
+    bool any_channel = false, any_rank1 = false;
 };
 
 cf_status check_opts(const cf_options *o, cf_options &out)
@@ -62,7 +62,12 @@ cf_status check_desc(const cf_tensor_desc &d)
         if (d.group != 128 || d.n_channels % 128 != 0) return CF_ERR_SHAPE;
         return CF_OK;
     }
-    return CF_ERR_UNSUPPORTED;   // CF_SCALE_RANK1 is declared but not built yet
+    if (d.scale == CF_SCALE_RANK1) {
+        if (d.bits == 4) return CF_ERR_UNSUPPORTED;                  // the paper's u v^T goes with its 1-/2-bit code books
+        if (d.n_channels > (int64_t)kMaxRank1Colblocks * kTileChannels) return CF_ERR_SHAPE;
+        return CF_OK;
+    }
+    return CF_ERR_UNSUPPORTED;
 }
 
 size_t dtype_size(int32_t dt) { return dt == CF_BF16 ? 2 : 4; }
@@ -103,6 +108,8 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     L.item_prefix.assign(n + 1, 0);
     L.group_prefix.assign(n + 1, 0);
     L.single_pass = o.ef == CF_EF_RECON && (o.flags & CF_FLAG_SINGLE_PASS) != 0;
+    for (int32_t t = 0; t < n; ++t)
+        if (descs[t].scale == CF_SCALE_RANK1) L.single_pass = false;   // the single-pass kernel knows channel scales only
     for (int32_t t = 0; t < n; ++t) {
         const cf_tensor_desc &d = descs[t];
         TensorDev &v = L.dev[t];
@@ -131,10 +138,15 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
         if (ew_tiles > 0x7fffffffull) return CF_ERR_SHAPE;
         fins += (uint64_t)((d.n_channels + kFinalizeThreads - 1) / kFinalizeThreads);
         if (tiles > 0x7fffffffull || fins > 0x7fffffffull) return CF_ERR_SHAPE;
-        if (d.scale == CF_SCALE_CHANNEL) {
+        if (d.scale == CF_SCALE_CHANNEL || d.scale == CF_SCALE_RANK1) {
             L.any_channel = true;
             v.partial_off = partial_bytes;   // relative; rebased below
             partial_bytes += align_up((size_t)v.n_rowblocks * (size_t)d.n_channels * sizeof(float));
+        }
+        if (d.scale == CF_SCALE_RANK1) {
+            L.any_rank1 = true;
+            v.rowpart_off = partial_bytes;
+            partial_bytes += align_up((size_t)d.n_tokens * (size_t)v.n_colblocks * sizeof(float));
         }
         L.item_prefix[t] = (uint32_t)items;
         L.group_prefix[t] = (uint32_t)groups;
@@ -171,11 +183,13 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     L.off_error = off;        off = align_up(off + sizeof(uint32_t));
     L.off_p_partials = off;   off = align_up(off + p_partial_bytes);
     L.total = off;
-    for (int32_t t = 0; t < n; ++t)
-        if (descs[t].scale == CF_SCALE_CHANNEL) {
+    for (int32_t t = 0; t < n; ++t) {
+        if (descs[t].scale == CF_SCALE_CHANNEL || descs[t].scale == CF_SCALE_RANK1) {
             L.dev[t].partial_off += L.off_partials;
             L.dev[t].p_partial_off += L.off_p_partials;
         }
+        if (descs[t].scale == CF_SCALE_RANK1) L.dev[t].rowpart_off += L.off_partials;
+    }
     return CF_OK;
 }
 
@@ -246,10 +260,17 @@ struct cf_ctx {
         return false;
     }
 
-    bool range_has_channel(int32_t first, int32_t count) const
+    bool range_has_channel(int32_t first, int32_t count) const      // anything that needs the reduction kernels
     {
         for (int32_t t = first; t < first + count; ++t)
-            if (descs[t].scale == CF_SCALE_CHANNEL) return true;
+            if (descs[t].scale != CF_SCALE_GROUP) return true;
+        return false;
+    }
+
+    bool range_has_rank1(int32_t first, int32_t count) const
+    {
+        for (int32_t t = first; t < first + count; ++t)
+            if (descs[t].scale == CF_SCALE_RANK1) return true;
         return false;
     }
 };
@@ -387,6 +408,10 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
         if (e != hipSuccess) return device_fail(ctx, e);
         e = launch(ctx, s, "k_finalize", [&] { return launch_finalize(v, r, s); });
         if (e != hipSuccess) return device_fail(ctx, e);
+        if (ctx->range_has_rank1(first, count)) {
+            e = launch(ctx, s, "k_finalize_rank1", [&] { return launch_finalize_rank1(v, r, s); });
+            if (e != hipSuccess) return device_fail(ctx, e);
+        }
     }
     e = launch(ctx, s, "k_encode", [&] { return launch_encode(v, r, ef, et, fused, s); });
     if (e != hipSuccess) return device_fail(ctx, e);
@@ -421,7 +446,8 @@ cf_status cf_sizes(const cf_tensor_desc *desc, const cf_options *opts, size_t *c
     if ((st = check_desc(*desc)) != CF_OK) return st;
     const size_t n = (size_t)desc->n_tokens, c = (size_t)desc->n_channels;
     if (codes_bytes) *codes_bytes = n * (c * (size_t)desc->bits / 8);
-    if (scales_bytes) *scales_bytes = sizeof(float) * (desc->scale == CF_SCALE_GROUP ? n * (c / 128) : c);
+    if (scales_bytes)
+        *scales_bytes = sizeof(float) * (desc->scale == CF_SCALE_GROUP ? n * (c / 128) : desc->scale == CF_SCALE_RANK1 ? c + n : c);
     if (recon_bytes) *recon_bytes = n * c * dtype_size(desc->dtype);
     if (err_bytes) *err_bytes = n * c * dtype_size(o.err_dtype);
     return CF_OK;

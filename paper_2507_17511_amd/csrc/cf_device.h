@@ -14,7 +14,7 @@ namespace cf {
 namespace dev {
 
 constexpr int F32 = 0, BF16 = 1;
-constexpr int SCALE_CHANNEL = 0, SCALE_GROUP = 1;
+constexpr int SCALE_CHANNEL = 0, SCALE_GROUP = 1, SCALE_RANK1 = 2;
 constexpr int EF_RECON = 0, EF_LITERAL = 1, EF_OFF = 2;
 
 #define CF_GLOBAL __attribute__((address_space(1)))
@@ -52,6 +52,10 @@ template <> struct Raw8<BF16> {
     __device__ __forceinline__ void load(const void *base, int64_t elem) { w = *gconst<u32x4>(static_cast<const uint16_t *>(base) + elem); }
     __device__ __forceinline__ void load_stream(const void *base, int64_t elem) { w = __builtin_nontemporal_load(gconst<u32x4>(static_cast<const uint16_t *>(base) + elem)); }
     __device__ __forceinline__ void store(void *base, int64_t elem) const { *gmut<u32x4>(static_cast<uint16_t *>(base) + elem) = w; }
+    // Uniform base pointer plus a 32-bit per-lane byte offset: the scalar-base form of the global
+    // instructions, which needs no 64-bit address arithmetic in vector registers.
+    __device__ __forceinline__ void load_at(const void *ubase, uint32_t off) { w = *gconst<u32x4>(static_cast<const char *>(ubase) + off); }
+    __device__ __forceinline__ void store_at(void *ubase, uint32_t off) const { *gmut<u32x4>(static_cast<char *>(ubase) + off) = w; }
     // Makes the registers opaque to the optimiser: values derived from them earlier are not reused.
     __device__ __forceinline__ void opaque() { asm volatile("" : "+v"(w)); }
     __device__ __forceinline__ F8 widen() const
@@ -89,6 +93,18 @@ template <> struct Raw8<F32> {
     __device__ __forceinline__ void store(void *base, int64_t elem) const
     {
         CF_GLOBAL f32x4 *p = gmut<f32x4>(static_cast<float *>(base) + elem);
+        p[0] = a;
+        p[1] = b;
+    }
+    __device__ __forceinline__ void load_at(const void *ubase, uint32_t off)
+    {
+        const CF_GLOBAL f32x4 *p = gconst<f32x4>(static_cast<const char *>(ubase) + off);
+        a = p[0];
+        b = p[1];
+    }
+    __device__ __forceinline__ void store_at(void *ubase, uint32_t off) const
+    {
+        CF_GLOBAL f32x4 *p = gmut<f32x4>(static_cast<char *>(ubase) + off);
         p[0] = a;
         p[1] = b;
     }
@@ -193,10 +209,16 @@ template <int BITS> __device__ __forceinline__ void store_codes(uint8_t *row, in
 // two lanes.  `wide` (uniform over the wave) says that rows are a multiple of
 // four bytes long and that a tensor's lanes come in whole quads; all lanes of a
 // quad must be active.
-template <int BITS> __device__ __forceinline__ void store_codes_wide(uint8_t *row, int chunk, uint32_t packed, bool wide)
+// `mine` is the address of the lane's own BITS code bytes; `chunk` its chunk index in the row.
+template <int BITS> __device__ __forceinline__ void store_codes_ptr(uint8_t *mine, int chunk, uint32_t packed, bool wide)
 {
-    if (BITS == 4 || !wide) {
-        store_codes<BITS>(row, chunk, packed);
+    if (BITS == 4) {
+        *gmut<uint32_t>(mine) = packed;
+        return;
+    }
+    if (!wide) {
+        if (BITS == 1) *gmut<uint8_t>(mine) = (uint8_t)packed;
+        else *gmut<uint16_t>(mine) = (uint16_t)packed;
         return;
     }
     const int me = (int)packed;
@@ -205,12 +227,17 @@ template <int BITS> __device__ __forceinline__ void store_codes_wide(uint8_t *ro
         const uint32_t b2 = (uint32_t)__builtin_amdgcn_update_dpp(0, me, 0xAA, 0xF, 0xF, false);   // quad_perm [2,2,2,2]
         const uint32_t b3 = (uint32_t)__builtin_amdgcn_update_dpp(0, me, 0xFF, 0xF, 0xF, false);   // quad_perm [3,3,3,3]
         const uint32_t w = (packed & 0xFFu) | ((b1 & 0xFFu) << 8) | ((b2 & 0xFFu) << 16) | (b3 << 24);
-        if ((chunk & 3) == 0) *gmut<uint32_t>(row + chunk) = w;
+        if ((chunk & 3) == 0) *gmut<uint32_t>(mine) = w;
     } else {
         const uint32_t h1 = (uint32_t)__builtin_amdgcn_update_dpp(0, me, 0xF5, 0xF, 0xF, false);   // quad_perm [1,1,3,3]
         const uint32_t w = (packed & 0xFFFFu) | (h1 << 16);
-        if ((chunk & 1) == 0) *gmut<uint32_t>(row + 2 * chunk) = w;
+        if ((chunk & 1) == 0) *gmut<uint32_t>(mine) = w;
     }
+}
+
+template <int BITS> __device__ __forceinline__ void store_codes_wide(uint8_t *row, int chunk, uint32_t packed, bool wide)
+{
+    store_codes_ptr<BITS>(row + chunk * BITS, chunk, packed, wide);
 }
 
 template <int BITS> __device__ __forceinline__ uint32_t load_codes(const uint8_t *row, int chunk)
@@ -241,6 +268,21 @@ __device__ __forceinline__ float row16_max(float m)
     v = __builtin_amdgcn_update_dpp(0, __float_as_int(m), 0x140, 0xF, 0xF, false);  // row_mirror
     m = fmaxf(m, __int_as_float(v));
     return m;
+}
+
+// Sum over the 64 lanes of a wave as a balanced tree over the lane index (lane pairs, then pairs
+// of pairs, ...): every lane ends up with the total.  After the two quad steps the lanes of a quad
+// agree, so the mirror steps pair quad with quad and half-row with half-row exactly as an xor
+// butterfly would.  All 64 lanes must be active.
+__device__ __forceinline__ float wave_tree_sum(float v)
+{
+    v = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, false));   // lane ^ 1
+    v = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, false));   // lane ^ 2
+    v = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, false));  // other quad of 8
+    v = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, false));  // other half of 16
+    v = v + __shfl_xor(v, 16);
+    v = v + __shfl_xor(v, 32);
+    return v;
 }
 
 template <bool IS_MAX> __device__ __forceinline__ float comb(float a, float b) { return IS_MAX ? fmaxf(a, b) : a + b; }

@@ -13,6 +13,8 @@ constexpr int kTileThreads = 128;
 constexpr int kChunk = 8;                                   // channels per lane
 constexpr int kTileChannels = kTileThreads * kChunk;        // 1024
 constexpr int kFinalizeThreads = 256;                       // columns per finalise block
+constexpr int kRank1Threads = 1024;                         // one block per tensor finishes the token scales u
+constexpr int kMaxRank1Colblocks = 128;                     // rank-1 scales: C <= 128 * 1024
 constexpr int kMaxUploadTensors = 64;                       // pointer sets per upload launch
 // Single-pass path: one workgroup of 256 lanes keeps an item of p_rows x 256
 // channels (x and recon, raw) in registers between the scale reduction and the
@@ -48,6 +50,9 @@ struct alignas(16) TensorDev {
     int32_t ew_rows;
     int32_t ew_n_rowblocks; // ceil(N / ew_rows)
     uint32_t ew_tile_begin;
+    // rank-1 scales: per-row sums of |z| over each 1024-channel tile, rowpart[N][n_colblocks]
+    uint32_t r1_pad_;
+    uint64_t rowpart_off;
 };
 
 // Per-call device pointers of one tensor; uploaded into the workspace.
@@ -94,6 +99,7 @@ hipError_t launch_upload_ptrs(const PtrChunk &chunk, TensorPtrs *dst, int n, hip
 hipError_t launch_warmup(const BatchView &v, const LaunchRange &r, int err_dtype, hipStream_t s);
 hipError_t launch_colreduce(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, hipStream_t s);
 hipError_t launch_finalize(const BatchView &v, const LaunchRange &r, hipStream_t s);
+hipError_t launch_finalize_rank1(const BatchView &v, const LaunchRange &r, hipStream_t s);
 hipError_t launch_encode(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, bool fused, hipStream_t s);
 hipError_t launch_decode(const BatchView &v, const LaunchRange &r, hipStream_t s);
 

@@ -89,15 +89,18 @@ __global__ __launch_bounds__(kTileThreads) void k_warmup(BatchView v, LaunchRang
 // |z| of 8 consecutive rows, combined as a balanced tree:
 // ((r0+r1)+(r2+r3)) + ((r4+r5)+(r6+r7)).  Rows past the end count as +0, which
 // is exactly the zero padding of the tree.
-template <int DT, int EF, int ET, bool IS_MAX>
-__device__ __forceinline__ F8 rows8(const TensorDev &d, const TensorPtrs &p, int chunk, int64_t row)
+// R1 (rank-1 scales): also the sum of |z| over the wave's 512 channels of each of the 8 rows, as
+// a balanced tree over the channels (8 in the lane, then lane pairs upwards); every lane takes
+// part, lanes past the last chunk contribute zeros.
+template <int DT, int EF, int ET, bool IS_MAX, bool R1>
+__device__ __forceinline__ F8 rows8(const TensorDev &d, const TensorPtrs &p, int chunk, int64_t row, float (&wave_rowsum)[8])
 {
     Raw8<DT> xr[8], br[8];
     Raw8<ET> er[8];
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
         int64_t i = row + r;
-        if (i < d.n_tokens) {
+        if (i < d.n_tokens && (!R1 || chunk < d.n_chunks)) {
             int64_t e = i * d.n_channels + (int64_t)chunk * kChunk;
             xr[r].load_stream(p.x, e);       // streaming: the batch is far larger than any cache
             br[r].load_stream(p.recon, e);
@@ -114,6 +117,10 @@ __device__ __forceinline__ F8 rows8(const TensorDev &d, const TensorPtrs &p, int
         F8 z = residual8<EF>(xr[r].widen(), br[r].widen(), er[r].widen());
 #pragma unroll
         for (int k = 0; k < 8; ++k) a[r].v[k] = fabsf(z.v[k]);
+        if (R1) {
+            const float lane = ((a[r].v[0] + a[r].v[1]) + (a[r].v[2] + a[r].v[3])) + ((a[r].v[4] + a[r].v[5]) + (a[r].v[6] + a[r].v[7]));
+            wave_rowsum[r] = wave_tree_sum(lane);
+        }
     }
     F8 t;
 #pragma unroll
@@ -126,13 +133,15 @@ __device__ __forceinline__ F8 rows8(const TensorDev &d, const TensorPtrs &p, int
     return t;
 }
 
-template <int DT, int EF, int ET, bool IS_MAX>
+template <int DT, int EF, int ET, bool IS_MAX, bool R1>
 __device__ __forceinline__ void colreduce_tile(const TileCtx &c, uint8_t *ws)
 {
     const TensorDev &d = c.d;
     int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
-    if (chunk >= d.n_chunks) return;
-    int64_t row = (int64_t)c.rowblock * d.rb_rows;
+    if (!R1 && chunk >= d.n_chunks) return;
+    __shared__ float tile_rowsum[kTileThreads / 64][64];      // [wave][row of the tile]
+    const int64_t tile_row0 = (int64_t)c.rowblock * d.rb_rows;
+    int64_t row = tile_row0;
     // Balanced tree over the tile's rb_rows = 8 * nb rows (nb in {1,2,4,8}) as three
     // nested two-way loops: level k combines two results of level k-1.  The loops
     // stay rolled so that only one batch of 16 row loads is in flight per lane.
@@ -145,7 +154,12 @@ __device__ __forceinline__ void colreduce_tile(const TileCtx &c, uint8_t *ws)
         for (int h1 = 0; h1 < n1; ++h1) {
 #pragma unroll 1
             for (int h0 = 0; h0 < n0; ++h0) {
-                F8 t = rows8<DT, EF, ET, IS_MAX>(d, c.p, chunk, row);
+                float wave_rowsum[8];
+                F8 t = rows8<DT, EF, ET, IS_MAX, R1>(d, c.p, chunk, row, wave_rowsum);
+                if (R1 && (threadIdx.x & 63) == 0) {
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) tile_rowsum[threadIdx.x >> 6][(int)(row - tile_row0) + q] = wave_rowsum[q];
+                }
                 row += 8;
 #pragma unroll
                 for (int k = 0; k < 8; ++k) s0.v[k] = (h0 == 0) ? t.v[k] : comb<IS_MAX>(s0.v[k], t.v[k]);
@@ -156,10 +170,20 @@ __device__ __forceinline__ void colreduce_tile(const TileCtx &c, uint8_t *ws)
 #pragma unroll
         for (int k = 0; k < 8; ++k) s2.v[k] = (h2 == 0) ? s1.v[k] : comb<IS_MAX>(s2.v[k], s1.v[k]);
     }
-    float *partial = reinterpret_cast<float *>(ws + d.partial_off) + (int64_t)c.rowblock * d.n_channels + (int64_t)chunk * kChunk;
-    Raw8<F32> out;
-    out.narrow(s2);
-    out.store(partial, 0);
+    if (chunk < d.n_chunks) {
+        float *partial = reinterpret_cast<float *>(ws + d.partial_off) + (int64_t)c.rowblock * d.n_channels + (int64_t)chunk * kChunk;
+        Raw8<F32> out;
+        out.narrow(s2);
+        out.store(partial, 0);
+    }
+    if (R1) {       // the tile's two waves cover channels [0,512) and [512,1024) of the tile: lower + upper
+        __syncthreads();
+        const int q = (int)threadIdx.x;
+        if (q < d.rb_rows && tile_row0 + q < d.n_tokens) {
+            float *rowpart = reinterpret_cast<float *>(ws + d.rowpart_off);
+            rowpart[(tile_row0 + q) * d.n_colblocks + c.colblock] = tile_rowsum[0][q] + tile_rowsum[1][q];
+        }
+    }
 }
 
 template <int EF, int ET, int DTS>
@@ -167,13 +191,15 @@ __global__ __launch_bounds__(kTileThreads) void k_colreduce(BatchView v, LaunchR
 {
     TileCtx c = locate_tile<false>(v, r);
     const TensorDev &d = c.d;
-    if (d.scale != SCALE_CHANNEL) return;
+    if (d.scale == SCALE_GROUP) return;
     if (is_bf16<DTS>(d)) {
-        if (d.bits == 4) colreduce_tile<BF16, EF, ET, true>(c, v.workspace);
-        else colreduce_tile<BF16, EF, ET, false>(c, v.workspace);
+        if (d.scale == SCALE_RANK1) colreduce_tile<BF16, EF, ET, false, true>(c, v.workspace);
+        else if (d.bits == 4) colreduce_tile<BF16, EF, ET, true, false>(c, v.workspace);
+        else colreduce_tile<BF16, EF, ET, false, false>(c, v.workspace);
     } else {
-        if (d.bits == 4) colreduce_tile<F32, EF, ET, true>(c, v.workspace);
-        else colreduce_tile<F32, EF, ET, false>(c, v.workspace);
+        if (d.scale == SCALE_RANK1) colreduce_tile<F32, EF, ET, false, true>(c, v.workspace);
+        else if (d.bits == 4) colreduce_tile<F32, EF, ET, true, false>(c, v.workspace);
+        else colreduce_tile<F32, EF, ET, false, false>(c, v.workspace);
     }
 }
 
@@ -186,7 +212,7 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_finalize(BatchView v, Laun
     uint32_t blk = r.fin_lo + blockIdx.x;
     int t = find_slot(v.fin_prefix, r.first, r.first + r.count, blk);
     const TensorDev d = v.descs[t];
-    if (d.scale != SCALE_CHANNEL) return;
+    if (d.scale == SCALE_GROUP) return;
     int col = (int)(blk - d.fin_begin) * kFinalizeThreads + (int)threadIdx.x;
     if (col >= d.n_channels) return;
     const CF_GLOBAL float *partial = gconst<float>(v.workspace + d.partial_off) + col;
@@ -202,9 +228,48 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_finalize(BatchView v, Laun
     gmut<float>(v.ptrs[t].scales)[col] = s;
 }
 
+// Rank-1 scales (App. D "Quantization"): u_i = (rowsum_i / C) / (sum_i rowsum_i / (N C)), written
+// behind v in the scales buffer.  One block per tensor: lane t owns an aligned block of B rows
+// (B a power of two); a row's sum is the tree over its 1024-channel tile sums, the total is the
+// tree over the rows (in the lane, then across lanes in LDS).
+__global__ __launch_bounds__(kRank1Threads) void k_finalize_rank1(BatchView v, LaunchRange r)
+{
+    const int t = r.first + (int)blockIdx.x;
+    const TensorDev d = v.descs[t];
+    if (d.scale != SCALE_RANK1) return;
+    __shared__ float lane_total[kRank1Threads];
+    const CF_GLOBAL float *rowpart = gconst<float>(v.workspace + d.rowpart_off);
+    CF_GLOBAL float *u = gmut<float>(v.ptrs[t].scales) + d.n_channels;
+    const int64_t N = d.n_tokens;
+    const int ncb = d.n_colblocks;
+    int64_t B = 1;
+    while (B * kRank1Threads < N) B <<= 1;
+    const int64_t first = (int64_t)threadIdx.x * B;
+    auto rowsum = [&](int64_t i) { return tree_over<false, 4>(ncb, [&](int cb) { return rowpart[i * ncb + cb]; }); };
+    // pass 1: row sums (kept in u for pass 2) and this lane's block total
+    const int nmine = first >= N ? 0 : (int)(N - first < B ? N - first : B);
+    lane_total[threadIdx.x] = tree_over<false, 12>(nmine, [&](int q) {
+        const float rs = rowsum(first + q);
+        u[first + q] = rs;
+        return rs;
+    });
+    __syncthreads();
+    for (int w = 1; w < kRank1Threads; w <<= 1) {
+        if ((threadIdx.x & (2 * w - 1)) == 0) lane_total[threadIdx.x] = lane_total[threadIdx.x] + lane_total[threadIdx.x + w];
+        __syncthreads();
+    }
+    const float total = lane_total[0];
+    const float gmean = total / (float)(N * (int64_t)d.n_channels);
+    for (int q = 0; q < nmine; ++q) {
+        const float rmean = u[first + q] / (float)d.n_channels;
+        u[first + q] = gmean == 0.0f ? 0.0f : rmean / gmean;
+    }
+}
+
 // ---------------------------------------------------------------- a4-a8: encode (+ fused state update)
 
-// MODE: 0 = channel scales read from memory, 1 = group scales computed in the wave.
+// MODE: 0 = channel scales read from memory, 1 = group scales computed in the wave,
+// 2 = rank-1 scales u_i * v_j (v read once per lane, u once per row).
 template <int DT, int BITS, int MODE, int EF, int ET, bool FUSED>
 __device__ __forceinline__ void encode_tile(const TileCtx &c)
 {
@@ -212,7 +277,7 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
     const TensorPtrs &p = c.p;
     int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
     const bool cvalid = chunk < d.n_chunks;
-    if (MODE == 0 && !cvalid) return;           // group mode keeps every lane alive for the DPP reduction
+    if (MODE != 1 && !cvalid) return;           // group mode keeps every lane alive for the DPP reduction
     int64_t row0 = (int64_t)c.rowblock * c.rows;
     int64_t row1 = row0 + c.rows < d.n_tokens ? row0 + c.rows : d.n_tokens;
     const int64_t C = d.n_channels;
@@ -220,8 +285,9 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
     const int n_groups = d.n_channels >> 7;
     const bool wide = (d.n_channels & 31) == 0;
 
-    F8 s;
+    F8 s, vj;
     if (MODE == 0) s = load_scales8(p.scales, (int64_t)chunk * kChunk);
+    if (MODE == 2) vj = load_scales8(p.scales, (int64_t)chunk * kChunk);
 
     constexpr int U = 4;
     for (int64_t i0 = row0; i0 < row1; i0 += U) {
@@ -258,6 +324,11 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
                 for (int k = 0; k < 8; ++k) s.v[k] = sg;
                 if (cvalid && (threadIdx.x & 15) == 0) gmut<float>(p.scales)[i * n_groups + (chunk >> 4)] = sg;
             }
+            if (MODE == 2) {
+                const float ui = gconst<float>(p.scales)[C + i];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) s.v[k] = ui * vj.v[k];
+            }
             if (!cvalid) continue;
             F8 dq;
             uint32_t packed = quant8<BITS>(z, s, dq);
@@ -290,6 +361,11 @@ __device__ __forceinline__ void encode_dispatch(const TileCtx &c)
 {
     const TensorDev &d = c.d;
     if (d.scale == SCALE_GROUP) { encode_tile<DT, 4, 1, EF, ET, FUSED>(c); return; }
+    if (d.scale == SCALE_RANK1) {
+        if (d.bits == 1) encode_tile<DT, 1, 2, EF, ET, FUSED>(c);
+        else encode_tile<DT, 2, 2, EF, ET, FUSED>(c);
+        return;
+    }
     if (d.bits == 1) encode_tile<DT, 1, 0, EF, ET, FUSED>(c);
     else if (d.bits == 2) encode_tile<DT, 2, 0, EF, ET, FUSED>(c);
     else encode_tile<DT, 4, 0, EF, ET, FUSED>(c);
@@ -318,8 +394,9 @@ __device__ __forceinline__ void decode_tile(const TileCtx &c)
     const int64_t C = d.n_channels;
     const int64_t row_bytes = C * BITS / 8;
     const int n_groups = d.n_channels >> 7;
-    F8 s;
+    F8 s, vj;
     if (MODE == 0) s = load_scales8(p.scales, (int64_t)chunk * kChunk);
+    if (MODE == 2) vj = load_scales8(p.scales, (int64_t)chunk * kChunk);
     constexpr int U = 4;
     for (int64_t i0 = row0; i0 < row1; i0 += U) {
         Raw8<DT> br[U];
@@ -331,7 +408,8 @@ __device__ __forceinline__ void decode_tile(const TileCtx &c)
             if (i < row1) {
                 br[u].load(p.recon, i * C + (int64_t)chunk * kChunk);
                 pk[u] = load_codes<BITS>(p.codes + i * row_bytes, chunk);
-                sg[u] = (MODE == 1) ? gconst<float>(p.scales)[i * n_groups + (chunk >> 4)] : 0.0f;
+                sg[u] = (MODE == 1) ? gconst<float>(p.scales)[i * n_groups + (chunk >> 4)]
+                                    : (MODE == 2) ? gconst<float>(p.scales)[C + i] : 0.0f;
             } else {
                 br[u].zero();
                 pk[u] = 0;
@@ -345,6 +423,10 @@ __device__ __forceinline__ void decode_tile(const TileCtx &c)
             if (MODE == 1) {
 #pragma unroll
                 for (int k = 0; k < 8; ++k) s.v[k] = sg[u];
+            }
+            if (MODE == 2) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) s.v[k] = sg[u] * vj.v[k];
             }
             F8 dq, b = br[u].widen(), nb;
             dequant8<BITS>(pk[u], s, dq);
@@ -361,6 +443,10 @@ template <int DT> __device__ __forceinline__ void decode_dispatch(const TileCtx 
 {
     const TensorDev &d = c.d;
     if (d.scale == SCALE_GROUP) { decode_tile<DT, 4, 1>(c); return; }
+    if (d.scale == SCALE_RANK1) {
+        if (d.bits == 1) decode_tile<DT, 1, 2>(c); else decode_tile<DT, 2, 2>(c);
+        return;
+    }
     if (d.bits == 1) decode_tile<DT, 1, 0>(c);
     else if (d.bits == 2) decode_tile<DT, 2, 0>(c);
     else decode_tile<DT, 4, 0>(c);
@@ -437,6 +523,13 @@ hipError_t launch_finalize(const BatchView &v, const LaunchRange &r, hipStream_t
     dim3 grid(r.fin_hi - r.fin_lo), block(kFinalizeThreads);
     if (grid.x == 0) return hipSuccess;
     hipLaunchKernelGGL(k_finalize, grid, block, 0, s, v, r);
+    return hipGetLastError();
+}
+
+hipError_t launch_finalize_rank1(const BatchView &v, const LaunchRange &r, hipStream_t s)
+{
+    if (r.count == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_finalize_rank1, dim3(r.count), dim3(kRank1Threads), 0, s, v, r);
     return hipGetLastError();
 }
 

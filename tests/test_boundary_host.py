@@ -47,6 +47,11 @@ def test_sizes_follow_the_layouts():
     assert codes == 16384 * 3072 // 2 and scales == 16384 * 24 * 4 and err == recon == 16384 * 3072 * 2
     d = cf.desc(256, 64, cf.CF_F32, 2)
     assert cf.cf_sizes(d) == (256 * 16, 64 * 4, 256 * 64 * 4, 256 * 64 * 4)
+    d = cf.desc(4096, 3072, cf.CF_BF16, 2, cf.CF_SCALE_RANK1)          # v[C] then u[N]
+    assert cf.cf_sizes(d)[1] == (3072 + 4096) * 4
+    # the workspace of a rank-1 tensor also holds one partial row sum per token and column tile
+    ch = cf.cf_workspace_bytes([cf.desc(4096, 3072, cf.CF_BF16, 2, cf.CF_SCALE_CHANNEL)])
+    assert cf.cf_workspace_bytes([d]) >= ch + 4096 * 3 * 4
 
 
 BAD = [
@@ -59,6 +64,8 @@ BAD = [
     (cf.desc(16, 64, cf.CF_BF16, 3), cf.CF_ERR_UNSUPPORTED),
     (cf.desc(16, 64, 7, 2), cf.CF_ERR_UNSUPPORTED),
     (cf.desc(16, 64, cf.CF_BF16, 2, 9), cf.CF_ERR_UNSUPPORTED),
+    (cf.desc(16, 64, cf.CF_BF16, 4, cf.CF_SCALE_RANK1), cf.CF_ERR_UNSUPPORTED),         # u v^T goes with 1-/2-bit codes
+    (cf.desc(16, 128 * 1024 + 8, cf.CF_BF16, 2, cf.CF_SCALE_RANK1), cf.CF_ERR_SHAPE),   # more than 128 column tiles
 ]
 
 

@@ -335,3 +335,81 @@ def test_configs_reduced(name, shrink):
         xs.append([x.clone() for x in stream.advance()])
     for flags in (0, cf.CF_FLAG_SINGLE_PASS):
         run_parity(descs, cf.options(flags=flags), xs, mode="fused", tag=f"{name} flags={flags}")
+
+
+# ---------------------------------------------------------------- rank-1 scales u v^T (App. D "Quantization")
+
+R1 = cf.CF_SCALE_RANK1
+
+
+def token_outlier_stream(shape, dtype, steps, seed):
+    """A drift whose per-token magnitude spans two decades: what the row factor u is for."""
+    n, c = shape
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    row_gain = torch.exp(torch.randn((n, 1), generator=g, device=DEV) * 1.5)
+    x = torch.randn(shape, generator=g, device=DEV)
+    out = []
+    for _ in range(steps):
+        out.append(x.to(torch.bfloat16).contiguous() if dtype == cf.CF_BF16 else x.clone())
+        x = x + 0.05 * row_gain * torch.randn(shape, generator=g, device=DEV)
+    return out
+
+
+@pytest.mark.parametrize("bits", [1, 2])
+@pytest.mark.parametrize("dtype", [cf.CF_BF16, cf.CF_F32])
+@pytest.mark.parametrize("mode", ["fused", "split"])
+def test_parity_rank1_shapes(bits, dtype, mode):
+    """Row sums cross lanes, the two waves of a tile and several column tiles; the total crosses the
+    1024 lanes of the finalising block with one row (N <= 1024) or several (N = 2500) per lane."""
+    for k, (n, c) in enumerate(SHAPES + [(2500, 264), (1025, 1032)]):
+        say(f"rank1 bits={bits} dtype={dtype} mode={mode} N={n} C={c}")
+        d = cf.desc(n, c, dtype, bits, R1)
+        xs = token_outlier_stream((n, c), dtype, steps=4, seed=300 + k)
+        run_parity([d], cf.options(), [[x] for x in xs], mode=mode, tag=f"rank1 N{n}C{c}")
+
+
+@pytest.mark.parametrize("ef", [cf.CF_EF_RECON, cf.CF_EF_LITERAL, cf.CF_EF_OFF])
+def test_parity_rank1_ef_modes_tile_heights(ef):
+    n, c = 333, 1096
+    for tile_rows in (0, 8, 16, 32, 64):
+        for err_dtype in (cf.CF_F32, cf.CF_BF16):
+            say(f"rank1 ef={ef} tile_rows={tile_rows} err_dtype={err_dtype}")
+            d = cf.desc(n, c, cf.CF_BF16, 2, R1)
+            xs = token_outlier_stream((n, c), cf.CF_BF16, steps=4, seed=17 + ef)
+            run_parity([d], cf.options(ef=ef, err_dtype=err_dtype, tile_rows=tile_rows), [[x] for x in xs])
+
+
+def test_parity_rank1_zero_residual_and_mixed_batch():
+    """An unchanged tensor has mean |z| = 0, for which u is defined as 0; and rank-1 tensors share
+    one batch (and one launch of every kernel) with channel- and group-scaled ones.  The single-pass
+    flag is accepted and ignored for a context that holds a rank-1 tensor."""
+    n, c = 130, 1152
+    x = drift_stream((n, c), cf.CF_BF16, steps=1, seed=5, device=DEV)[0]
+    say("rank1 zero residual")
+    run_parity([cf.desc(n, c, cf.CF_BF16, 1, R1)], cf.options(), [[x], [x], [x]], tag="rank1 zero")
+    descs = [cf.desc(203, 1096, cf.CF_BF16, 2, R1), cf.desc(64, 256, cf.CF_F32, 4, GR), cf.desc(67, 3072, cf.CF_BF16, 1, CH),
+             cf.desc(1500, 136, cf.CF_F32, 1, R1), cf.desc(9, 8, cf.CF_BF16, 2, R1)]
+    streams = [token_outlier_stream((int(d.n_tokens), int(d.n_channels)), int(d.dtype), 4, 40 + t) for t, d in enumerate(descs)]
+    for flags in (0, cf.CF_FLAG_SINGLE_PASS):
+        say(f"rank1 mixed batch flags={flags}")
+        run_parity(descs, cf.options(flags=flags), [[s[k] for s in streams] for k in range(4)], tag="rank1 mixed")
+
+
+def test_rank1_beats_channel_scale_on_token_outliers():
+    """Why the paper uses u v^T: with token-wise outliers the rank-1 scale leaves a smaller error
+    than the channel scale at the same code width (both computed by the library)."""
+    n, c = 512, 1024
+    xs = token_outlier_stream((n, c), cf.CF_F32, steps=2, seed=9)
+    rel = {}
+    for scale in (CH, R1):
+        sess = CodecSession([cf.desc(n, c, cf.CF_F32, 2, scale)], cf.options(), device=DEV)
+        try:
+            sess.warmup([xs[0]])
+            sess.step_fused([xs[1]])
+            cf.cf_check_device(sess.ctx, sess.stream_handle)
+            rel[scale] = float((sess.recon[0] - xs[1]).norm() / (xs[1] - xs[0]).norm())
+        finally:
+            sess.close()
+    say(f"relative residual error: channel {rel[CH]:.3f}, rank-1 {rel[R1]:.3f}")
+    assert rel[R1] < rel[CH]
