@@ -42,6 +42,8 @@ def parse_args():
     ap.add_argument("--tile-rows", type=int, default=0)
     ap.add_argument("--encode-rows", type=int, default=0)
     ap.add_argument("--tensors", type=int, default=0, help="override the workload's tensor count (exploration only)")
+    ap.add_argument("--scale", default="", choices=("", "channel", "group", "rank1"), help="override the workload's scale kind (exploration only)")
+    ap.add_argument("--bits", type=int, default=0, help="override the workload's code width (exploration only)")
     ap.add_argument("--sub-batch", type=int, default=0, help="issue the step as calls over ranges of this many tensors (exploration only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
@@ -96,13 +98,31 @@ def bytes_per_element(wl, bits: int, ef: int, err_bytes: int = 4) -> float:
     b = sx + sx + sx + err_bytes + bits / 8.0          # x, recon read, recon write, err write, codes
     if ef != 0:
         b += err_bytes                                  # LITERAL / OFF also read err
-    b += 4.0 / wl.group if wl.scale == "group" else 4.0 / wl.n_tokens
+    b += scale_bytes_per_element(wl)
     return b
+
+
+def scale_bytes_per_element(wl) -> float:
+    if wl.scale == "group":
+        return 4.0 / wl.group
+    if wl.scale == "rank1":                             # v[C] and u[N]
+        return 4.0 / wl.n_tokens + 4.0 / wl.n_channels
+    return 4.0 / wl.n_tokens
 
 
 def step_bytes(wl, ef: int) -> float:
     per_tensor = wl.n_tokens * wl.n_channels
     return sum(per_tensor * bytes_per_element(wl, wl.bits_of(t), ef) for t in range(wl.n_tensors))
+
+
+def apply_overrides(wl, args):
+    if args.tensors:
+        wl = wl.scaled(n_tensors=args.tensors)
+    if args.scale:
+        wl = wl.scaled(scale=args.scale)
+    if args.bits:
+        wl = wl.scaled(bits=(args.bits,))
+    return wl
 
 
 def run_workload(name: str, args, events: HipEvents | None):
@@ -113,11 +133,10 @@ def run_workload(name: str, args, events: HipEvents | None):
     from workloads import CONFIGS, ActivationStream
 
     wl = CONFIGS[name]
-    if args.tensors:
-        wl = wl.scaled(n_tensors=args.tensors)
+    wl = apply_overrides(wl, args)
     dev = "cuda:0"
     dt = cf.CF_F32 if wl.dtype == "f32" else cf.CF_BF16
-    scale = cf.CF_SCALE_GROUP if wl.scale == "group" else cf.CF_SCALE_CHANNEL
+    scale = {"group": cf.CF_SCALE_GROUP, "rank1": cf.CF_SCALE_RANK1}.get(wl.scale, cf.CF_SCALE_CHANNEL)
     descs = [cf.desc(wl.n_tokens, wl.n_channels, dt, wl.bits_of(t), scale, wl.group) for t in range(wl.n_tensors)]
     opts = cf.options(ef=args.ef, flags=args.flags, tile_rows=args.tile_rows, encode_rows=args.encode_rows)
 
@@ -215,7 +234,7 @@ def kernel_algorithmic_bytes(nm: str, wl, ef: int) -> float:
         n = wl.n_tokens * wl.n_channels
         sx = 4 if wl.dtype == "f32" else 2
         bits = wl.bits_of(t)
-        scale_b = 4.0 / wl.group if wl.scale == "group" else 4.0 / wl.n_tokens
+        scale_b = scale_bytes_per_element(wl)
         if nm == "k_colreduce":
             per = 2 * sx + (4 if ef else 0)
         elif nm == "k_encode":          # reads x, recon (+err); writes codes, err, recon
@@ -239,11 +258,11 @@ def cpu_baseline(wl, ef: int, budget_s: float = 15.0):
     small = wl.scaled(n_tensors=min(wl.n_tensors, 3))
     stream = ActivationStream(small, device="cpu")
     cfgs = [oracle.Config(wl.n_tokens, wl.n_channels, dtype=oracle.F32 if wl.dtype == "f32" else oracle.BF16,
-                          bits=wl.bits_of(t), scale=oracle.SCALE_GROUP if wl.scale == "group" else oracle.SCALE_CHANNEL,
+                          bits=wl.bits_of(t), scale={"group": oracle.SCALE_GROUP, "rank1": oracle.SCALE_RANK1}.get(wl.scale, oracle.SCALE_CHANNEL),
                           group=wl.group, ef=ef) for t in range(small.n_tensors)]
     state = [oracle.warmup(cfgs[t], as_numpy(stream.current[t])) for t in range(small.n_tensors)]
     done, spent, nbytes = 0, 0.0, 0.0
-    while spent < budget_s and done < 12:
+    while spent < budget_s and done < 64:
         xs = [as_numpy(x) for x in stream.advance()]
         for t in range(small.n_tensors):
             t0 = time.perf_counter()
@@ -300,7 +319,7 @@ def main():
         kb = kernel_algorithmic_bytes(kname, wl, args.ef)
         achieved = kb / (kms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(kname, head),
+                    "frac": achieved / HBM_PEAK_GBPS, "traffic": None if (args.scale or args.bits or args.tensors or args.ef or args.flags) else read_traffic(kname, head),
                     "algorithmic_bytes_per_launch": kb, "avg_launch_ms": kms}
     cpu = None if args.no_cpu_baseline else cpu_baseline(wl, args.ef)
     if events is not None:

@@ -86,8 +86,11 @@ typedef enum { CF_SCALE_CHANNEL = 0, CF_SCALE_GROUP = 1, CF_SCALE_RANK1 = 2 } cf
  *   CF_EF_LITERAL z = (x_t - recon_{t-1}) + e_{t-1}; e_t = z - D.
  *   CF_EF_OFF     z = (x_t - recon_{t-1}) - e_{t-1} (the true residual
  *                 x_t - x_{t-1}: the paper's no-feedback ablation);
- *                 e_t = e_{t-1} + (z - D). */
-typedef enum { CF_EF_RECON = 0, CF_EF_LITERAL = 1, CF_EF_OFF = 2 } cf_ef_mode;
+ *                 e_t = e_{t-1} + (z - D).
+ *   CF_EF_NAIVE   z = x_t: the activation itself is compressed (Sec. 3.1, the
+ *                 baseline residual compression is compared with); recon_t = D,
+ *                 e_t = z - D = x_t - recon_t; neither recon nor e is read. */
+typedef enum { CF_EF_RECON = 0, CF_EF_LITERAL = 1, CF_EF_OFF = 2, CF_EF_NAIVE = 3 } cf_ef_mode;
 
 typedef struct {
     int64_t n_tokens;   /* N >= 1 */

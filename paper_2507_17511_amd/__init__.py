@@ -24,7 +24,7 @@ CF_F32, CF_BF16 = 0, 1
 # cf_scale_kind
 CF_SCALE_CHANNEL, CF_SCALE_GROUP, CF_SCALE_RANK1 = 0, 1, 2
 # cf_ef_mode
-CF_EF_RECON, CF_EF_LITERAL, CF_EF_OFF = 0, 1, 2
+CF_EF_RECON, CF_EF_LITERAL, CF_EF_OFF, CF_EF_NAIVE = 0, 1, 2, 3
 CF_FLAG_SINGLE_PASS = 0x1
 
 EXPORTS = ["cf_sizes", "cf_workspace_bytes", "cf_init", "cf_warmup", "cf_set_warm", "cf_compress",

@@ -39,7 +39,7 @@ cf_status check_opts(const cf_options *o, cf_options &out)
     out.tile_rows = 0;
     out.encode_rows = 0;
     if (!o) return CF_OK;
-    if (o->ef != CF_EF_RECON && o->ef != CF_EF_LITERAL && o->ef != CF_EF_OFF) return CF_ERR_UNSUPPORTED;
+    if (o->ef != CF_EF_RECON && o->ef != CF_EF_LITERAL && o->ef != CF_EF_OFF && o->ef != CF_EF_NAIVE) return CF_ERR_UNSUPPORTED;
     if (o->err_dtype != CF_F32 && o->err_dtype != CF_BF16) return CF_ERR_UNSUPPORTED;
     if (o->flags & ~CF_FLAG_SINGLE_PASS) return CF_ERR_UNSUPPORTED;
     if (o->tile_rows != 0 && o->tile_rows != 8 && o->tile_rows != 16 && o->tile_rows != 32 && o->tile_rows != 64)
@@ -247,6 +247,7 @@ struct cf_ctx {
         r.group_lo = L.group_prefix[first];
         r.group_hi = L.group_prefix[first + count];
         r.only_group_scale = 0;
+        r.naive = opts.ef == CF_EF_NAIVE;
         r.dts = descs[first].dtype;
         for (int32_t t = first; t < first + count; ++t)
             if (descs[t].dtype != descs[first].dtype) r.dts = 2;

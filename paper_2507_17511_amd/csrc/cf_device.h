@@ -15,7 +15,7 @@ namespace dev {
 
 constexpr int F32 = 0, BF16 = 1;
 constexpr int SCALE_CHANNEL = 0, SCALE_GROUP = 1, SCALE_RANK1 = 2;
-constexpr int EF_RECON = 0, EF_LITERAL = 1, EF_OFF = 2;
+constexpr int EF_RECON = 0, EF_LITERAL = 1, EF_OFF = 2, EF_NAIVE = 3;
 
 #define CF_GLOBAL __attribute__((address_space(1)))
 
@@ -136,7 +136,7 @@ __device__ __forceinline__ F8 residual8(const F8 &x, const F8 &b, const F8 &e)
     F8 z;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-        float r = x.v[k] - b.v[k];
+        float r = (EF == EF_NAIVE) ? x.v[k] : x.v[k] - b.v[k];     // naive: the activation itself (Sec. 3.1)
         if (EF == EF_LITERAL) r = r + e.v[k];
         if (EF == EF_OFF) r = r - e.v[k];
         z.v[k] = r;

@@ -91,6 +91,7 @@ struct LaunchRange {
     uint32_t group_lo, group_hi;
     int32_t dts;                // storage dtype of every tensor in the range (cf_dtype), or 2 if mixed
     int32_t only_group_scale;   // tiled encode: skip tensors the single-pass kernel covers
+    int32_t naive;              // decode: recon_t = D instead of recon_{t-1} + D (CF_EF_NAIVE)
 };
 
 enum class Op { Compress, StepFused };

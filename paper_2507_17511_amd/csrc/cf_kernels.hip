@@ -103,8 +103,8 @@ __device__ __forceinline__ F8 rows8(const TensorDev &d, const TensorPtrs &p, int
         if (i < d.n_tokens && (!R1 || chunk < d.n_chunks)) {
             int64_t e = i * d.n_channels + (int64_t)chunk * kChunk;
             xr[r].load_stream(p.x, e);       // streaming: the batch is far larger than any cache
-            br[r].load_stream(p.recon, e);
-            if (EF != EF_RECON) er[r].load(p.err, e); else er[r].zero();
+            if (EF != EF_NAIVE) br[r].load_stream(p.recon, e); else br[r].zero();
+            if (EF == EF_LITERAL || EF == EF_OFF) er[r].load(p.err, e); else er[r].zero();
         } else {
             xr[r].zero();
             br[r].zero();
@@ -299,8 +299,8 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
             if (i < row1 && cvalid) {
                 int64_t e = i * C + (int64_t)chunk * kChunk;
                 xr[u].load(p.x, e);
-                br[u].load(p.recon, e);
-                if (EF != EF_RECON) er[u].load(p.err, e); else er[u].zero();
+                if (EF != EF_NAIVE) br[u].load(p.recon, e); else br[u].zero();
+                if (EF == EF_LITERAL || EF == EF_OFF) er[u].load(p.err, e); else er[u].zero();
             } else {
                 xr[u].zero();
                 br[u].zero();
@@ -347,7 +347,7 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
             if (FUSED) {
                 F8 nb;
 #pragma unroll
-                for (int k = 0; k < 8; ++k) nb.v[k] = b.v[k] + dq.v[k];
+                for (int k = 0; k < 8; ++k) nb.v[k] = (EF == EF_NAIVE) ? dq.v[k] : b.v[k] + dq.v[k];
                 Raw8<DT> out;
                 out.narrow(nb);
                 out.store(p.recon, e);
@@ -382,8 +382,9 @@ __global__ __launch_bounds__(kTileThreads) void k_encode(BatchView v, LaunchRang
 
 // ---------------------------------------------------------------- a6 + a8: receiver decode
 
+// replace: recon_t = D (naive compression) instead of recon_{t-1} + D.
 template <int DT, int BITS, int MODE>
-__device__ __forceinline__ void decode_tile(const TileCtx &c)
+__device__ __forceinline__ void decode_tile(const TileCtx &c, bool replace)
 {
     const TensorDev &d = c.d;
     const TensorPtrs &p = c.p;
@@ -406,7 +407,7 @@ __device__ __forceinline__ void decode_tile(const TileCtx &c)
         for (int u = 0; u < U; ++u) {
             int64_t i = i0 + u;
             if (i < row1) {
-                br[u].load(p.recon, i * C + (int64_t)chunk * kChunk);
+                if (!replace) br[u].load(p.recon, i * C + (int64_t)chunk * kChunk); else br[u].zero();
                 pk[u] = load_codes<BITS>(p.codes + i * row_bytes, chunk);
                 sg[u] = (MODE == 1) ? gconst<float>(p.scales)[i * n_groups + (chunk >> 4)]
                                     : (MODE == 2) ? gconst<float>(p.scales)[C + i] : 0.0f;
@@ -431,7 +432,7 @@ __device__ __forceinline__ void decode_tile(const TileCtx &c)
             F8 dq, b = br[u].widen(), nb;
             dequant8<BITS>(pk[u], s, dq);
 #pragma unroll
-            for (int k = 0; k < 8; ++k) nb.v[k] = b.v[k] + dq.v[k];
+            for (int k = 0; k < 8; ++k) nb.v[k] = replace ? dq.v[k] : b.v[k] + dq.v[k];
             Raw8<DT> out;
             out.narrow(nb);
             out.store(p.recon, i * C + (int64_t)chunk * kChunk);
@@ -439,24 +440,24 @@ __device__ __forceinline__ void decode_tile(const TileCtx &c)
     }
 }
 
-template <int DT> __device__ __forceinline__ void decode_dispatch(const TileCtx &c)
+template <int DT> __device__ __forceinline__ void decode_dispatch(const TileCtx &c, bool replace)
 {
     const TensorDev &d = c.d;
-    if (d.scale == SCALE_GROUP) { decode_tile<DT, 4, 1>(c); return; }
+    if (d.scale == SCALE_GROUP) { decode_tile<DT, 4, 1>(c, replace); return; }
     if (d.scale == SCALE_RANK1) {
-        if (d.bits == 1) decode_tile<DT, 1, 2>(c); else decode_tile<DT, 2, 2>(c);
+        if (d.bits == 1) decode_tile<DT, 1, 2>(c, replace); else decode_tile<DT, 2, 2>(c, replace);
         return;
     }
-    if (d.bits == 1) decode_tile<DT, 1, 0>(c);
-    else if (d.bits == 2) decode_tile<DT, 2, 0>(c);
-    else decode_tile<DT, 4, 0>(c);
+    if (d.bits == 1) decode_tile<DT, 1, 0>(c, replace);
+    else if (d.bits == 2) decode_tile<DT, 2, 0>(c, replace);
+    else decode_tile<DT, 4, 0>(c, replace);
 }
 
 template <int DTS>
 __global__ __launch_bounds__(kTileThreads) void k_decode(BatchView v, LaunchRange r)
 {
     TileCtx c = locate_tile<true>(v, r);
-    if (is_bf16<DTS>(c.d)) decode_dispatch<BF16>(c); else decode_dispatch<F32>(c);
+    if (is_bf16<DTS>(c.d)) decode_dispatch<BF16>(c, r.naive != 0); else decode_dispatch<F32>(c, r.naive != 0);
 }
 
 // ---------------------------------------------------------------- pointer table upload
@@ -493,10 +494,12 @@ hipError_t launch_upload_ptrs(const PtrChunk &chunk, TensorPtrs *dst, int n, hip
         if (err_dtype == BF16) {                                                                        \
             if (ef == EF_RECON) CF_LAUNCH_DTS(KERNEL, EF_RECON, BF16 __VA_ARGS__);                      \
             else if (ef == EF_LITERAL) CF_LAUNCH_DTS(KERNEL, EF_LITERAL, BF16 __VA_ARGS__);             \
+            else if (ef == EF_NAIVE) CF_LAUNCH_DTS(KERNEL, EF_NAIVE, BF16 __VA_ARGS__);                 \
             else CF_LAUNCH_DTS(KERNEL, EF_OFF, BF16 __VA_ARGS__);                                       \
         } else {                                                                                        \
             if (ef == EF_RECON) CF_LAUNCH_DTS(KERNEL, EF_RECON, F32 __VA_ARGS__);                       \
             else if (ef == EF_LITERAL) CF_LAUNCH_DTS(KERNEL, EF_LITERAL, F32 __VA_ARGS__);              \
+            else if (ef == EF_NAIVE) CF_LAUNCH_DTS(KERNEL, EF_NAIVE, F32 __VA_ARGS__);                  \
             else CF_LAUNCH_DTS(KERNEL, EF_OFF, F32 __VA_ARGS__);                                        \
         }                                                                                               \
     } while (0)

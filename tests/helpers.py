@@ -25,8 +25,10 @@ BF16_ULP_TOL = 1
 
 
 def oracle_config(d: cf.cf_tensor_desc, opts: cf.cf_options) -> oracle.Config:
+    # naive compression is a function of its own in the oracle, not an error-feedback mode
+    ef = 0 if opts.ef == cf.CF_EF_NAIVE else int(opts.ef)
     return oracle.Config(int(d.n_tokens), int(d.n_channels), dtype=int(d.dtype), bits=int(d.bits), scale=int(d.scale),
-                         group=int(d.group) if d.scale == cf.CF_SCALE_GROUP else 128, ef=int(opts.ef),
+                         group=int(d.group) if d.scale == cf.CF_SCALE_GROUP else 128, ef=ef,
                          err_dtype=int(opts.err_dtype))
 
 
@@ -88,6 +90,16 @@ class OracleState:
         self.recon[t], self.err[t] = oracle.warmup(self.cfg[t], x0)
 
     def step(self, t: int, x: np.ndarray):
+        if self.opts.ef == cf.CF_EF_NAIVE:
+            # Sec. 3.1's baseline: recon_t = D(C(x_t)).  The library also reports e_t = x_t - D; the
+            # oracle's stages give D, and one fp32 subtraction gives what e must hold.
+            cfg = self.cfg[t]
+            self.recon[t], self.codes[t], self.scales[t] = oracle.naive(cfg, x)
+            dec = oracle.decode(cfg, oracle.unpack(cfg, self.codes[t]), self.scales[t])
+            xf = bf16_to_f32(x) if cfg.dtype == oracle.BF16 else x       # widening is exact: a 16-bit shift
+            lost = (xf.reshape(cfg.shape).astype(np.float32) - dec).astype(np.float32)
+            self.err[t] = oracle.f32_to_bf16(lost) if cfg.err_dtype == oracle.BF16 else lost
+            return
         self.codes[t], self.scales[t] = oracle.step(self.cfg[t], x, self.recon[t], self.err[t])
 
 

@@ -413,3 +413,37 @@ def test_rank1_beats_channel_scale_on_token_outliers():
             sess.close()
     say(f"relative residual error: channel {rel[CH]:.3f}, rank-1 {rel[R1]:.3f}")
     assert rel[R1] < rel[CH]
+
+
+# ---------------------------------------------------------------- naive compression (Sec. 3.1) and the error study
+
+@pytest.mark.parametrize("bits,scale", COMBOS + [(1, R1), (2, R1)])
+@pytest.mark.parametrize("dtype", [cf.CF_BF16, cf.CF_F32])
+@pytest.mark.parametrize("mode", ["fused", "split"])
+def test_parity_naive_compression(bits, scale, dtype, mode):
+    """CF_EF_NAIVE: codes and scales of x_t itself, recon_t = D, e_t = x_t - D; the state of the step
+    before is never read (it is deliberately left holding other values by the warm-up)."""
+    for k, (n, c) in enumerate([(203, 1152), (9, 8), (67, 3072)]):
+        if scale == GR and c % 128:
+            continue
+        for err_dtype in (cf.CF_F32, cf.CF_BF16):
+            say(f"naive bits={bits} scale={scale} dtype={dtype} mode={mode} err_dtype={err_dtype} N={n} C={c}")
+            d = cf.desc(n, c, dtype, bits, scale)
+            xs = drift_stream((n, c), dtype, steps=3, seed=500 + k, sigma=0.3, device=DEV)
+            run_parity([d], cf.options(ef=cf.CF_EF_NAIVE, err_dtype=err_dtype), [[x] for x in xs], mode=mode, tag="naive")
+
+
+@pytest.mark.parametrize("bits", [1, 2])
+def test_error_study_orders_the_strategies_as_the_paper_does(bits):
+    """Sec. 3.1-3.3 on a synthetic stationary stream with sigma_Delta^2 / sigma_a^2 = 0.01: naive compression is
+    far worse than residual compression; without feedback the total error keeps growing; with feedback it
+    settles.  All numbers come from the library's own state buffers."""
+    from paper_2507_17511_amd import error_study
+    res = error_study.run(n_tokens=512, n_channels=1024, steps=28, bits=bits, rho=0.995, seed=3, device=DEV)
+    checks = error_study.ordering_holds(res)
+    say(f"error study bits={bits}: total error at the last step naive {res['naive']['total'][-1]:.3e}, "
+        f"residual {res['residual']['total'][-1]:.3e}, residual+ef {res['residual+ef']['total'][-1]:.3e}")
+    assert all(checks.values()), checks
+    # 1-bit on a Gaussian signal loses 1 - 2/pi of the energy: the delta of the paper's compressor model
+    if bits == 1:
+        assert abs(res["naive"]["compression"][-1] - (1 - 2 / np.pi)) < 0.02
