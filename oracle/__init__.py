@@ -21,7 +21,7 @@ _SRC = os.path.join(_HERE, "cf_oracle.c")
 _LIB = os.path.join(_HERE, "libcf_oracle.so")
 
 F32, BF16 = 0, 1
-SCALE_CHANNEL, SCALE_GROUP, SCALE_RANK1 = 0, 1, 2
+SCALE_CHANNEL, SCALE_GROUP, SCALE_RANK1, SPARSE_NM = 0, 1, 2, 3
 EF_RECON, EF_LITERAL, EF_OFF = 0, 1, 2
 
 CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared", "-Wall", "-Wextra"]
@@ -96,9 +96,11 @@ def lib() -> ctypes.CDLL:
         L.cfo_codes_bytes.argtypes = [cp]
         L.cfo_scales_count.restype = ctypes.c_int64
         L.cfo_scales_count.argtypes = [cp]
+        L.cfo_nm_values_offset.restype = ctypes.c_int64
+        L.cfo_nm_values_offset.argtypes = [cp]
         L.cfo_check.argtypes = [cp]
         for name, n in [("cfo_residual", 4), ("cfo_scales", 2), ("cfo_select", 3), ("cfo_pack", 2),
-                        ("cfo_unpack", 2), ("cfo_decode", 3)]:
+                        ("cfo_unpack", 2), ("cfo_decode", 3), ("cfo_nm_select", 2), ("cfo_nm_pack", 3), ("cfo_nm_unpack", 2)]:
             getattr(L, name).restype = None
             getattr(L, name).argtypes = [cp] + [vp] * n
         for name, n in [("cfo_warmup", 3), ("cfo_compress", 5), ("cfo_decompress", 3), ("cfo_step", 5),
@@ -142,7 +144,13 @@ def treesum(v: np.ndarray) -> np.float32:
 
 # ---------------------------------------------------------------- stages
 
+def codes_bytes(cfg: Config) -> int:
+    return int(lib().cfo_codes_bytes(ctypes.byref(cfg.c())))
+
+
 def alloc_codes(cfg: Config) -> np.ndarray:
+    if cfg.scale == SPARSE_NM:          # masks, then values: not a [tokens, bytes] matrix
+        return np.zeros(codes_bytes(cfg), dtype=np.uint8)
     return np.zeros((cfg.n_tokens, cfg.n_channels * cfg.bits // 8), dtype=np.uint8)
 
 
@@ -193,6 +201,34 @@ def decode(cfg: Config, code, s) -> np.ndarray:
     return d
 
 
+# ---------------------------------------------------------------- N:M block sparsifier stages
+
+def nm_select(cfg: Config, z) -> np.ndarray:
+    _chk(z, np.float32, cfg.n_tokens * cfg.n_channels, "z")
+    keep = np.empty(cfg.shape, dtype=np.uint8)
+    lib().cfo_nm_select(ctypes.byref(cfg.c()), _p(z), _p(keep))
+    return keep
+
+
+def nm_pack(cfg: Config, z, keep) -> np.ndarray:
+    _chk(z, np.float32, cfg.n_tokens * cfg.n_channels, "z")
+    _chk(keep, np.uint8, cfg.n_tokens * cfg.n_channels, "keep")
+    wire = alloc_codes(cfg)
+    lib().cfo_nm_pack(ctypes.byref(cfg.c()), _p(z), _p(keep), _p(wire))
+    return wire
+
+
+def nm_unpack(cfg: Config, wire) -> np.ndarray:
+    _chk(wire, np.uint8, codes_bytes(cfg), "wire")
+    d = np.empty(cfg.shape, dtype=np.float32)
+    lib().cfo_nm_unpack(ctypes.byref(cfg.c()), _p(wire), _p(d))
+    return d
+
+
+def nm_values_offset(cfg: Config) -> int:
+    return int(lib().cfo_nm_values_offset(ctypes.byref(cfg.c())))
+
+
 # ---------------------------------------------------------------- whole operations
 
 def _state_chk(cfg, x=None, recon=None, err=None):
@@ -227,7 +263,7 @@ def compress(cfg: Config, x, recon, err):
 def decompress(cfg: Config, codes, s, recon):
     """Receiver half; updates ``recon`` in place."""
     _state_chk(cfg, recon=recon)
-    _chk(codes, np.uint8, cfg.n_tokens * cfg.n_channels * cfg.bits // 8, "codes")
+    _chk(codes, np.uint8, codes_bytes(cfg), "codes")
     _rc(lib().cfo_decompress(ctypes.byref(cfg.c()), _p(codes), _p(s), _p(recon)))
 
 

@@ -62,6 +62,12 @@ int cfo_check(const cfo_config *cfg)
     if (cfg->n_tokens < 1 || cfg->n_channels < 8 || cfg->n_channels % 8 != 0) return -1;
     if (cfg->dtype != CFO_F32 && cfg->dtype != CFO_BF16) return -1;
     if (cfg->err_dtype != CFO_F32 && cfg->err_dtype != CFO_BF16) return -1;
+    if (cfg->scale == CFO_SPARSE_NM) {  /* bits = N kept of every group = M channels */
+        if (cfg->group < 8 || cfg->group > 64 || cfg->group % 8 != 0 || cfg->n_channels % cfg->group != 0) return -1;
+        if (cfg->bits < 1 || cfg->bits >= cfg->group) return -1;
+        if (cfg->ef != CFO_EF_RECON && cfg->ef != CFO_EF_LITERAL && cfg->ef != CFO_EF_OFF) return -1;
+        return 0;
+    }
     if (cfg->bits != 1 && cfg->bits != 2 && cfg->bits != 4) return -1;
     if (cfg->ef != CFO_EF_RECON && cfg->ef != CFO_EF_LITERAL && cfg->ef != CFO_EF_OFF) return -1;
     if (cfg->scale == CFO_SCALE_GROUP) {
@@ -75,8 +81,18 @@ int cfo_check(const cfo_config *cfg)
     return 0;
 }
 
+int64_t cfo_nm_values_offset(const cfo_config *cfg)
+{
+    int64_t mask_bytes = cfg->n_tokens * (cfg->n_channels / 8);
+    return (mask_bytes + 15) / 16 * 16;
+}
+
 int64_t cfo_codes_bytes(const cfo_config *cfg)
 {
+    if (cfg->scale == CFO_SPARSE_NM) {
+        int64_t elem = cfg->dtype == CFO_BF16 ? 2 : 4;
+        return cfo_nm_values_offset(cfg) + cfg->n_tokens * (cfg->n_channels / cfg->group) * cfg->bits * elem;
+    }
     return cfg->n_tokens * (cfg->n_channels * cfg->bits / 8);
 }
 
@@ -86,6 +102,7 @@ int64_t cfo_scales_count(const cfo_config *cfg)
 {
     if (cfg->scale == CFO_SCALE_GROUP) return cfg->n_tokens * (cfg->n_channels / cfg->group);
     if (cfg->scale == CFO_SCALE_RANK1) return cfg->n_channels + cfg->n_tokens;
+    if (cfg->scale == CFO_SPARSE_NM) return 0;
     return cfg->n_channels;
 }
 
@@ -323,6 +340,88 @@ void cfo_decode(const cfo_config *cfg, const uint8_t *code, const float *scales,
 }
 
 /* ------------------------------------------------------------------ */
+/* N:M block sparsifier                                                */
+/* ------------------------------------------------------------------ */
+
+/* Sec. 3.4 names an N:M block sparsifier (selection in linear time, regular
+ * memory access, in place of a global top-k) and gives no more.  Reading:
+ * blocks are M consecutive channels of one token; the N elements of largest
+ * magnitude are kept; magnitudes are ordered by the bit pattern of |z| (the
+ * numeric order for everything but NaN, which sorts above infinity, so the
+ * order is total); of equal magnitudes the lower channel wins.
+ * Element k is kept iff fewer than N elements of its block come before it in
+ * that order. */
+static uint32_t magnitude_key(float v)
+{
+    uint32_t u;
+    memcpy(&u, &v, sizeof u);
+    return u & 0x7fffffffu;
+}
+
+void cfo_nm_select(const cfo_config *cfg, const float *z, uint8_t *keep)
+{
+    int64_t N = cfg->n_tokens, C = cfg->n_channels;
+    int M = cfg->group, K = cfg->bits;
+    for (int64_t i = 0; i < N; ++i)
+        for (int64_t b = 0; b < C / M; ++b) {
+            const float *blk = z + i * C + b * M;
+            for (int k = 0; k < M; ++k) {
+                int before = 0;
+                for (int j = 0; j < M; ++j) {
+                    uint32_t kj = magnitude_key(blk[j]), kk = magnitude_key(blk[k]);
+                    if (kj > kk || (kj == kk && j < k)) ++before;
+                }
+                keep[i * C + b * M + k] = (uint8_t)(before < K);
+            }
+        }
+}
+
+/* The kept values travel in the storage dtype of the tensor (bf16 values are
+ * rounded to nearest even; what the rounding loses stays in the error). */
+void cfo_nm_pack(const cfo_config *cfg, const float *z, const uint8_t *keep, uint8_t *wire)
+{
+    int64_t N = cfg->n_tokens, C = cfg->n_channels;
+    int M = cfg->group, K = cfg->bits;
+    int64_t row_mask_bytes = C / 8;
+    void *values = wire + cfo_nm_values_offset(cfg);
+    memset(wire, 0, (size_t)cfo_codes_bytes(cfg));
+    for (int64_t i = 0; i < N; ++i)
+        for (int64_t b = 0; b < C / M; ++b) {
+            int r = 0;
+            for (int k = 0; k < M; ++k) {
+                int64_t j = b * M + k;
+                if (!keep[i * C + j]) continue;
+                wire[i * row_mask_bytes + j / 8] |= (uint8_t)(1u << (j % 8));
+                store_elem(values, cfg->dtype, (i * (C / M) + b) * K + r, z[i * C + j]);
+                ++r;
+            }
+        }
+}
+
+/* D: the transmitted value where the mask bit is set, +0 elsewhere. */
+void cfo_nm_unpack(const cfo_config *cfg, const uint8_t *wire, float *d)
+{
+    int64_t N = cfg->n_tokens, C = cfg->n_channels;
+    int M = cfg->group, K = cfg->bits;
+    int64_t row_mask_bytes = C / 8;
+    const void *values = wire + cfo_nm_values_offset(cfg);
+    for (int64_t i = 0; i < N; ++i)
+        for (int64_t b = 0; b < C / M; ++b) {
+            int r = 0;
+            for (int k = 0; k < M; ++k) {
+                int64_t j = b * M + k;
+                int set = (wire[i * row_mask_bytes + j / 8] >> (j % 8)) & 1;
+                float v = 0.0f;
+                if (set && r < K) {
+                    v = load_elem(values, cfg->dtype, (i * (C / M) + b) * K + r);
+                    ++r;
+                }
+                d[i * C + j] = v;
+            }
+        }
+}
+
+/* ------------------------------------------------------------------ */
 /* a7, a8: state updates                                               */
 /* ------------------------------------------------------------------ */
 
@@ -399,10 +498,16 @@ int cfo_compress(const cfo_config *cfg, const void *x, const void *recon, void *
     work w;
     if (work_alloc(cfg, &w)) { work_free(&w); return -1; }
     cfo_residual(cfg, x, recon, err, w.z);      /* a1, a2 */
-    cfo_scales(cfg, w.z, scales);               /* a3 */
-    cfo_select(cfg, w.z, scales, w.code);       /* a4 */
-    cfo_pack(cfg, w.code, codes);               /* a5 */
-    cfo_decode(cfg, w.code, scales, w.d);       /* a6 */
+    if (cfg->scale == CFO_SPARSE_NM) {
+        cfo_nm_select(cfg, w.z, w.code);
+        cfo_nm_pack(cfg, w.z, w.code, codes);
+        cfo_nm_unpack(cfg, codes, w.d);
+    } else {
+        cfo_scales(cfg, w.z, scales);               /* a3 */
+        cfo_select(cfg, w.z, scales, w.code);       /* a4 */
+        cfo_pack(cfg, w.code, codes);               /* a5 */
+        cfo_decode(cfg, w.code, scales, w.d);       /* a6 */
+    }
     update_err(cfg, w.z, w.d, err);             /* a7 */
     work_free(&w);
     return 0;
@@ -414,8 +519,12 @@ int cfo_decompress(const cfo_config *cfg, const uint8_t *codes, const float *sca
     if (cfo_check(cfg)) return -1;
     work w;
     if (work_alloc(cfg, &w)) { work_free(&w); return -1; }
-    cfo_unpack(cfg, codes, w.code);
-    cfo_decode(cfg, w.code, scales, w.d);       /* a6 */
+    if (cfg->scale == CFO_SPARSE_NM) {
+        cfo_nm_unpack(cfg, codes, w.d);
+    } else {
+        cfo_unpack(cfg, codes, w.code);
+        cfo_decode(cfg, w.code, scales, w.d);       /* a6 */
+    }
     update_recon(cfg, w.d, recon);              /* a8 */
     work_free(&w);
     return 0;
@@ -429,10 +538,16 @@ int cfo_step(const cfo_config *cfg, const void *x, void *recon, void *err,
     work w;
     if (work_alloc(cfg, &w)) { work_free(&w); return -1; }
     cfo_residual(cfg, x, recon, err, w.z);      /* a1, a2 */
-    cfo_scales(cfg, w.z, scales);               /* a3 */
-    cfo_select(cfg, w.z, scales, w.code);       /* a4 */
-    cfo_pack(cfg, w.code, codes);               /* a5 */
-    cfo_decode(cfg, w.code, scales, w.d);       /* a6 */
+    if (cfg->scale == CFO_SPARSE_NM) {
+        cfo_nm_select(cfg, w.z, w.code);
+        cfo_nm_pack(cfg, w.z, w.code, codes);
+        cfo_nm_unpack(cfg, codes, w.d);
+    } else {
+        cfo_scales(cfg, w.z, scales);               /* a3 */
+        cfo_select(cfg, w.z, scales, w.code);       /* a4 */
+        cfo_pack(cfg, w.code, codes);               /* a5 */
+        cfo_decode(cfg, w.code, scales, w.d);       /* a6 */
+    }
     update_err(cfg, w.z, w.d, err);             /* a7 */
     update_recon(cfg, w.d, recon);              /* a8 */
     work_free(&w);
@@ -448,10 +563,16 @@ int cfo_naive(const cfo_config *cfg, const void *x, void *recon, uint8_t *codes,
     if (work_alloc(cfg, &w)) { work_free(&w); return -1; }
     int64_t total = cfg->n_tokens * cfg->n_channels;
     for (int64_t k = 0; k < total; ++k) w.z[k] = load_elem(x, cfg->dtype, k);
-    cfo_scales(cfg, w.z, scales);
-    cfo_select(cfg, w.z, scales, w.code);
-    cfo_pack(cfg, w.code, codes);
-    cfo_decode(cfg, w.code, scales, w.d);
+    if (cfg->scale == CFO_SPARSE_NM) {
+        cfo_nm_select(cfg, w.z, w.code);
+        cfo_nm_pack(cfg, w.z, w.code, codes);
+        cfo_nm_unpack(cfg, codes, w.d);
+    } else {
+        cfo_scales(cfg, w.z, scales);
+        cfo_select(cfg, w.z, scales, w.code);
+        cfo_pack(cfg, w.code, codes);
+        cfo_decode(cfg, w.code, scales, w.d);
+    }
     for (int64_t k = 0; k < total; ++k) store_elem(recon, cfg->dtype, k, w.d[k]);
     work_free(&w);
     return 0;

@@ -7,6 +7,8 @@
  *   - error feedback kept at the sender                      Sec. 3.2; App. D "Residual Base and Error Feedback"
  *   - warm-up seeds the base with the uncompressed tensor    App. D "Warmup Implementation"; App. H.2
  *   - 1-bit / 2-bit code books and the channel scale v_j     App. D "Quantization"
+ *   - N:M block sparsifier under the same residual recursion  Sec. 3.4 (named there, not specified:
+ *     block shape, tie rule and wire format are this build's reading; parity unpinned by the paper)
  * Where the paper is silent (4-bit codes, scale groups, packing, tie rules,
  * summation order) the readings are stated at each function.
  *
@@ -28,16 +30,16 @@ extern "C" {
 #endif
 
 enum { CFO_F32 = 0, CFO_BF16 = 1 };
-enum { CFO_SCALE_CHANNEL = 0, CFO_SCALE_GROUP = 1, CFO_SCALE_RANK1 = 2 };
+enum { CFO_SCALE_CHANNEL = 0, CFO_SCALE_GROUP = 1, CFO_SCALE_RANK1 = 2, CFO_SPARSE_NM = 3 };
 enum { CFO_EF_RECON = 0, CFO_EF_LITERAL = 1, CFO_EF_OFF = 2 };
 
 typedef struct {
     int64_t n_tokens;    /* N */
     int64_t n_channels;  /* C, multiple of 8 */
     int32_t dtype;       /* dtype of x and recon: CFO_F32 | CFO_BF16 */
-    int32_t bits;        /* 1, 2 or 4 */
-    int32_t scale;       /* CFO_SCALE_* */
-    int32_t group;       /* channels per group when scale == GROUP */
+    int32_t bits;        /* 1, 2 or 4; with CFO_SPARSE_NM: N, the values kept per block */
+    int32_t scale;       /* CFO_SCALE_*, or CFO_SPARSE_NM for the N:M block sparsifier (no scales) */
+    int32_t group;       /* channels per group when scale == GROUP; with CFO_SPARSE_NM: M, the block length */
     int32_t ef;          /* CFO_EF_* */
     int32_t err_dtype;   /* dtype of the error buffer */
 } cfo_config;
@@ -56,6 +58,15 @@ void cfo_select(const cfo_config *cfg, const float *z, const float *scales, uint
 void cfo_pack(const cfo_config *cfg, const uint8_t *code, uint8_t *packed);
 void cfo_unpack(const cfo_config *cfg, const uint8_t *packed, uint8_t *code);
 void cfo_decode(const cfo_config *cfg, const uint8_t *code, const float *scales, float *d);
+
+/* N:M block sparsifier (scale == CFO_SPARSE_NM): of every M consecutive channels of a token the N of
+ * largest magnitude are kept.  keep[i*C + j] is 1 for a kept element.  The wire holds one mask bit per
+ * element (bit j%8 of byte j/8 of the token's C/8 mask bytes), then, from cfo_nm_values_offset on, the
+ * kept values in the storage dtype, token-major, N per block in channel order. */
+void cfo_nm_select(const cfo_config *cfg, const float *z, uint8_t *keep);
+void cfo_nm_pack(const cfo_config *cfg, const float *z, const uint8_t *keep, uint8_t *wire);
+void cfo_nm_unpack(const cfo_config *cfg, const uint8_t *wire, float *d);
+int64_t cfo_nm_values_offset(const cfo_config *cfg);
 
 /* Sizes in bytes/elements of the per-tensor buffers. */
 int64_t cfo_codes_bytes(const cfo_config *cfg);

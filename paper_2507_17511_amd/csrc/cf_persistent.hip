@@ -196,7 +196,11 @@ template <int ET, bool FUSED>
 __global__ __launch_bounds__(kPersistThreads, 2) void k_persistent(BatchView v, LaunchRange r)
 {
     __shared__ Shared sh;
-    for (uint32_t item = r.item_lo + blockIdx.x; item < r.item_hi; item += gridDim.x) {
+    // Workgroups are handed to the 8 XCDs in turn (blockIdx.x % 8).  Numbering them XCD-major puts
+    // the consecutive items of one reduction group on one XCD, behind one L2.
+    const uint32_t q = gridDim.x >> 3, rem = gridDim.x & 7u, xcd = blockIdx.x & 7u;
+    const uint32_t vb = xcd * q + (xcd < rem ? xcd : rem) + (blockIdx.x >> 3);
+    for (uint32_t item = r.item_lo + vb; item < r.item_hi; item += gridDim.x) {
         const int t = find_slot(v.item_prefix, r.first, r.first + r.count, item);
         const TensorDev d = v.descs[t];                             // by value: scalar registers, never re-read
         const TensorPtrs p = v.ptrs[t];
