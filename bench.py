@@ -42,7 +42,7 @@ def parse_args():
     ap.add_argument("--tile-rows", type=int, default=0)
     ap.add_argument("--encode-rows", type=int, default=0)
     ap.add_argument("--tensors", type=int, default=0, help="override the workload's tensor count (exploration only)")
-    ap.add_argument("--scale", default="", choices=("", "channel", "group", "rank1"), help="override the workload's scale kind (exploration only)")
+    ap.add_argument("--scale", default="", choices=("", "channel", "group", "rank1", "nm"), help="override the workload's scale kind (exploration only)")
     ap.add_argument("--bits", type=int, default=0, help="override the workload's code width (exploration only)")
     ap.add_argument("--sub-batch", type=int, default=0, help="issue the step as calls over ranges of this many tensors (exploration only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -95,14 +95,22 @@ class HipEvents:
 
 def bytes_per_element(wl, bits: int, ef: int, err_bytes: int = 4) -> float:
     sx = 4 if wl.dtype == "f32" else 2
-    b = sx + sx + sx + err_bytes + bits / 8.0          # x, recon read, recon write, err write, codes
+    b = sx + sx + sx + err_bytes + code_bytes_per_element(wl, bits)     # x, recon read, recon write, err write, codes
     if ef != 0:
         b += err_bytes                                  # LITERAL / OFF also read err
     b += scale_bytes_per_element(wl)
     return b
 
 
+def code_bytes_per_element(wl, bits: int) -> float:
+    if wl.scale == "nm":                                # a mask byte and `bits` values per block of 8
+        return (1 + bits * (4 if wl.dtype == "f32" else 2)) / 8.0
+    return bits / 8.0
+
+
 def scale_bytes_per_element(wl) -> float:
+    if wl.scale == "nm":
+        return 0.0
     if wl.scale == "group":
         return 4.0 / wl.group
     if wl.scale == "rank1":                             # v[C] and u[N]
@@ -119,7 +127,7 @@ def apply_overrides(wl, args):
     if args.tensors:
         wl = wl.scaled(n_tensors=args.tensors)
     if args.scale:
-        wl = wl.scaled(scale=args.scale)
+        wl = wl.scaled(scale=args.scale, group=8 if args.scale == "nm" else wl.group)
     if args.bits:
         wl = wl.scaled(bits=(args.bits,))
     return wl
@@ -136,7 +144,7 @@ def run_workload(name: str, args, events: HipEvents | None):
     wl = apply_overrides(wl, args)
     dev = "cuda:0"
     dt = cf.CF_F32 if wl.dtype == "f32" else cf.CF_BF16
-    scale = {"group": cf.CF_SCALE_GROUP, "rank1": cf.CF_SCALE_RANK1}.get(wl.scale, cf.CF_SCALE_CHANNEL)
+    scale = {"group": cf.CF_SCALE_GROUP, "rank1": cf.CF_SCALE_RANK1, "nm": cf.CF_SPARSE_NM}.get(wl.scale, cf.CF_SCALE_CHANNEL)
     descs = [cf.desc(wl.n_tokens, wl.n_channels, dt, wl.bits_of(t), scale, wl.group) for t in range(wl.n_tensors)]
     opts = cf.options(ef=args.ef, flags=args.flags, tile_rows=args.tile_rows, encode_rows=args.encode_rows)
 
@@ -238,9 +246,9 @@ def kernel_algorithmic_bytes(nm: str, wl, ef: int) -> float:
         if nm == "k_colreduce":
             per = 2 * sx + (4 if ef else 0)
         elif nm == "k_encode":          # reads x, recon (+err); writes codes, err, recon
-            per = 3 * sx + 4 + bits / 8.0 + (4 if ef else 0) + scale_b
+            per = 3 * sx + 4 + code_bytes_per_element(wl, bits) + (4 if ef else 0) + scale_b
         elif nm == "k_decode":
-            per = 2 * sx + bits / 8.0 + scale_b
+            per = 2 * sx + code_bytes_per_element(wl, bits) + scale_b
         else:                            # a kernel that does the whole step
             per = bytes_per_element(wl, bits, ef)
         total += n * per
@@ -258,7 +266,7 @@ def cpu_baseline(wl, ef: int, budget_s: float = 15.0):
     small = wl.scaled(n_tensors=min(wl.n_tensors, 3))
     stream = ActivationStream(small, device="cpu")
     cfgs = [oracle.Config(wl.n_tokens, wl.n_channels, dtype=oracle.F32 if wl.dtype == "f32" else oracle.BF16,
-                          bits=wl.bits_of(t), scale={"group": oracle.SCALE_GROUP, "rank1": oracle.SCALE_RANK1}.get(wl.scale, oracle.SCALE_CHANNEL),
+                          bits=wl.bits_of(t), scale={"group": oracle.SCALE_GROUP, "rank1": oracle.SCALE_RANK1, "nm": oracle.SPARSE_NM}.get(wl.scale, oracle.SCALE_CHANNEL),
                           group=wl.group, ef=ef) for t in range(small.n_tensors)]
     state = [oracle.warmup(cfgs[t], as_numpy(stream.current[t])) for t in range(small.n_tensors)]
     done, spent, nbytes = 0, 0.0, 0.0

@@ -31,7 +31,12 @@
  *              (8/bits)*k ... (8/bits)*k + 8/bits - 1, channel (8/bits)*k + m in
  *              bits [bits*m, bits*m + bits)  (least significant first)
  *   scales   : fp32 [C] (CF_SCALE_CHANNEL), fp32 [N, C/group] (CF_SCALE_GROUP),
- *              fp32 v[C] followed by u[N] (CF_SCALE_RANK1)
+ *              fp32 v[C] followed by u[N] (CF_SCALE_RANK1); none (CF_SPARSE_NM: the
+ *              entry is ignored and may be null)
+ *   codes with CF_SPARSE_NM: [N, C/8] mask bytes (bit m of byte k = channel 8k+m
+ *              kept), then, from the next multiple of 16 bytes on (the bytes in
+ *              between are never written), the kept values in
+ *              `dtype`, token-major, `bits` per block of 8 channels in channel order
  * x must not alias recon or err; codes and scales must alias nothing.
  *
  * Codes.  1-bit: bit = 1 for z < 0.  2-bit: bit1 = sign, bit0 = magnitude
@@ -76,8 +81,15 @@ typedef enum { CF_F32 = 0, CF_BF16 = 1 } cf_dtype;
  * RANK1: the paper's u v^T (App. D "Quantization"), s_ij = u_i * v_j with v_j as
  * for CHANNEL and u_i = rowmean_i|z| / mean|z| (0 when z is all zero); 1-/2-bit
  * only, C <= 131072 (CF_ERR_SHAPE beyond), two-kernel path only (the
- * single-pass flag is ignored for a context that holds such a tensor). */
-typedef enum { CF_SCALE_CHANNEL = 0, CF_SCALE_GROUP = 1, CF_SCALE_RANK1 = 2 } cf_scale_kind;
+ * single-pass flag is ignored for a context that holds such a tensor).
+ *
+ * CF_SPARSE_NM is not a scale but the other compressor of the paper's kernel set
+ * (Sec. 3.4, N:M block sparsifier): of every `group` = 8 consecutive channels of a
+ * token the `bits` = N in {1, 2, 4} of largest magnitude are kept and travel in
+ * `dtype` (bf16 values rounded to nearest even), the rest are dropped into the
+ * error.  Magnitudes are ordered by the bit pattern of |z| (NaN above infinity),
+ * equal ones by channel, lowest first.  No scales, no reduction over tokens. */
+typedef enum { CF_SCALE_CHANNEL = 0, CF_SCALE_GROUP = 1, CF_SCALE_RANK1 = 2, CF_SPARSE_NM = 3 } cf_scale_kind;
 
 /* How the error buffer enters (a2) and is updated (a7).
  *   CF_EF_RECON   z = x_t - recon_{t-1}; e_t = z - D.  The residual against the
@@ -96,9 +108,9 @@ typedef struct {
     int64_t n_tokens;   /* N >= 1 */
     int64_t n_channels; /* C >= 8, multiple of 8 (and of group for CF_SCALE_GROUP) */
     int32_t dtype;      /* cf_dtype of x and recon */
-    int32_t bits;       /* 1, 2 or 4 */
+    int32_t bits;       /* 1, 2 or 4 (CF_SPARSE_NM: values kept per block) */
     int32_t scale;      /* cf_scale_kind; supported pairs: (1|2|4, CHANNEL), (4, GROUP), (1|2, RANK1) */
-    int32_t group;      /* 128 when scale == CF_SCALE_GROUP, ignored otherwise */
+    int32_t group;      /* 128 when scale == CF_SCALE_GROUP, 8 when CF_SPARSE_NM, ignored otherwise */
 } cf_tensor_desc;
 
 typedef struct {

@@ -62,6 +62,10 @@ cf_status check_desc(const cf_tensor_desc &d)
         if (d.group != 128 || d.n_channels % 128 != 0) return CF_ERR_SHAPE;
         return CF_OK;
     }
+    if (d.scale == CF_SPARSE_NM) {      // bits = N values kept of every group = M channels
+        if (d.group != 8) return CF_ERR_UNSUPPORTED;
+        return CF_OK;                   // bits in {1, 2, 4} was checked above
+    }
     if (d.scale == CF_SCALE_RANK1) {
         if (d.bits == 4) return CF_ERR_UNSUPPORTED;                  // the paper's u v^T goes with its 1-/2-bit code books
         if (d.n_channels > (int64_t)kMaxRank1Colblocks * kTileChannels) return CF_ERR_SHAPE;
@@ -254,17 +258,17 @@ struct cf_ctx {
         return r;
     }
 
-    bool range_has_group_scale(int32_t first, int32_t count) const
+    bool range_has_group_scale(int32_t first, int32_t count) const   // anything the single-pass kernel leaves to k_encode
     {
         for (int32_t t = first; t < first + count; ++t)
-            if (descs[t].scale == CF_SCALE_GROUP) return true;
+            if (descs[t].scale != CF_SCALE_CHANNEL) return true;
         return false;
     }
 
     bool range_has_channel(int32_t first, int32_t count) const      // anything that needs the reduction kernels
     {
         for (int32_t t = first; t < first + count; ++t)
-            if (descs[t].scale != CF_SCALE_GROUP) return true;
+            if (descs[t].scale == CF_SCALE_CHANNEL || descs[t].scale == CF_SCALE_RANK1) return true;
         return false;
     }
 
@@ -298,6 +302,20 @@ cf_status check_ptrs(const void *const *arr, int32_t count)
     if (!arr) return CF_ERR_INVALID_ARG;
     for (int32_t k = 0; k < count; ++k)
         if (!arr[k] || !aligned16(arr[k])) return CF_ERR_INVALID_ARG;
+    return CF_OK;
+}
+
+// Scale buffers: the N:M sparsifier has none, its entries are ignored and may be null.
+cf_status check_scale_ptrs(const cf_ctx *ctx, int32_t first, int32_t count, const void *const *arr)
+{
+    if (!arr) return CF_ERR_INVALID_ARG;
+    for (int32_t k = 0; k < count; ++k) {
+        if (ctx->descs[first + k].scale == CF_SPARSE_NM) {
+            if (arr[k] && !aligned16(arr[k])) return CF_ERR_INVALID_ARG;
+        } else if (!arr[k] || !aligned16(arr[k])) {
+            return CF_ERR_INVALID_ARG;
+        }
+    }
     return CF_OK;
 }
 
@@ -375,11 +393,12 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
     if ((st = check_ptrs(recon, count)) != CF_OK) return st;
     if ((st = check_ptrs(err, count)) != CF_OK) return st;
     if ((st = check_ptrs(codes, count)) != CF_OK) return st;
-    if ((st = check_ptrs(reinterpret_cast<const void *const *>(scales), count)) != CF_OK) return st;
+    if ((st = check_scale_ptrs(ctx, first, count, reinterpret_cast<const void *const *>(scales))) != CF_OK) return st;
     for (int32_t k = 0; k < count; ++k) {
         const void *px = x[k], *pr = recon[k], *pe = err[k], *pc = codes[k], *ps = scales[k];
         if (px == pr || px == pe || pr == pe) return CF_ERR_INVALID_ARG;
-        if (pc == px || pc == pr || pc == pe || ps == px || ps == pr || ps == pe || ps == pc) return CF_ERR_INVALID_ARG;
+        if (pc == px || pc == pr || pc == pe) return CF_ERR_INVALID_ARG;
+        if (ps && (ps == px || ps == pr || ps == pe || ps == pc)) return CF_ERR_INVALID_ARG;
     }
     if ((st = check_warm(ctx, first, count)) != CF_OK) return st;
 
@@ -446,9 +465,14 @@ cf_status cf_sizes(const cf_tensor_desc *desc, const cf_options *opts, size_t *c
     if (st != CF_OK) return st;
     if ((st = check_desc(*desc)) != CF_OK) return st;
     const size_t n = (size_t)desc->n_tokens, c = (size_t)desc->n_channels;
-    if (codes_bytes) *codes_bytes = n * (c * (size_t)desc->bits / 8);
-    if (scales_bytes)
-        *scales_bytes = sizeof(float) * (desc->scale == CF_SCALE_GROUP ? n * (c / 128) : desc->scale == CF_SCALE_RANK1 ? c + n : c);
+    if (desc->scale == CF_SPARSE_NM) {      // one mask byte per block of 8, then (16-byte aligned) bits values per block
+        if (codes_bytes) *codes_bytes = (n * (c / 8) + 15) / 16 * 16 + n * (c / 8) * (size_t)desc->bits * dtype_size(desc->dtype);
+        if (scales_bytes) *scales_bytes = 0;
+    } else {
+        if (codes_bytes) *codes_bytes = n * (c * (size_t)desc->bits / 8);
+        if (scales_bytes)
+            *scales_bytes = sizeof(float) * (desc->scale == CF_SCALE_GROUP ? n * (c / 128) : desc->scale == CF_SCALE_RANK1 ? c + n : c);
+    }
     if (recon_bytes) *recon_bytes = n * c * dtype_size(desc->dtype);
     if (err_bytes) *err_bytes = n * c * dtype_size(o.err_dtype);
     return CF_OK;
@@ -613,10 +637,12 @@ cf_status cf_decompress(cf_ctx *ctx, int32_t first, int32_t count, const void *c
     if (st != CF_OK) return st;
     if (count == 0) return CF_OK;
     if ((st = check_ptrs(codes, count)) != CF_OK) return st;
-    if ((st = check_ptrs(scales, count)) != CF_OK) return st;
+    if ((st = check_scale_ptrs(ctx, first, count, scales)) != CF_OK) return st;
     if ((st = check_ptrs(recon, count)) != CF_OK) return st;
-    for (int32_t k = 0; k < count; ++k)
-        if (codes[k] == scales[k] || codes[k] == recon[k] || scales[k] == recon[k]) return CF_ERR_INVALID_ARG;
+    for (int32_t k = 0; k < count; ++k) {
+        if (codes[k] == recon[k]) return CF_ERR_INVALID_ARG;
+        if (scales[k] && (codes[k] == scales[k] || scales[k] == recon[k])) return CF_ERR_INVALID_ARG;
+    }
     if ((st = check_warm(ctx, first, count)) != CF_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     ProfileScope prof(ctx);

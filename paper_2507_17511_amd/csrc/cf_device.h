@@ -14,7 +14,7 @@ namespace cf {
 namespace dev {
 
 constexpr int F32 = 0, BF16 = 1;
-constexpr int SCALE_CHANNEL = 0, SCALE_GROUP = 1, SCALE_RANK1 = 2;
+constexpr int SCALE_CHANNEL = 0, SCALE_GROUP = 1, SCALE_RANK1 = 2, SPARSE_NM = 3;
 constexpr int EF_RECON = 0, EF_LITERAL = 1, EF_OFF = 2, EF_NAIVE = 3;
 
 #define CF_GLOBAL __attribute__((address_space(1)))
@@ -252,6 +252,121 @@ __device__ __forceinline__ F8 load_scales8(const float *scales, int64_t first)
     Raw8<F32> r;
     r.load(scales, first);
     return r.widen();
+}
+
+// ---------------------------------------------------------------- N:M block sparsifier, M = 8
+
+// Sec. 3.4 names an N:M block sparsifier; here a block is the 8 channels of one lane.  Returns
+// the mask of the KEEP elements of largest magnitude (bit k = channel k).  Magnitudes are ordered
+// by the bit pattern of |z|, equal ones by channel: element k is kept iff fewer than KEEP elements
+// come before it.  28 comparisons, no cross-lane traffic.
+template <int KEEP> __device__ __forceinline__ uint32_t nm_select8(const F8 &z)
+{
+    uint32_t key[8];
+    int before[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        key[k] = __float_as_uint(z.v[k]) & 0x7fffffffu;
+        before[k] = 0;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int k = j + 1; k < 8; ++k) {
+            const bool j_first = key[j] >= key[k];      // j < k: a tie goes to j
+            before[k] += j_first ? 1 : 0;
+            before[j] += j_first ? 0 : 1;
+        }
+    uint32_t mask = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) mask |= (before[k] < KEEP ? 1u : 0u) << k;
+    return mask;
+}
+
+// The kept values in channel order as they travel (bf16: rounded to nearest even, 16-bit patterns;
+// fp32: the bits of z), and D: the travelled value where kept, +0 elsewhere.
+template <int DT, int KEEP> __device__ __forceinline__ void nm_values8(const F8 &z, uint32_t mask, uint32_t (&vals)[KEEP], F8 &d)
+{
+#pragma unroll
+    for (int r = 0; r < KEEP; ++r) vals[r] = 0u;
+    int r = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const bool kept = (mask >> k) & 1u;
+        const uint32_t raw = (DT == BF16) ? bf16_rne(z.v[k]) : __float_as_uint(z.v[k]);
+        const float back = (DT == BF16) ? __uint_as_float(raw << 16) : z.v[k];
+        d.v[k] = kept ? back : 0.0f;
+#pragma unroll
+        for (int q = 0; q < KEEP; ++q) vals[q] = (kept && r == q) ? raw : vals[q];
+        r += kept ? 1 : 0;
+    }
+}
+
+// Receiver side: D from the mask and the travelled values.  Mask bits beyond the KEEP-th are ignored.
+template <int DT, int KEEP> __device__ __forceinline__ void nm_scatter8(uint32_t mask, const uint32_t (&vals)[KEEP], F8 &d)
+{
+    int r = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const bool set = ((mask >> k) & 1u) && r < KEEP;
+        uint32_t raw = 0u;
+#pragma unroll
+        for (int q = 0; q < KEEP; ++q) raw = (r == q) ? vals[q] : raw;
+        const float v = (DT == BF16) ? __uint_as_float(raw << 16) : __uint_as_float(raw);
+        d.v[k] = set ? v : 0.0f;
+        r += set ? 1 : 0;
+    }
+}
+
+// A lane's KEEP values are KEEP * (2 | 4) contiguous bytes at `mine`: 2 bytes are paired with the
+// neighbour lane's into one dword (see store_codes_ptr), the rest are dword vectors.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+template <int DT, int KEEP> __device__ __forceinline__ void nm_store_values(uint8_t *mine, int chunk, const uint32_t (&vals)[KEEP], bool wide)
+{
+    if (DT == BF16) {
+        if (KEEP == 1) store_codes_ptr<2>(mine, chunk, vals[0], wide);
+        else if (KEEP == 2) *gmut<uint32_t>(mine) = vals[0] | (vals[1] << 16);
+        else {
+            u32x2 w;
+            w.x = vals[0] | (vals[1] << 16);
+            w.y = vals[2] | (vals[3] << 16);
+            *gmut<u32x2>(mine) = w;
+        }
+    } else {
+        if (KEEP == 1) *gmut<uint32_t>(mine) = vals[0];
+        else if (KEEP == 2) {
+            u32x2 w;
+            w.x = vals[0]; w.y = vals[1];
+            *gmut<u32x2>(mine) = w;
+        } else {
+            u32x4 w;
+            w.x = vals[0]; w.y = vals[1]; w.z = vals[2]; w.w = vals[3];
+            *gmut<u32x4>(mine) = w;
+        }
+    }
+}
+
+template <int DT, int KEEP> __device__ __forceinline__ void nm_load_values(const uint8_t *mine, uint32_t (&vals)[KEEP])
+{
+    if (DT == BF16) {
+        if (KEEP == 1) vals[0] = *gconst<uint16_t>(mine);
+        else if (KEEP == 2) {
+            const uint32_t w = *gconst<uint32_t>(mine);
+            vals[0] = w & 0xffffu; vals[1] = w >> 16;
+        } else {
+            const u32x2 w = *gconst<u32x2>(mine);
+            vals[0] = w.x & 0xffffu; vals[1] = w.x >> 16; vals[2] = w.y & 0xffffu; vals[3] = w.y >> 16;
+        }
+    } else {
+        if (KEEP == 1) vals[0] = *gconst<uint32_t>(mine);
+        else if (KEEP == 2) {
+            const u32x2 w = *gconst<u32x2>(mine);
+            vals[0] = w.x; vals[1] = w.y;
+        } else {
+            const u32x4 w = *gconst<u32x4>(mine);
+            vals[0] = w.x; vals[1] = w.y; vals[2] = w.z; vals[3] = w.w;
+        }
+    }
 }
 
 // Max over the 16 lanes of a DPP row (16 lanes x 8 channels = one group of 128).

@@ -191,7 +191,7 @@ __global__ __launch_bounds__(kTileThreads) void k_colreduce(BatchView v, LaunchR
 {
     TileCtx c = locate_tile<false>(v, r);
     const TensorDev &d = c.d;
-    if (d.scale == SCALE_GROUP) return;
+    if (d.scale == SCALE_GROUP || d.scale == SPARSE_NM) return;      // row-local: nothing to reduce
     if (is_bf16<DTS>(d)) {
         if (d.scale == SCALE_RANK1) colreduce_tile<BF16, EF, ET, false, true>(c, v.workspace);
         else if (d.bits == 4) colreduce_tile<BF16, EF, ET, true, false>(c, v.workspace);
@@ -212,7 +212,7 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_finalize(BatchView v, Laun
     uint32_t blk = r.fin_lo + blockIdx.x;
     int t = find_slot(v.fin_prefix, r.first, r.first + r.count, blk);
     const TensorDev d = v.descs[t];
-    if (d.scale == SCALE_GROUP) return;
+    if (d.scale == SCALE_GROUP || d.scale == SPARSE_NM) return;
     int col = (int)(blk - d.fin_begin) * kFinalizeThreads + (int)threadIdx.x;
     if (col >= d.n_channels) return;
     const CF_GLOBAL float *partial = gconst<float>(v.workspace + d.partial_off) + col;
@@ -356,10 +356,85 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
     }
 }
 
+// N:M block sparsifier (Sec. 3.4), blocks of 8 channels: one lane selects, packs and decodes its own
+// block; the row's mask bytes go where 1-bit codes would, the kept values behind all masks.
+template <int DT, int KEEP, int EF, int ET, bool FUSED>
+__device__ __forceinline__ void nm_encode_tile(const TileCtx &c)
+{
+    const TensorDev &d = c.d;
+    const TensorPtrs &p = c.p;
+    const int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
+    if (chunk >= d.n_chunks) return;
+    const int64_t row0 = (int64_t)c.rowblock * c.rows;
+    const int64_t row1 = row0 + c.rows < d.n_tokens ? row0 + c.rows : d.n_tokens;
+    const int64_t C = d.n_channels;
+    const bool wide = (d.n_channels & 31) == 0;
+    constexpr int kValueBytes = KEEP * (DT == BF16 ? 2 : 4);
+    uint8_t *values = p.codes + ((d.n_tokens * d.n_chunks + 15) / 16) * 16;
+    constexpr int U = 4;
+    for (int64_t i0 = row0; i0 < row1; i0 += U) {
+        Raw8<DT> xr[U], br[U];
+        Raw8<ET> er[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = i0 + u;
+            if (i < row1) {
+                const int64_t e = i * C + (int64_t)chunk * kChunk;
+                xr[u].load(p.x, e);
+                if (EF != EF_NAIVE) br[u].load(p.recon, e); else br[u].zero();
+                if (EF == EF_LITERAL || EF == EF_OFF) er[u].load(p.err, e); else er[u].zero();
+            } else {
+                xr[u].zero();
+                br[u].zero();
+                er[u].zero();
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = i0 + u;
+            if (i >= row1) break;               // uniform over the workgroup
+            const F8 b = br[u].widen();
+            const F8 eold = er[u].widen();
+            const F8 z = residual8<EF>(xr[u].widen(), b, eold);
+            const uint32_t mask = nm_select8<KEEP>(z);
+            uint32_t vals[KEEP];
+            F8 dq;
+            nm_values8<DT, KEEP>(z, mask, vals, dq);
+            store_codes_wide<1>(p.codes + i * d.n_chunks, chunk, mask, wide);
+            nm_store_values<DT, KEEP>(values + (i * d.n_chunks + chunk) * kValueBytes, chunk, vals, wide);
+            const int64_t e = i * C + (int64_t)chunk * kChunk;
+            F8 enew;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                float lost = z.v[k] - dq.v[k];
+                if (EF == EF_OFF) lost = eold.v[k] + lost;
+                enew.v[k] = lost;
+            }
+            Raw8<ET> eo;
+            eo.narrow(enew);
+            eo.store(p.err, e);
+            if (FUSED) {
+                F8 nb;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) nb.v[k] = (EF == EF_NAIVE) ? dq.v[k] : b.v[k] + dq.v[k];
+                Raw8<DT> out;
+                out.narrow(nb);
+                out.store(p.recon, e);
+            }
+        }
+    }
+}
+
 template <int DT, int EF, int ET, bool FUSED>
 __device__ __forceinline__ void encode_dispatch(const TileCtx &c)
 {
     const TensorDev &d = c.d;
+    if (d.scale == SPARSE_NM) {
+        if (d.bits == 1) nm_encode_tile<DT, 1, EF, ET, FUSED>(c);
+        else if (d.bits == 2) nm_encode_tile<DT, 2, EF, ET, FUSED>(c);
+        else nm_encode_tile<DT, 4, EF, ET, FUSED>(c);
+        return;
+    }
     if (d.scale == SCALE_GROUP) { encode_tile<DT, 4, 1, EF, ET, FUSED>(c); return; }
     if (d.scale == SCALE_RANK1) {
         if (d.bits == 1) encode_tile<DT, 1, 2, EF, ET, FUSED>(c);
@@ -375,7 +450,7 @@ template <int EF, int ET, bool FUSED, int DTS>
 __global__ __launch_bounds__(kTileThreads) void k_encode(BatchView v, LaunchRange r)
 {
     TileCtx c = locate_tile<true>(v, r);
-    if (r.only_group_scale && c.d.scale != SCALE_GROUP) return;     // covered by the single-pass kernel
+    if (r.only_group_scale && c.d.scale == SCALE_CHANNEL) return;   // covered by the single-pass kernel
     if (is_bf16<DTS>(c.d)) encode_dispatch<BF16, EF, ET, FUSED>(c);
     else encode_dispatch<F32, EF, ET, FUSED>(c);
 }
@@ -440,9 +515,44 @@ __device__ __forceinline__ void decode_tile(const TileCtx &c, bool replace)
     }
 }
 
+template <int DT, int KEEP>
+__device__ __forceinline__ void nm_decode_tile(const TileCtx &c, bool replace)
+{
+    const TensorDev &d = c.d;
+    const TensorPtrs &p = c.p;
+    const int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
+    if (chunk >= d.n_chunks) return;
+    const int64_t row0 = (int64_t)c.rowblock * c.rows;
+    const int64_t row1 = row0 + c.rows < d.n_tokens ? row0 + c.rows : d.n_tokens;
+    const int64_t C = d.n_channels;
+    constexpr int kValueBytes = KEEP * (DT == BF16 ? 2 : 4);
+    const uint8_t *values = p.codes + ((d.n_tokens * d.n_chunks + 15) / 16) * 16;
+    for (int64_t i = row0; i < row1; ++i) {
+        Raw8<DT> br;
+        if (!replace) br.load(p.recon, i * C + (int64_t)chunk * kChunk); else br.zero();
+        const uint32_t mask = load_codes<1>(p.codes + i * d.n_chunks, chunk);
+        uint32_t vals[KEEP];
+        nm_load_values<DT, KEEP>(values + (i * d.n_chunks + chunk) * kValueBytes, vals);
+        F8 dq, nb;
+        nm_scatter8<DT, KEEP>(mask, vals, dq);
+        const F8 b = br.widen();
+#pragma unroll
+        for (int k = 0; k < 8; ++k) nb.v[k] = replace ? dq.v[k] : b.v[k] + dq.v[k];
+        Raw8<DT> out;
+        out.narrow(nb);
+        out.store(p.recon, i * C + (int64_t)chunk * kChunk);
+    }
+}
+
 template <int DT> __device__ __forceinline__ void decode_dispatch(const TileCtx &c, bool replace)
 {
     const TensorDev &d = c.d;
+    if (d.scale == SPARSE_NM) {
+        if (d.bits == 1) nm_decode_tile<DT, 1>(c, replace);
+        else if (d.bits == 2) nm_decode_tile<DT, 2>(c, replace);
+        else nm_decode_tile<DT, 4>(c, replace);
+        return;
+    }
     if (d.scale == SCALE_GROUP) { decode_tile<DT, 4, 1>(c, replace); return; }
     if (d.scale == SCALE_RANK1) {
         if (d.bits == 1) decode_tile<DT, 1, 2>(c, replace); else decode_tile<DT, 2, 2>(c, replace);

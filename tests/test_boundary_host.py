@@ -119,3 +119,13 @@ def test_calls_on_null_context_fail_cleanly():
         assert ei.value.status == cf.CF_ERR_INVALID_ARG
     cf.cf_destroy(None)
     assert cf.cf_last_hip_error(None) == 0
+
+
+def test_nm_sizes_and_block_lengths():
+    for group in (4, 16, 32):
+        with pytest.raises(cf.CFError) as ei:
+            cf.cf_sizes(cf.desc(16, 64, cf.CF_BF16, 2, cf.CF_SPARSE_NM, group))
+        assert ei.value.status == cf.CF_ERR_UNSUPPORTED
+    codes, scales, recon, err = cf.cf_sizes(cf.desc(4096, 3072, cf.CF_BF16, 2, cf.CF_SPARSE_NM, 8))
+    assert scales == 0 and codes == 4096 * 384 * (1 + 4)           # 16-byte blocks travel as 5 bytes
+    assert cf.cf_sizes(cf.desc(3, 8, cf.CF_F32, 1, cf.CF_SPARSE_NM, 8))[0] == 16 + 3 * 4

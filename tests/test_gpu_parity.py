@@ -447,3 +447,62 @@ def test_error_study_orders_the_strategies_as_the_paper_does(bits):
     # 1-bit on a Gaussian signal loses 1 - 2/pi of the energy: the delta of the paper's compressor model
     if bits == 1:
         assert abs(res["naive"]["compression"][-1] - (1 - 2 / np.pi)) < 0.02
+
+
+# ---------------------------------------------------------------- N:M block sparsifier (Sec. 3.4)
+
+NMK = cf.CF_SPARSE_NM
+
+
+def tie_stream(shape, dtype, steps, seed):
+    """Small integers times 1/4: most magnitudes inside a block of 8 tie, many residuals are exactly zero."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    x = torch.randint(-8, 9, shape, generator=g, device=DEV).float()
+    out = []
+    for _ in range(steps):
+        out.append(x.to(torch.bfloat16).contiguous() if dtype == cf.CF_BF16 else x.clone())
+        x = x + 0.25 * torch.randint(-2, 3, shape, generator=g, device=DEV).float()
+    return out
+
+
+@pytest.mark.parametrize("keep", [1, 2, 4])
+@pytest.mark.parametrize("dtype", [cf.CF_BF16, cf.CF_F32])
+@pytest.mark.parametrize("mode", ["fused", "split"])
+def test_parity_nm_shapes(keep, dtype, mode):
+    """Masks, kept values, error and reconstruction, on continuous drifts and on drifts full of ties;
+    channel counts with (1152, 3072) and without (1096, 8) whole quads of lanes."""
+    for k, (n, c) in enumerate(SHAPES + [(33, 1152)]):
+        for maker in (drift_stream_local, tie_stream):
+            say(f"nm keep={keep} dtype={dtype} mode={mode} N={n} C={c} {maker.__name__}")
+            d = cf.desc(n, c, dtype, keep, NMK, 8)
+            xs = maker((n, c), dtype, 4, 700 + k)
+            run_parity([d], cf.options(), [[x] for x in xs], mode=mode, tag=f"nm N{n}C{c}")
+
+
+def drift_stream_local(shape, dtype, steps, seed):
+    return drift_stream(shape, dtype, steps=steps, seed=seed, device=DEV)
+
+
+@pytest.mark.parametrize("ef", [cf.CF_EF_RECON, cf.CF_EF_LITERAL, cf.CF_EF_OFF, cf.CF_EF_NAIVE])
+def test_parity_nm_ef_modes_err_dtypes_heights(ef):
+    n, c = 203, 1096
+    for err_dtype in (cf.CF_F32, cf.CF_BF16):
+        for encode_rows in (0, 3, 64):
+            for keep, dtype in ((1, cf.CF_BF16), (2, cf.CF_BF16), (4, cf.CF_F32)):
+                say(f"nm ef={ef} err_dtype={err_dtype} encode_rows={encode_rows} keep={keep} dtype={dtype}")
+                d = cf.desc(n, c, dtype, keep, NMK, 8)
+                xs = drift_stream((n, c), dtype, steps=4, seed=31 + ef, device=DEV)
+                run_parity([d], cf.options(ef=ef, err_dtype=err_dtype, encode_rows=encode_rows), [[x] for x in xs])
+
+
+def test_parity_nm_in_a_mixed_batch():
+    """Sparsified tensors share a batch with quantised ones, with and without the single-pass kernel
+    taking the channel-scaled tensors."""
+    descs = [cf.desc(203, 1096, cf.CF_BF16, 2, NMK, 8), cf.desc(64, 256, cf.CF_F32, 4, GR), cf.desc(300, 1024, cf.CF_BF16, 1, CH),
+             cf.desc(67, 3072, cf.CF_F32, 1, NMK, 8), cf.desc(9, 8, cf.CF_BF16, 4, NMK, 8), cf.desc(130, 264, cf.CF_BF16, 2, CH)]
+    streams = [drift_stream((int(d.n_tokens), int(d.n_channels)), int(d.dtype), 4, 60 + t, device=DEV) for t, d in enumerate(descs)]
+    for flags in (0, cf.CF_FLAG_SINGLE_PASS):
+        for mode in ("fused", "split"):
+            say(f"nm mixed batch flags={flags} mode={mode}")
+            run_parity(descs, cf.options(flags=flags), [[s[k] for s in streams] for k in range(4)], mode=mode, tag="nm mixed")
