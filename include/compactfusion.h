@@ -33,6 +33,7 @@
  *   scales   : fp32 [C] (CF_SCALE_CHANNEL), fp32 [N, C/group] (CF_SCALE_GROUP),
  *              fp32 v[C] followed by u[N] (CF_SCALE_RANK1); none (CF_SPARSE_NM: the
  *              entry is ignored and may be null)
+ *   codes with CF_LOWRANK: U [N, 32] then V [C, 32], both in `dtype`
  *   codes with CF_SPARSE_NM: [N, C/8] mask bytes (bit m of byte k = channel 8k+m
  *              kept), then, from the next multiple of 16 bytes on (the bytes in
  *              between are never written), the kept values in
@@ -88,8 +89,21 @@ typedef enum { CF_F32 = 0, CF_BF16 = 1 } cf_dtype;
  * token the `bits` = N in {1, 2, 4} of largest magnitude are kept and travel in
  * `dtype` (bf16 values rounded to nearest even), the rest are dropped into the
  * error.  Magnitudes are ordered by the bit pattern of |z| (NaN above infinity),
- * equal ones by channel, lowest first.  No scales, no reduction over tokens. */
-typedef enum { CF_SCALE_CHANNEL = 0, CF_SCALE_GROUP = 1, CF_SCALE_RANK1 = 2, CF_SPARSE_NM = 3 } cf_scale_kind;
+ * equal ones by channel, lowest first.  No scales, no reduction over tokens.
+ *
+ * CF_LOWRANK is the low-rank compressor (Alg. 3; App. D "Low-Rank Compression"): the
+ * residual A [N, C] travels as rank-32 factors U = A Q [N, 32] and V = Q [C, 32] in
+ * `dtype`, found by `bits` = T in {1, 2, 4} steps of subspace iteration
+ *   Q <- orth(Q0);  T x { Z <- A^T (A Q); Q <- orth(Z) };  U <- A Q
+ * (orth = Gram-Schmidt over the columns; a column left with less than 1e-4 of its
+ * length is dropped to zero; U is not normalised, so U V^T is the projection of A
+ * onto span(Q)).  D = U V^T is formed from the travelled (rounded) factors in fp32
+ * on the matrix cores.  `group` = 32 (the rank); C a multiple of 32, at most 3072;
+ * CF_EF_RECON only.  The `scales` entry of such a tensor is an INPUT of the sender:
+ * the start matrix Q0 [C, 32] fp32 that the caller draws; the receiver ignores it
+ * (it must still be a valid pointer).  Results agree with an fp64 evaluation to
+ * fp32 rounding, not bit for bit. */
+typedef enum { CF_SCALE_CHANNEL = 0, CF_SCALE_GROUP = 1, CF_SCALE_RANK1 = 2, CF_SPARSE_NM = 3, CF_LOWRANK = 4 } cf_scale_kind;
 
 /* How the error buffer enters (a2) and is updated (a7).
  *   CF_EF_RECON   z = x_t - recon_{t-1}; e_t = z - D.  The residual against the
@@ -108,9 +122,9 @@ typedef struct {
     int64_t n_tokens;   /* N >= 1 */
     int64_t n_channels; /* C >= 8, multiple of 8 (and of group for CF_SCALE_GROUP) */
     int32_t dtype;      /* cf_dtype of x and recon */
-    int32_t bits;       /* 1, 2 or 4 (CF_SPARSE_NM: values kept per block) */
+    int32_t bits;       /* 1, 2 or 4 (CF_SPARSE_NM: values kept per block; CF_LOWRANK: subspace iterations) */
     int32_t scale;      /* cf_scale_kind; supported pairs: (1|2|4, CHANNEL), (4, GROUP), (1|2, RANK1) */
-    int32_t group;      /* 128 when scale == CF_SCALE_GROUP, 8 when CF_SPARSE_NM, ignored otherwise */
+    int32_t group;      /* 128 when scale == CF_SCALE_GROUP, 8 when CF_SPARSE_NM, 32 when CF_LOWRANK, ignored otherwise */
 } cf_tensor_desc;
 
 typedef struct {

@@ -22,7 +22,7 @@ CF_OK, CF_ERR_INVALID_ARG, CF_ERR_SHAPE, CF_ERR_UNSUPPORTED, CF_ERR_STATE, CF_ER
 # cf_dtype
 CF_F32, CF_BF16 = 0, 1
 # cf_scale_kind
-CF_SCALE_CHANNEL, CF_SCALE_GROUP, CF_SCALE_RANK1, CF_SPARSE_NM = 0, 1, 2, 3
+CF_SCALE_CHANNEL, CF_SCALE_GROUP, CF_SCALE_RANK1, CF_SPARSE_NM, CF_LOWRANK = 0, 1, 2, 3, 4
 # cf_ef_mode
 CF_EF_RECON, CF_EF_LITERAL, CF_EF_OFF, CF_EF_NAIVE = 0, 1, 2, 3
 CF_FLAG_SINGLE_PASS = 0x1

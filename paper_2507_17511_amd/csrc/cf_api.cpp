@@ -28,7 +28,7 @@ struct Layout {
     std::vector<TensorDev> dev;
     std::vector<uint32_t> tile_prefix, fin_prefix, ew_prefix;
     size_t off_ew_prefix = 0;
-    bool any_channel = false, any_rank1 = false;
+    bool any_channel = false, any_rank1 = false, any_lowrank = false;
 };
 
 cf_status check_opts(const cf_options *o, cf_options &out)
@@ -60,6 +60,11 @@ cf_status check_desc(const cf_tensor_desc &d)
     if (d.scale == CF_SCALE_GROUP) {
         if (d.bits != 4) return CF_ERR_UNSUPPORTED;
         if (d.group != 128 || d.n_channels % 128 != 0) return CF_ERR_SHAPE;
+        return CF_OK;
+    }
+    if (d.scale == CF_LOWRANK) {        // bits = subspace iterations T, group = rank
+        if (d.group != kLowRankRank) return CF_ERR_UNSUPPORTED;
+        if (d.n_channels % 32 != 0 || d.n_channels > kLowRankMaxChannels) return CF_ERR_SHAPE;
         return CF_OK;
     }
     if (d.scale == CF_SPARSE_NM) {      // bits = N values kept of every group = M channels
@@ -147,6 +152,16 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
             v.partial_off = partial_bytes;   // relative; rebased below
             partial_bytes += align_up((size_t)v.n_rowblocks * (size_t)d.n_channels * sizeof(float));
         }
+        if (d.scale == CF_LOWRANK) {
+            if (o.ef != CF_EF_RECON) return CF_ERR_UNSUPPORTED;
+            L.any_lowrank = true;
+            v.lr_p_off = partial_bytes;
+            partial_bytes += align_up((size_t)d.n_tokens * kLowRankRank * sizeof(float));
+            v.lr_z_off = partial_bytes;
+            partial_bytes += align_up((size_t)d.n_channels * kLowRankRank * sizeof(float));
+            v.lr_q_off = partial_bytes;
+            partial_bytes += align_up((size_t)d.n_channels * kLowRankRank * sizeof(float));
+        }
         if (d.scale == CF_SCALE_RANK1) {
             L.any_rank1 = true;
             v.rowpart_off = partial_bytes;
@@ -193,6 +208,11 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
             L.dev[t].p_partial_off += L.off_p_partials;
         }
         if (descs[t].scale == CF_SCALE_RANK1) L.dev[t].rowpart_off += L.off_partials;
+        if (descs[t].scale == CF_LOWRANK) {
+            L.dev[t].lr_p_off += L.off_partials;
+            L.dev[t].lr_z_off += L.off_partials;
+            L.dev[t].lr_q_off += L.off_partials;
+        }
     }
     return CF_OK;
 }
@@ -253,8 +273,15 @@ struct cf_ctx {
         r.only_group_scale = 0;
         r.naive = opts.ef == CF_EF_NAIVE;
         r.dts = descs[first].dtype;
-        for (int32_t t = first; t < first + count; ++t)
+        r.lr_max_channels = 0;
+        r.lr_max_tokens = 0;
+        for (int32_t t = first; t < first + count; ++t) {
             if (descs[t].dtype != descs[first].dtype) r.dts = 2;
+            if (descs[t].scale == CF_LOWRANK) {
+                if (descs[t].n_channels > r.lr_max_channels) r.lr_max_channels = (int32_t)descs[t].n_channels;
+                if (descs[t].n_tokens > r.lr_max_tokens) r.lr_max_tokens = descs[t].n_tokens;
+            }
+        }
         return r;
     }
 
@@ -270,6 +297,14 @@ struct cf_ctx {
         for (int32_t t = first; t < first + count; ++t)
             if (descs[t].scale == CF_SCALE_CHANNEL || descs[t].scale == CF_SCALE_RANK1) return true;
         return false;
+    }
+
+    int range_lowrank_iters(int32_t first, int32_t count) const       // most subspace iterations any tensor asks for; -1 = no such tensor
+    {
+        int iters = -1;
+        for (int32_t t = first; t < first + count; ++t)
+            if (descs[t].scale == CF_LOWRANK && descs[t].bits > iters) iters = descs[t].bits;
+        return iters;
     }
 
     bool range_has_rank1(int32_t first, int32_t count) const
@@ -383,6 +418,31 @@ cf_status sync_ptrs(cf_ctx *ctx, int32_t first, int32_t count, const void *const
     return CF_OK;
 }
 
+// Alg. 3 on the low-rank tensors of the range: Q <- orth(Q0); T x { P <- A Q; Z <- A^T P; Q <- orth(Z) };
+// U <- A Q; then D = U V^T, error and reconstruction.
+cf_status run_lowrank_sender(cf_ctx *ctx, int32_t first, int32_t count, const BatchView &v, const LaunchRange &r,
+                             bool fused, hipStream_t s)
+{
+    const int iters = ctx->range_lowrank_iters(first, count);
+    if (iters < 0) return CF_OK;
+    if (count > 65535) return CF_ERR_SHAPE;     // the low-rank kernels index the tensors of a call with blockIdx.y
+    hipError_t e = launch(ctx, s, "k_lr_orth", [&] { return launch_lr_orth(v, r, true, 0, s); });
+    if (e != hipSuccess) return device_fail(ctx, e);
+    for (int it = 1; it <= iters; ++it) {       // tensors that asked for fewer iterations sit the later ones out
+        e = launch(ctx, s, "k_lr_project", [&] { return launch_lr_project(v, r, false, it, s); });
+        if (e != hipSuccess) return device_fail(ctx, e);
+        e = launch(ctx, s, "k_lr_backproject", [&] { return launch_lr_backproject(v, r, it, s); });
+        if (e != hipSuccess) return device_fail(ctx, e);
+        e = launch(ctx, s, "k_lr_orth", [&] { return launch_lr_orth(v, r, false, it, s); });
+        if (e != hipSuccess) return device_fail(ctx, e);
+    }
+    e = launch(ctx, s, "k_lr_project", [&] { return launch_lr_project(v, r, true, 0, s); });
+    if (e != hipSuccess) return device_fail(ctx, e);
+    e = launch(ctx, s, "k_lr_apply", [&] { return launch_lr_encode(v, r, ctx->opts.err_dtype, fused, s); });
+    if (e != hipSuccess) return device_fail(ctx, e);
+    return CF_OK;
+}
+
 cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *const *x, void *const *recon,
                      void *const *err, void *const *codes, void *const *scales, void *stream, bool fused)
 {
@@ -421,7 +481,7 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
             e = launch(ctx, s, "k_encode", [&] { return launch_encode(v, r, ef, et, fused, s); });
             if (e != hipSuccess) return device_fail(ctx, e);
         }
-        return CF_OK;
+        return run_lowrank_sender(ctx, first, count, v, r, fused, s);
     }
     if (ctx->range_has_channel(first, count)) {
         e = launch(ctx, s, "k_colreduce", [&] { return launch_colreduce(v, r, ef, et, s); });
@@ -435,7 +495,7 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
     }
     e = launch(ctx, s, "k_encode", [&] { return launch_encode(v, r, ef, et, fused, s); });
     if (e != hipSuccess) return device_fail(ctx, e);
-    return CF_OK;
+    return run_lowrank_sender(ctx, first, count, v, r, fused, s);
 }
 
 }  // namespace
@@ -465,7 +525,10 @@ cf_status cf_sizes(const cf_tensor_desc *desc, const cf_options *opts, size_t *c
     if (st != CF_OK) return st;
     if ((st = check_desc(*desc)) != CF_OK) return st;
     const size_t n = (size_t)desc->n_tokens, c = (size_t)desc->n_channels;
-    if (desc->scale == CF_SPARSE_NM) {      // one mask byte per block of 8, then (16-byte aligned) bits values per block
+    if (desc->scale == CF_LOWRANK) {        // U [N, 32] then V [C, 32] in the storage dtype; the scales entry is the input Q0 [C, 32] fp32
+        if (codes_bytes) *codes_bytes = (n + c) * kLowRankRank * dtype_size(desc->dtype);
+        if (scales_bytes) *scales_bytes = c * kLowRankRank * sizeof(float);
+    } else if (desc->scale == CF_SPARSE_NM) {      // one mask byte per block of 8, then (16-byte aligned) bits values per block
         if (codes_bytes) *codes_bytes = (n * (c / 8) + 15) / 16 * 16 + n * (c / 8) * (size_t)desc->bits * dtype_size(desc->dtype);
         if (scales_bytes) *scales_bytes = 0;
     } else {
@@ -651,6 +714,10 @@ cf_status cf_decompress(cf_ctx *ctx, int32_t first, int32_t count, const void *c
     if (st != CF_OK) return st;
     hipError_t e = launch(ctx, s, "k_decode", [&] { return launch_decode(ctx->view(), ctx->range(first, count), s); });
     if (e != hipSuccess) return device_fail(ctx, e);
+    if (ctx->range_lowrank_iters(first, count) >= 0) {
+        e = launch(ctx, s, "k_lr_apply", [&] { return launch_lr_decode(ctx->view(), ctx->range(first, count), s); });
+        if (e != hipSuccess) return device_fail(ctx, e);
+    }
     return CF_OK;
 }
 

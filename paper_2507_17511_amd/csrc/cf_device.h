@@ -14,7 +14,7 @@ namespace cf {
 namespace dev {
 
 constexpr int F32 = 0, BF16 = 1;
-constexpr int SCALE_CHANNEL = 0, SCALE_GROUP = 1, SCALE_RANK1 = 2, SPARSE_NM = 3;
+constexpr int SCALE_CHANNEL = 0, SCALE_GROUP = 1, SCALE_RANK1 = 2, SPARSE_NM = 3, LOWRANK = 4;
 constexpr int EF_RECON = 0, EF_LITERAL = 1, EF_OFF = 2, EF_NAIVE = 3;
 
 #define CF_GLOBAL __attribute__((address_space(1)))

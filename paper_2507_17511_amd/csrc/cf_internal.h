@@ -53,6 +53,8 @@ struct alignas(16) TensorDev {
     // rank-1 scales: per-row sums of |z| over each 1024-channel tile, rowpart[N][n_colblocks]
     uint32_t r1_pad_;
     uint64_t rowpart_off;
+    // low-rank compressor: P = A Q [N][32], Z = A^T P [C][32], Q in the order k_lr_project reads it (all fp32)
+    uint64_t lr_p_off, lr_z_off, lr_q_off;
 };
 
 // Per-call device pointers of one tensor; uploaded into the workspace.
@@ -92,6 +94,8 @@ struct LaunchRange {
     int32_t dts;                // storage dtype of every tensor in the range (cf_dtype), or 2 if mixed
     int32_t only_group_scale;   // tiled encode: skip tensors the single-pass kernel covers
     int32_t naive;              // decode: recon_t = D instead of recon_{t-1} + D (CF_EF_NAIVE)
+    int32_t lr_max_channels;    // low-rank tensors of the range: largest C and N (0 = none)
+    int64_t lr_max_tokens;
 };
 
 enum class Op { Compress, StepFused };
@@ -103,6 +107,16 @@ hipError_t launch_finalize(const BatchView &v, const LaunchRange &r, hipStream_t
 hipError_t launch_finalize_rank1(const BatchView &v, const LaunchRange &r, hipStream_t s);
 hipError_t launch_encode(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, bool fused, hipStream_t s);
 hipError_t launch_decode(const BatchView &v, const LaunchRange &r, hipStream_t s);
+
+// Low-rank compressor (cf_lowrank.hip): rank 32, C a multiple of 32 and at most kLowRankMaxChannels.
+constexpr int kLowRankRank = 32;
+constexpr int kLowRankMaxChannels = 3072;
+// min_iters: only tensors whose descriptor asks for at least that many subspace iterations take part
+hipError_t launch_lr_orth(const BatchView &v, const LaunchRange &r, bool from_q0, int min_iters, hipStream_t s);
+hipError_t launch_lr_project(const BatchView &v, const LaunchRange &r, bool wire, int min_iters, hipStream_t s);
+hipError_t launch_lr_backproject(const BatchView &v, const LaunchRange &r, int min_iters, hipStream_t s);
+hipError_t launch_lr_encode(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, hipStream_t s);
+hipError_t launch_lr_decode(const BatchView &v, const LaunchRange &r, hipStream_t s);
 
 // Single-pass kernel (channel scales, CF_EF_RECON).  `grid` workgroups must be co-resident.
 int persistent_max_blocks_per_cu(int err_dtype, bool fused);

@@ -191,7 +191,7 @@ __global__ __launch_bounds__(kTileThreads) void k_colreduce(BatchView v, LaunchR
 {
     TileCtx c = locate_tile<false>(v, r);
     const TensorDev &d = c.d;
-    if (d.scale == SCALE_GROUP || d.scale == SPARSE_NM) return;      // row-local: nothing to reduce
+    if (d.scale != SCALE_CHANNEL && d.scale != SCALE_RANK1) return;  // row-local codecs: nothing to reduce
     if (is_bf16<DTS>(d)) {
         if (d.scale == SCALE_RANK1) colreduce_tile<BF16, EF, ET, false, true>(c, v.workspace);
         else if (d.bits == 4) colreduce_tile<BF16, EF, ET, true, false>(c, v.workspace);
@@ -212,7 +212,7 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_finalize(BatchView v, Laun
     uint32_t blk = r.fin_lo + blockIdx.x;
     int t = find_slot(v.fin_prefix, r.first, r.first + r.count, blk);
     const TensorDev d = v.descs[t];
-    if (d.scale == SCALE_GROUP || d.scale == SPARSE_NM) return;
+    if (d.scale != SCALE_CHANNEL && d.scale != SCALE_RANK1) return;
     int col = (int)(blk - d.fin_begin) * kFinalizeThreads + (int)threadIdx.x;
     if (col >= d.n_channels) return;
     const CF_GLOBAL float *partial = gconst<float>(v.workspace + d.partial_off) + col;
@@ -451,6 +451,7 @@ __global__ __launch_bounds__(kTileThreads) void k_encode(BatchView v, LaunchRang
 {
     TileCtx c = locate_tile<true>(v, r);
     if (r.only_group_scale && c.d.scale == SCALE_CHANNEL) return;   // covered by the single-pass kernel
+    if (c.d.scale == LOWRANK) return;                               // has kernels of its own
     if (is_bf16<DTS>(c.d)) encode_dispatch<BF16, EF, ET, FUSED>(c);
     else encode_dispatch<F32, EF, ET, FUSED>(c);
 }
@@ -567,6 +568,7 @@ template <int DTS>
 __global__ __launch_bounds__(kTileThreads) void k_decode(BatchView v, LaunchRange r)
 {
     TileCtx c = locate_tile<true>(v, r);
+    if (c.d.scale == LOWRANK) return;
     if (is_bf16<DTS>(c.d)) decode_dispatch<BF16>(c, r.naive != 0); else decode_dispatch<F32>(c, r.naive != 0);
 }
 

@@ -1,0 +1,466 @@
+// Low-rank compressor (arxiv 2507.17511, Alg. 3 and App. D "Low-Rank Compression") under the
+// residual recursion of Sec. 3.1: A = x_t - recon_{t-1} [tokens, channels] is sent as rank-32 factors
+// U = A Q [tokens, 32], V = Q [channels, 32] found by T steps of subspace iteration
+//     Q <- orth(Q0);  T x { Z <- A^T (A Q);  Q <- orth(Z) };  U <- A Q,
+// and both ends add D = U V^T to the reconstruction; e_t = A - D stays at the sender.
+//
+// This is the one dense contraction of the codec, so it runs on the matrix cores: every product is a
+// chain of v_mfma_f32_32x32x2_f32 (fp32 in, fp32 accumulate; 32 = the rank fills the N side of the
+// tile exactly).  A is never materialised: each pass re-forms it from x and recon (4 bytes per element
+// in bf16 storage, the same as reading an fp32 A would cost) and is bound by that stream.
+//
+// Operand layouts are chosen so that every lane feeds the MFMA straight from a 128-bit row-major
+// load, with no staging through LDS.  The instruction computes D[m][n] += sum_k A[m][k] B[k][n] with
+// lane l holding A[l % 32][l / 32] and B[l / 32][l % 32]: any relabelling of k that both operands share,
+// and any relabelling of m or n that the epilogue undoes, is free.
+//   project      P = A Q     m = token, k = channel: a lane loads 16 consecutive channels of its token
+//                            and spends them on 16 instructions; Q is kept in that per-lane order.
+//   backproject  Z = A^T P   m = channel, k = token: a lane loads 8 consecutive channels of its token and
+//                            spends them on 8 accumulator tiles (tile j holds channels = j mod 8).
+//   encode       D^T = V U^T m = channel (relabelled so that a lane ends up with 16 consecutive channels
+//                            of its token), n = token, k = rank.
+#include "cf_device.h"
+#include "cf_internal.h"
+
+namespace cf {
+namespace {
+
+using namespace dev;
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kRank = 32;
+constexpr float kDrop2 = 1e-8f;     // (1e-4)^2: a column left with less than 1e-4 of its length is dropped
+
+__device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
+
+template <int DT> __device__ __forceinline__ void load16(const void *base, int64_t elem, float (&out)[16])
+{
+    Raw8<DT> lo, hi;
+    lo.load(base, elem);
+    hi.load(base, elem + 8);
+    const F8 a = lo.widen(), b = hi.widen();
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        out[k] = a.v[k];
+        out[8 + k] = b.v[k];
+    }
+}
+
+// 16 consecutive elements of the residual x - recon of one token, or zeros.
+template <int DT> __device__ __forceinline__ void residual16(const TensorPtrs &p, int64_t elem, bool valid, float (&z)[16])
+{
+    if (valid) {
+        float x[16], b[16];
+        load16<DT>(p.x, elem, x);
+        load16<DT>(p.recon, elem, b);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) z[k] = x[k] - b[k];
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) z[k] = 0.0f;
+    }
+}
+
+__device__ __forceinline__ uint8_t *wire_u(const TensorPtrs &p) { return p.codes; }
+__device__ __forceinline__ uint8_t *wire_v(const TensorDev &d, const TensorPtrs &p)
+{
+    return p.codes + d.n_tokens * kRank * (d.dtype == BF16 ? 2 : 4);
+}
+
+// ---------------------------------------------------------------- P = A Q  (and U on the wire)
+
+// A wave owns 64 tokens (two accumulator tiles that share the Q operand), a workgroup 256.
+// Q is read in its per-lane order: step s (32 channels), lane l, 16 floats at ((s * 64 + l) * 16).
+template <int DT>
+__device__ __forceinline__ void lr_project_body(const BatchView &v, const TensorDev &d, const TensorPtrs &p, bool wire)
+{
+    const int lane = (int)threadIdx.x & 63, wave = (int)threadIdx.x >> 6;
+    const int m = lane & 31, h = lane >> 5;
+    const int64_t row_base = (int64_t)blockIdx.x * 256 + wave * 64;
+    if (row_base >= d.n_tokens) return;                     // uniform over the wave
+    const int64_t r0 = row_base + m, r1 = r0 + 32;
+    const bool ok0 = r0 < d.n_tokens, ok1 = r1 < d.n_tokens;
+    const int64_t C = d.n_channels;
+    const CF_GLOBAL f32x4 *qs = gconst<f32x4>(v.workspace + d.lr_q_off);
+    f32x16 acc0 = {}, acc1 = {};
+    const int steps = d.n_channels / 32;
+    for (int s = 0; s < steps; ++s) {
+        const int64_t cb = (int64_t)s * 32 + 16 * h;
+        float z0[16], z1[16], q[16];
+        residual16<DT>(p, r0 * C + cb, ok0, z0);
+        residual16<DT>(p, r1 * C + cb, ok1, z1);
+        const CF_GLOBAL f32x4 *qp = qs + ((int64_t)s * 64 + lane) * 4;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const f32x4 w = qp[k];
+            q[4 * k] = w.x; q[4 * k + 1] = w.y; q[4 * k + 2] = w.z; q[4 * k + 3] = w.w;
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            acc0 = mfma32(z0[j], q[j], acc0);
+            acc1 = mfma32(z1[j], q[j], acc1);
+        }
+    }
+    // accumulator register i of lane (m, h): row 8 * (i / 4) + 4 * h + i % 4 of the tile, column m
+    CF_GLOBAL float *P = gmut<float>(v.workspace + d.lr_p_off);
+    uint8_t *U = wire_u(p);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int row = 8 * (i >> 2) + 4 * h + (i & 3);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int64_t rr = row_base + 32 * half + row;
+            const float val = half ? acc1[i] : acc0[i];
+            if (rr < d.n_tokens) {
+                P[rr * kRank + m] = val;
+                if (wire) {
+                    if (DT == BF16) gmut<uint16_t>(U)[rr * kRank + m] = (uint16_t)bf16_rne(val);
+                    else gmut<float>(U)[rr * kRank + m] = val;
+                }
+            }
+        }
+    }
+}
+
+// min_iters: tensors that asked for fewer subspace iterations than this sit the launch out.
+__global__ __launch_bounds__(256) void k_lr_project(BatchView v, LaunchRange r, int wire, int min_iters)
+{
+    const int t = r.first + (int)blockIdx.y;
+    const TensorDev d = v.descs[t];
+    if (d.scale != LOWRANK || d.bits < min_iters) return;
+    const TensorPtrs p = v.ptrs[t];
+    if (d.dtype == BF16) lr_project_body<BF16>(v, d, p, wire != 0);
+    else lr_project_body<F32>(v, d, p, wire != 0);
+}
+
+// ---------------------------------------------------------------- Z = A^T P
+
+// A workgroup owns a stripe of 256 channels; its 4 waves split the tokens and add their tiles up
+// through LDS in wave order.  Lane (q, h): channels 8q..8q+7 of the stripe, token 2 * pair + h.
+template <int DT>
+__device__ __forceinline__ void lr_backproject_body(const BatchView &v, const TensorDev &d, const TensorPtrs &p, float *sum)
+{
+    const int lane = (int)threadIdx.x & 63, wave = (int)threadIdx.x >> 6;
+    const int q = lane & 31, h = lane >> 5;
+    const int ch0 = (int)blockIdx.x * 256 + 8 * q;
+    const bool cvalid = ch0 < d.n_channels;
+    const int64_t C = d.n_channels;
+    const int64_t n_pairs = (d.n_tokens + 1) / 2;
+    const int64_t per_wave = (n_pairs + 3) / 4;
+    const int64_t lo = wave * per_wave;
+    const int64_t hi = lo + per_wave < n_pairs ? lo + per_wave : n_pairs;
+    const CF_GLOBAL float *P = gconst<float>(v.workspace + d.lr_p_off);
+    f32x16 acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = (f32x16){};
+    constexpr int U = 2;                                    // token pairs in flight
+    for (int64_t pair0 = lo; pair0 < hi; pair0 += U) {
+        Raw8<DT> xr[U], br[U];
+        float pv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t row = 2 * (pair0 + u) + h;
+            const bool rvalid = pair0 + u < hi && row < d.n_tokens;
+            if (rvalid && cvalid) {
+                xr[u].load(p.x, row * C + ch0);
+                br[u].load(p.recon, row * C + ch0);
+            } else {
+                xr[u].zero();
+                br[u].zero();
+            }
+            pv[u] = rvalid ? P[row * kRank + q] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const F8 x = xr[u].widen(), b = br[u].widen();
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = mfma32(x.v[j] - b.v[j], pv[u], acc[j]);
+        }
+    }
+    // tile j, register i of lane (q, h): channel 8 * rho + j of the stripe with rho = 8 * (i / 4) + 4 * h + i % 4, column q
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int rho = 8 * (i >> 2) + 4 * h + (i & 3);
+                    const int idx = (8 * rho + j) * kRank + q;
+                    sum[idx] = (w == 0) ? acc[j][i] : sum[idx] + acc[j][i];
+                }
+        }
+        __syncthreads();
+    }
+    CF_GLOBAL float *Z = gmut<float>(v.workspace + d.lr_z_off);
+    for (int k = (int)threadIdx.x; k < 256 * kRank; k += 256) {
+        const int ch = (int)blockIdx.x * 256 + k / kRank;
+        if (ch < d.n_channels) Z[(int64_t)ch * kRank + (k % kRank)] = sum[k];
+    }
+}
+
+__global__ __launch_bounds__(256, 2) void k_lr_backproject(BatchView v, LaunchRange r, int min_iters)
+{
+    __shared__ float sum[256 * kRank];
+    const int t = r.first + (int)blockIdx.y;
+    const TensorDev d = v.descs[t];
+    if (d.scale != LOWRANK || d.bits < min_iters) return;
+    if ((int)blockIdx.x * 256 >= d.n_channels) return;      // uniform over the workgroup
+    const TensorPtrs p = v.ptrs[t];
+    if (d.dtype == BF16) lr_backproject_body<BF16>(v, d, p, sum);
+    else lr_backproject_body<F32>(v, d, p, sum);
+}
+
+// ---------------------------------------------------------------- Q = orth(Z)
+
+// Gram-Schmidt over the 32 columns, left to right, every column projected twice; one workgroup of
+// 1024 lanes per tensor holds the matrix in registers (3 channel rows per lane: C <= 3072).  A column
+// left with less than 1e-4 of its length is dropped (zero): a residual of rank < 32 then gives zero
+// columns rather than amplified rounding noise.  Writes Q in the per-lane order k_lr_project reads,
+// and V = Q on the wire.
+constexpr int kOrthThreads = 1024;
+constexpr int kOrthRows = 3;
+
+struct OrthShared {
+    float part[kOrthThreads / 64][kRank + 1];
+    float total[kRank + 1];
+};
+
+// Sums `val` over the workgroup into sh.total[slot]; the caller places the barriers.
+__device__ __forceinline__ void orth_partial(OrthShared &sh, int slot, float val)
+{
+    const float w = wave_tree_sum(val);
+    if (((int)threadIdx.x & 63) == 0) sh.part[(int)threadIdx.x >> 6][slot] = w;
+}
+
+__device__ __forceinline__ void orth_finish(OrthShared &sh, int n_slots)
+{
+    __syncthreads();
+    if ((int)threadIdx.x < n_slots) {
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kOrthThreads / 64; ++w) s += sh.part[w][threadIdx.x];
+        sh.total[threadIdx.x] = s;
+    }
+    __syncthreads();
+}
+
+// Column K: project it on the finished columns 0..K-1 (twice), then normalise or drop it.  K is a
+// template parameter so that every register of the matrix is addressed statically.
+template <int K>
+__device__ __forceinline__ void orth_column(float (&a)[kOrthRows][kRank], OrthShared &sh)
+{
+    float start2 = 0.0f;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        // <q_j, a_K> for every finished column j < K, and (first pass) the column's own length
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            float dot = 0.0f;
+#pragma unroll
+            for (int rr = 0; rr < kOrthRows; ++rr) dot += a[rr][j] * a[rr][K];
+            orth_partial(sh, j, dot);
+        }
+        if (pass == 0) {
+            float own = 0.0f;
+#pragma unroll
+            for (int rr = 0; rr < kOrthRows; ++rr) own += a[rr][K] * a[rr][K];
+            orth_partial(sh, K, own);
+        }
+        orth_finish(sh, pass == 0 ? K + 1 : K);
+        if (pass == 0) start2 = sh.total[K];
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            const float c = sh.total[j];
+#pragma unroll
+            for (int rr = 0; rr < kOrthRows; ++rr) a[rr][K] -= c * a[rr][j];
+        }
+    }
+    float own = 0.0f;
+#pragma unroll
+    for (int rr = 0; rr < kOrthRows; ++rr) own += a[rr][K] * a[rr][K];
+    orth_partial(sh, 0, own);
+    orth_finish(sh, 1);
+    const float left2 = sh.total[0];
+    const bool keep = start2 > 0.0f && left2 > kDrop2 * start2;
+    const float len = sqrtf(left2);
+#pragma unroll
+    for (int rr = 0; rr < kOrthRows; ++rr) a[rr][K] = keep ? a[rr][K] / len : 0.0f;
+    __syncthreads();                                        // sh.total is rewritten by the next column
+}
+
+template <int K>
+__device__ __forceinline__ void orth_columns_from(float (&a)[kOrthRows][kRank], OrthShared &sh)
+{
+    orth_column<K>(a, sh);
+    if constexpr (K + 1 < kRank) orth_columns_from<K + 1>(a, sh);
+}
+
+__global__ __launch_bounds__(kOrthThreads) void k_lr_orth(BatchView v, LaunchRange r, int from_q0, int min_iters)
+{
+    __shared__ OrthShared sh;
+    const int t = r.first + (int)blockIdx.x;
+    const TensorDev d = v.descs[t];
+    if (d.scale != LOWRANK || d.bits < min_iters) return;
+    const TensorPtrs p = v.ptrs[t];
+    const CF_GLOBAL f32x4 *src = from_q0 ? gconst<f32x4>(p.scales) : gconst<f32x4>(v.workspace + d.lr_z_off);
+    float a[kOrthRows][kRank];
+#pragma unroll
+    for (int rr = 0; rr < kOrthRows; ++rr) {
+        const int ch = (int)threadIdx.x + kOrthThreads * rr;
+#pragma unroll
+        for (int k = 0; k < kRank / 4; ++k) {
+            f32x4 w = {};
+            if (ch < d.n_channels) w = src[(int64_t)ch * (kRank / 4) + k];
+            a[rr][4 * k] = w.x; a[rr][4 * k + 1] = w.y; a[rr][4 * k + 2] = w.z; a[rr][4 * k + 3] = w.w;
+        }
+    }
+    orth_columns_from<0>(a, sh);
+    CF_GLOBAL float *qs = gmut<float>(v.workspace + d.lr_q_off);
+    uint8_t *V = wire_v(d, p);
+#pragma unroll
+    for (int rr = 0; rr < kOrthRows; ++rr) {
+        const int ch = (int)threadIdx.x + kOrthThreads * rr;
+        if (ch >= d.n_channels) continue;
+        const int s = ch >> 5, c = ch & 31, hh = c >> 4, j = c & 15;
+#pragma unroll
+        for (int n = 0; n < kRank; ++n) {
+            qs[((int64_t)s * 64 + hh * 32 + n) * 16 + j] = a[rr][n];
+            if (d.dtype == BF16) gmut<uint16_t>(V)[(int64_t)ch * kRank + n] = (uint16_t)bf16_rne(a[rr][n]);
+            else gmut<float>(V)[(int64_t)ch * kRank + n] = a[rr][n];
+        }
+    }
+}
+
+// ---------------------------------------------------------------- D = U V^T, error and reconstruction
+
+// 16 consecutive rank entries (16 * h ...) of one row of a factor on the wire, widened.
+template <int DT> __device__ __forceinline__ void factor16(const uint8_t *base, int64_t row, int h, bool valid, float (&out)[16])
+{
+    if (valid) {
+        load16<DT>(base, row * kRank + 16 * h, out);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) out[k] = 0.0f;
+    }
+}
+
+// A wave owns 32 tokens and walks the channels in tiles of 32.  MFMA rows are channels, relabelled
+// rho -> 16 * ((rho / 4) % 2) + 4 * (rho / 8) + rho % 4 so that the 16 accumulator registers of lane
+// (token, h) are the 16 consecutive channels 16 * h ... of the tile.
+// SENDER: also forms A again and writes e = A - D.  UPDATE: writes recon + D (or D alone when `replace`).
+template <int DT, int ET, bool SENDER, bool UPDATE>
+__device__ __forceinline__ void lr_apply_body(const TensorDev &d, const TensorPtrs &p)
+{
+    const int lane = (int)threadIdx.x & 63, wave = (int)threadIdx.x >> 6;
+    const int n = lane & 31, h = lane >> 5;
+    const int64_t tok_base = (int64_t)blockIdx.x * 128 + wave * 32;
+    if (tok_base >= d.n_tokens) return;                     // uniform over the wave
+    const int64_t tok = tok_base + n;
+    const bool tvalid = tok < d.n_tokens;
+    const int64_t C = d.n_channels;
+    float u[16];
+    factor16<DT>(wire_u(p), tok, h, tvalid, u);
+    const int rho = lane & 31;
+    const int pi = 16 * ((rho >> 2) & 1) + 4 * (rho >> 3) + (rho & 3);
+    const uint8_t *V = wire_v(d, p);
+    const int tiles = d.n_channels / 32;
+    for (int tile = 0; tile < tiles; ++tile) {
+        float vv[16];
+        factor16<DT>(V, (int64_t)tile * 32 + pi, h, true, vv);
+        f32x16 acc = {};
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc = mfma32(vv[j], u[j], acc);
+        if (!tvalid) continue;
+        const int64_t e0 = tok * C + (int64_t)tile * 32 + 16 * h;
+        float b[16];
+        load16<DT>(p.recon, e0, b);
+        if (SENDER) {
+            float x[16];
+            load16<DT>(p.x, e0, x);
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                F8 lost;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const float z = x[8 * half + k] - b[8 * half + k];
+                    lost.v[k] = z - acc[8 * half + k];
+                }
+                Raw8<ET> eo;
+                eo.narrow(lost);
+                eo.store(p.err, e0 + 8 * half);
+            }
+        }
+        if (UPDATE) {
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                F8 nb;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) nb.v[k] = b[8 * half + k] + acc[8 * half + k];
+                Raw8<DT> out;
+                out.narrow(nb);
+                out.store(p.recon, e0 + 8 * half);
+            }
+        }
+    }
+}
+
+template <int ET, bool SENDER, bool UPDATE>
+__global__ __launch_bounds__(256) void k_lr_apply(BatchView v, LaunchRange r)
+{
+    const int t = r.first + (int)blockIdx.y;
+    const TensorDev d = v.descs[t];
+    if (d.scale != LOWRANK) return;
+    const TensorPtrs p = v.ptrs[t];
+    if (d.dtype == BF16) lr_apply_body<BF16, ET, SENDER, UPDATE>(d, p);
+    else lr_apply_body<F32, ET, SENDER, UPDATE>(d, p);
+}
+
+}  // namespace
+
+hipError_t launch_lr_orth(const BatchView &v, const LaunchRange &r, bool from_q0, int min_iters, hipStream_t s)
+{
+    if (r.count == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_lr_orth, dim3(r.count), dim3(kOrthThreads), 0, s, v, r, from_q0 ? 1 : 0, min_iters);
+    return hipGetLastError();
+}
+
+hipError_t launch_lr_project(const BatchView &v, const LaunchRange &r, bool wire, int min_iters, hipStream_t s)
+{
+    if (r.count == 0 || r.lr_max_tokens == 0) return hipSuccess;
+    dim3 grid((unsigned)((r.lr_max_tokens + 255) / 256), (unsigned)r.count);
+    hipLaunchKernelGGL(k_lr_project, grid, dim3(256), 0, s, v, r, wire ? 1 : 0, min_iters);
+    return hipGetLastError();
+}
+
+hipError_t launch_lr_backproject(const BatchView &v, const LaunchRange &r, int min_iters, hipStream_t s)
+{
+    if (r.count == 0 || r.lr_max_channels == 0) return hipSuccess;
+    dim3 grid((unsigned)((r.lr_max_channels + 255) / 256), (unsigned)r.count);
+    hipLaunchKernelGGL(k_lr_backproject, grid, dim3(256), 0, s, v, r, min_iters);
+    return hipGetLastError();
+}
+
+hipError_t launch_lr_encode(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, hipStream_t s)
+{
+    if (r.count == 0 || r.lr_max_tokens == 0) return hipSuccess;
+    dim3 grid((unsigned)((r.lr_max_tokens + 127) / 128), (unsigned)r.count), block(256);
+    if (err_dtype == BF16) {
+        if (fused) hipLaunchKernelGGL((k_lr_apply<BF16, true, true>), grid, block, 0, s, v, r);
+        else hipLaunchKernelGGL((k_lr_apply<BF16, true, false>), grid, block, 0, s, v, r);
+    } else {
+        if (fused) hipLaunchKernelGGL((k_lr_apply<F32, true, true>), grid, block, 0, s, v, r);
+        else hipLaunchKernelGGL((k_lr_apply<F32, true, false>), grid, block, 0, s, v, r);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_lr_decode(const BatchView &v, const LaunchRange &r, hipStream_t s)
+{
+    if (r.count == 0 || r.lr_max_tokens == 0) return hipSuccess;
+    dim3 grid((unsigned)((r.lr_max_tokens + 127) / 128), (unsigned)r.count);
+    hipLaunchKernelGGL((k_lr_apply<F32, false, true>), grid, dim3(256), 0, s, v, r);
+    return hipGetLastError();
+}
+
+}  // namespace cf

@@ -28,7 +28,7 @@ class CodecSession:
             shape = (d.n_tokens, d.n_channels)
             self.recon.append(torch.empty(shape, dtype=_TORCH_DT[d.dtype], device=self.device))
             self.err.append(torch.empty(shape, dtype=_TORCH_DT[self.opts.err_dtype], device=self.device))
-            codes_shape = (cb,) if d.scale == cf.CF_SPARSE_NM else (d.n_tokens, cb // d.n_tokens)   # masks then values
+            codes_shape = (cb,) if d.scale in (cf.CF_SPARSE_NM, cf.CF_LOWRANK) else (d.n_tokens, cb // d.n_tokens)   # two arrays in one buffer
             self.codes.append(torch.empty(codes_shape, dtype=torch.uint8, device=self.device))
             self.scales.append(torch.empty(sb // 4, dtype=torch.float32, device=self.device))
         self.ws_bytes = cf.cf_workspace_bytes(self.descs, self.opts)

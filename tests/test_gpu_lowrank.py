@@ -1,0 +1,197 @@
+"""GPU parity of the low-rank compressor (Alg. 3; App. D "Low-Rank Compression") against the fp64 oracle.
+
+The path is floating-point linear algebra on the matrix cores (fp32 in, fp32 accumulate), so the bar is a
+tolerance, derived here from the arithmetic:
+  * factors against the oracle: an fp32 dot product over C <= 3072 channels carries a relative error of about
+    sqrt(C) * 2^-24 ~ 3e-6 of the operand norms, Gram-Schmidt passes it on multiplied by the conditioning of Z
+    (below 100 for the test matrices): 1e-3 of the largest factor entry is asserted, 1e-5 is what is seen.  bf16
+    factors may also differ by one bf16 ulp where the fp32 value sits next to a rounding boundary.
+  * everything after the factors (D, error, reconstruction) is checked against an fp64 evaluation of the
+    GPU's OWN travelled factors, which removes that sensitivity: D is a 32-term fp32 dot product (1e-5 of the
+    term magnitudes); the reconstruction is rounded once (half a bf16 ulp).
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2507_17511_amd as cf
+from oracle import lowrank as lr
+from paper_2507_17511_amd.session import CodecSession
+from workloads import as_numpy
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+R = 32
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def stream(n, c, dtype, steps, seed, rank=48, decay=0.93, noise=0.02):
+    """x_0 ~ N(0,1); each step adds a matrix with a geometrically decaying spectrum plus a little full-rank noise."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    x = torch.randn((n, c), generator=g, device=DEV)
+    sv = decay ** torch.arange(rank, device=DEV, dtype=torch.float32)
+    out = []
+    for _ in range(steps):
+        out.append(x.to(torch.bfloat16).contiguous() if dtype == cf.CF_BF16 else x.clone())
+        left = torch.randn((n, rank), generator=g, device=DEV) * sv
+        right = torch.randn((rank, c), generator=g, device=DEV)
+        x = x + 0.05 * (left @ right) / rank ** 0.5 + noise * 0.05 * torch.randn((n, c), generator=g, device=DEV)
+    return out
+
+
+def start_matrices(c, steps, seed):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    return [torch.randn((c, R), generator=g, device=DEV) for _ in range(steps)]
+
+
+def split_wire(codes: np.ndarray, n, c, dtype):
+    flat = codes.reshape(-1)
+    if dtype == cf.CF_BF16:
+        w = flat.view(np.uint16)
+    else:
+        w = flat.view(np.float32)
+    return w[:n * R].reshape(n, R).copy(), w[n * R:(n + c) * R].reshape(c, R).copy()
+
+
+def check_step(tag, cfg, sess, t, x, recon_before, q0, wire_tol=1e-3):
+    n, c, dt = cfg.n_tokens, cfg.n_channels, cfg.dtype
+    Ug, Vg = split_wire(as_numpy(sess.codes[t]), n, c, dt)
+    Uo, Vo, erro, recono = lr.step(cfg, x, recon_before, q0)
+    U64, V64, Uo64, Vo64 = lr.widen(Ug, dt), lr.widen(Vg, dt), lr.widen(Uo, dt), lr.widen(Vo, dt)
+    ulp = 2.0 ** -7 if dt == lr.BF16 else 0.0      # one bf16 step is between 2^-8 and 2^-7 of the value
+    for name, got, want in (("U", U64, Uo64), ("V", V64, Vo64)):
+        tol = wire_tol * np.abs(want).max() + ulp * np.abs(want)
+        worst = float((np.abs(got - want) - ulp * np.abs(want)).max() / np.abs(want).max())
+        assert np.all(np.abs(got - want) <= tol), f"{tag}: factor {name} off by {worst:.2e} of its largest entry"
+    # the subspace itself (independent of the basis)
+    proj_gap = np.linalg.norm(V64 @ V64.T - Vo64 @ Vo64.T)
+    assert proj_gap < (0.05 if dt == lr.BF16 else 1e-3), f"{tag}: projector differs by {proj_gap:.2e}"
+    # from the GPU's own factors on: D, e, recon
+    A = lr.widen(x, dt).reshape(n, c) - lr.widen(recon_before, dt).reshape(n, c)
+    D = U64 @ V64.T
+    terms = np.abs(U64) @ np.abs(V64).T
+    err = as_numpy(sess.err[t]).astype(np.float64).reshape(n, c)
+    assert np.all(np.abs(err - (A - D)) <= 1e-5 * terms + 1e-6 * np.abs(A) + 1e-30), f"{tag}: e != A - U V^T"
+    recon = lr.widen(as_numpy(sess.recon[t]), dt).reshape(n, c)
+    target = lr.widen(recon_before, dt).reshape(n, c) + D
+    half_ulp = (2.0 ** -8 if dt == lr.BF16 else 2.0 ** -23) * np.abs(target) * 1.01
+    assert np.all(np.abs(recon - target) <= half_ulp + 1e-5 * terms + 1e-30), f"{tag}: recon != recon + U V^T"
+    # and the oracle's end result, loosely (it went through the oracle's own factors)
+    loose = (2e-2 if dt == lr.BF16 else 1e-3) * np.abs(A).max()
+    assert np.abs(err - erro).max() <= loose, f"{tag}: error buffer {np.abs(err - erro).max():.2e} from the oracle's"
+    return float(np.abs(U64 - Uo64).max() / np.abs(Uo64).max()), float(np.abs(V64 - Vo64).max())
+
+
+@pytest.mark.parametrize("dtype", [cf.CF_F32, cf.CF_BF16])
+@pytest.mark.parametrize("iters", [1, 2])
+@pytest.mark.parametrize("mode", ["fused", "split"])
+def test_lowrank_parity(dtype, iters, mode):
+    for k, (n, c) in enumerate([(96, 128), (203, 1024), (300, 3072), (64, 32), (1, 64), (517, 96)]):
+        say(f"lowrank dtype={dtype} T={iters} mode={mode} N={n} C={c}")
+        d = cf.desc(n, c, dtype, iters, cf.CF_LOWRANK, R)
+        cfg = lr.LowRankConfig(n, c, dtype=dtype, rank=R, iters=iters)
+        xs = stream(n, c, dtype, 4, 900 + k)
+        q0s = start_matrices(c, 4, 950 + k)
+        sess = CodecSession([d], cf.options(), device=DEV)
+        try:
+            sess.warmup([xs[0]])
+            for s in range(1, 4):
+                before = as_numpy(sess.recon[0]).copy()
+                sess.scales[0].copy_(q0s[s].reshape(-1))
+                if mode == "fused":
+                    sess.step_fused([xs[s]])
+                else:
+                    sess.compress([xs[s]])
+                    sess.decompress()
+                cf.cf_check_device(sess.ctx, sess.stream_handle)
+                du, dv = check_step(f"N{n}C{c} step {s}", cfg, sess, 0, as_numpy(xs[s]), before, as_numpy(q0s[s]))
+            say(f"   factors within {du:.1e} (U, relative) and {dv:.1e} (V, absolute) of the oracle")
+        finally:
+            sess.close()
+
+
+def test_lowrank_exact_for_residuals_of_small_rank():
+    """A residual of rank 5 < 32 comes through unchanged (fp32 storage), and the unused columns are dropped."""
+    n, c = 200, 256
+    g = torch.Generator(device=DEV)
+    g.manual_seed(4)
+    x0 = torch.randn((n, c), generator=g, device=DEV)
+    delta = torch.randn((n, 5), generator=g, device=DEV) @ torch.randn((5, c), generator=g, device=DEV)
+    x1 = x0 + 0.1 * delta
+    q0 = torch.randn((c, R), generator=g, device=DEV)
+    sess = CodecSession([cf.desc(n, c, cf.CF_F32, 1, cf.CF_LOWRANK, R)], cf.options(), device=DEV)
+    try:
+        sess.warmup([x0])
+        sess.scales[0].copy_(q0.reshape(-1))
+        sess.step_fused([x1])
+        cf.cf_check_device(sess.ctx, sess.stream_handle)
+        _, V = split_wire(as_numpy(sess.codes[0]), n, c, cf.CF_F32)
+        assert np.count_nonzero(np.abs(V).sum(axis=0)) == 5
+        assert float((sess.recon[0] - x1).abs().max()) < 1e-4 * float((x1 - x0).abs().max())
+        assert float(sess.err[0].abs().max()) < 1e-4 * float((x1 - x0).abs().max())
+    finally:
+        sess.close()
+
+
+def test_lowrank_in_a_mixed_batch_and_receiver():
+    """Low-rank tensors next to quantised and sparsified ones in one call; a receiver fed the wire reaches the
+    sender's reconstruction bit for bit (both ends add the same D)."""
+    from helpers import OracleState, compare_tensor
+    descs = [cf.desc(203, 1024, cf.CF_BF16, 1, cf.CF_LOWRANK, R), cf.desc(130, 264, cf.CF_BF16, 2, cf.CF_SCALE_CHANNEL),
+             cf.desc(96, 128, cf.CF_F32, 2, cf.CF_LOWRANK, R), cf.desc(67, 3072, cf.CF_BF16, 2, cf.CF_SPARSE_NM, 8)]
+    xs = [stream(int(d.n_tokens), int(d.n_channels), int(d.dtype), 3, 70 + t) for t, d in enumerate(descs)]
+    q0 = {0: start_matrices(1024, 3, 5), 2: start_matrices(128, 3, 6)}
+    send = CodecSession(descs, cf.options(), device=DEV)
+    recv = CodecSession(descs, cf.options(), device=DEV)
+    orc = OracleState(descs, cf.options(), [1, 3])
+    try:
+        first = [x[0] for x in xs]
+        send.warmup(first)
+        recv.warmup(first)
+        for t in (1, 3):
+            orc.warmup(t, as_numpy(first[t]))
+        for s in (1, 2):
+            now = [x[s] for x in xs]
+            before = {t: as_numpy(send.recon[t]).copy() for t in (0, 2)}
+            for t in (0, 2):
+                send.scales[t].copy_(q0[t][s].reshape(-1))
+            send.step_fused(now)
+            cf.cf_check_device(send.ctx, send.stream_handle)
+            for t in (0, 2):
+                cfg = lr.LowRankConfig(int(descs[t].n_tokens), int(descs[t].n_channels), dtype=int(descs[t].dtype), rank=R,
+                                       iters=int(descs[t].bits))
+                check_step(f"mixed t{t} step {s}", cfg, send, t, as_numpy(now[t]), before[t], as_numpy(q0[t][s]))
+            for t in (1, 3):
+                orc.step(t, as_numpy(now[t]))
+                compare_tensor(f"mixed step {s}", send, orc, t)
+            for t in range(len(descs)):
+                recv.codes[t].copy_(send.codes[t])
+                if recv.scales[t].numel():
+                    recv.scales[t].copy_(send.scales[t])
+            recv.decompress()
+            cf.cf_check_device(recv.ctx, recv.stream_handle)
+            for t in range(len(descs)):
+                assert torch.equal(recv.recon[t], send.recon[t]), f"receiver differs on tensor {t} at step {s}"
+    finally:
+        send.close()
+        recv.close()
+
+
+def test_lowrank_rejections():
+    for d, status in ((cf.desc(64, 100, cf.CF_BF16, 1, cf.CF_LOWRANK, R), cf.CF_ERR_SHAPE),       # C not a multiple of 32
+                      (cf.desc(64, 4096, cf.CF_BF16, 1, cf.CF_LOWRANK, R), cf.CF_ERR_SHAPE),      # C above 3072
+                      (cf.desc(64, 128, cf.CF_BF16, 1, cf.CF_LOWRANK, 8), cf.CF_ERR_UNSUPPORTED)):
+        with pytest.raises(cf.CFError) as ei:
+            cf.cf_sizes(d)
+        assert ei.value.status == status
+    good = cf.desc(64, 128, cf.CF_BF16, 1, cf.CF_LOWRANK, R)
+    assert cf.cf_sizes(good)[:2] == ((64 + 128) * R * 2, 128 * R * 4)
+    assert cf.cf_workspace_bytes([good], cf.options(ef=cf.CF_EF_OFF)) == 0     # only the default feedback mode
