@@ -42,7 +42,7 @@ def parse_args():
     ap.add_argument("--tile-rows", type=int, default=0)
     ap.add_argument("--encode-rows", type=int, default=0)
     ap.add_argument("--tensors", type=int, default=0, help="override the workload's tensor count (exploration only)")
-    ap.add_argument("--scale", default="", choices=("", "channel", "group", "rank1", "nm"), help="override the workload's scale kind (exploration only)")
+    ap.add_argument("--scale", default="", choices=("", "channel", "group", "rank1", "nm", "lowrank"), help="override the workload's scale kind (exploration only)")
     ap.add_argument("--bits", type=int, default=0, help="override the workload's code width (exploration only)")
     ap.add_argument("--sub-batch", type=int, default=0, help="issue the step as calls over ranges of this many tensors (exploration only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -105,12 +105,16 @@ def bytes_per_element(wl, bits: int, ef: int, err_bytes: int = 4) -> float:
 def code_bytes_per_element(wl, bits: int) -> float:
     if wl.scale == "nm":                                # a mask byte and `bits` values per block of 8
         return (1 + bits * (4 if wl.dtype == "f32" else 2)) / 8.0
+    if wl.scale == "lowrank":                           # U [N, 32] and V [C, 32] in the storage dtype
+        return (wl.n_tokens + wl.n_channels) * 32 * (4 if wl.dtype == "f32" else 2) / (wl.n_tokens * wl.n_channels)
     return bits / 8.0
 
 
 def scale_bytes_per_element(wl) -> float:
     if wl.scale == "nm":
         return 0.0
+    if wl.scale == "lowrank":                           # the start matrix Q0 [C, 32] fp32 is an input
+        return 32 * 4.0 / wl.n_tokens
     if wl.scale == "group":
         return 4.0 / wl.group
     if wl.scale == "rank1":                             # v[C] and u[N]
@@ -127,7 +131,7 @@ def apply_overrides(wl, args):
     if args.tensors:
         wl = wl.scaled(n_tensors=args.tensors)
     if args.scale:
-        wl = wl.scaled(scale=args.scale, group=8 if args.scale == "nm" else wl.group)
+        wl = wl.scaled(scale=args.scale, group={"nm": 8, "lowrank": 32}.get(args.scale, wl.group))
     if args.bits:
         wl = wl.scaled(bits=(args.bits,))
     return wl
@@ -144,7 +148,8 @@ def run_workload(name: str, args, events: HipEvents | None):
     wl = apply_overrides(wl, args)
     dev = "cuda:0"
     dt = cf.CF_F32 if wl.dtype == "f32" else cf.CF_BF16
-    scale = {"group": cf.CF_SCALE_GROUP, "rank1": cf.CF_SCALE_RANK1, "nm": cf.CF_SPARSE_NM}.get(wl.scale, cf.CF_SCALE_CHANNEL)
+    scale = {"group": cf.CF_SCALE_GROUP, "rank1": cf.CF_SCALE_RANK1, "nm": cf.CF_SPARSE_NM,
+             "lowrank": cf.CF_LOWRANK}.get(wl.scale, cf.CF_SCALE_CHANNEL)
     descs = [cf.desc(wl.n_tokens, wl.n_channels, dt, wl.bits_of(t), scale, wl.group) for t in range(wl.n_tensors)]
     opts = cf.options(ef=args.ef, flags=args.flags, tile_rows=args.tile_rows, encode_rows=args.encode_rows)
 
@@ -161,6 +166,11 @@ def run_workload(name: str, args, events: HipEvents | None):
               f"({wl.n_tensors} x [{wl.n_tokens},{wl.n_channels}] {wl.dtype}, bits {tuple(wl.bits)}, {wl.scale} scale)")
 
     sess = CodecSession(descs, opts, device=dev)
+    if wl.scale == "lowrank":                           # the start matrices the caller draws (Alg. 3, first line)
+        g = torch.Generator(device=dev)
+        g.manual_seed(wl.seed)
+        for q0 in sess.scales:
+            q0.copy_(torch.randn(q0.shape, generator=g, device=dev))
     p_ring = [cf.ptr_array(xs) for xs in ring]
     order = list(range(R)) + list(range(R - 2, 0, -1))      # 0 1 2 3 2 1 | 0 1 ...
 
@@ -207,12 +217,12 @@ def run_workload(name: str, args, events: HipEvents | None):
     # second, instrumented pass: HIP events around every kernel the library launches, on its stream
     if events is not None:
         n_prof = min(args.steps, 10)
-        sets = [events.create(16) for _ in range(n_prof)]
+        sets = [events.create(32) for _ in range(n_prof)]
         names = []
         for s in range(n_prof):
-            cf.cf_profile_next_call(sess.ctx, sets[s], 8)
+            cf.cf_profile_next_call(sess.ctx, sets[s], 16)
             step(k); k += 1
-            n_launch = min(cf.cf_profile_launch_count(sess.ctx), 8)
+            n_launch = min(cf.cf_profile_launch_count(sess.ctx), 16)
             names.append([cf.cf_profile_kernel_name(sess.ctx, i) for i in range(n_launch)])
         torch.cuda.synchronize()
         per_kernel = {}
@@ -247,6 +257,10 @@ def kernel_algorithmic_bytes(nm: str, wl, ef: int) -> float:
             per = 2 * sx + (4 if ef else 0)
         elif nm == "k_encode":          # reads x, recon (+err); writes codes, err, recon
             per = 3 * sx + 4 + code_bytes_per_element(wl, bits) + (4 if ef else 0) + scale_b
+        elif nm in ("k_lr_project", "k_lr_backproject"):     # re-form A from x and recon
+            per = 2 * sx
+        elif nm == "k_lr_apply":                            # reads x, recon and the factors; writes err, recon
+            per = 3 * sx + 4 + code_bytes_per_element(wl, bits)
         elif nm == "k_decode":
             per = 2 * sx + code_bytes_per_element(wl, bits) + scale_b
         else:                            # a kernel that does the whole step
@@ -329,7 +343,12 @@ def main():
         roofline = {"bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None if (args.scale or args.bits or args.tensors or args.ef or args.flags) else read_traffic(kname, head),
                     "algorithmic_bytes_per_launch": kb, "avg_launch_ms": kms}
-    cpu = None if args.no_cpu_baseline else cpu_baseline(wl, args.ef)
+    mfma = None
+    if wl.scale == "lowrank" and r.get("kernel_ms"):        # the dense contractions: 2 * 32 flops per element and launch
+        flops = 2.0 * 32 * wl.n_tensors * wl.n_tokens * wl.n_channels
+        mfma = {nm: {"tflops": flops / (ms * 1e-3) / 1e12, "peak_fp32_mfma": 157.3, "frac": flops / (ms * 1e-3) / 1e12 / 157.3}
+                for nm, ms in r["kernel_ms"].items() if nm in ("k_lr_project", "k_lr_backproject", "k_lr_apply")}
+    cpu = None if (args.no_cpu_baseline or wl.scale == "lowrank") else cpu_baseline(wl, args.ef)
     if events is not None:
         events.destroy()
 
@@ -346,6 +365,7 @@ def main():
         "bytes_per_element": r["bytes_per_element"],
         "kernel_ms": r.get("kernel_ms"),
         "roofline": roofline,
+        "mfma": mfma,
         "cpu_baseline": cpu,
     }
     if len(results) > 1:

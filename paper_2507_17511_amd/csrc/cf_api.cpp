@@ -307,6 +307,13 @@ struct cf_ctx {
         return iters;
     }
 
+    bool range_has_elementwise(int32_t first, int32_t count) const    // anything k_encode / k_decode handle
+    {
+        for (int32_t t = first; t < first + count; ++t)
+            if (descs[t].scale != CF_LOWRANK) return true;
+        return false;
+    }
+
     bool range_has_rank1(int32_t first, int32_t count) const
     {
         for (int32_t t = first; t < first + count; ++t)
@@ -493,8 +500,10 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
             if (e != hipSuccess) return device_fail(ctx, e);
         }
     }
-    e = launch(ctx, s, "k_encode", [&] { return launch_encode(v, r, ef, et, fused, s); });
-    if (e != hipSuccess) return device_fail(ctx, e);
+    if (ctx->range_has_elementwise(first, count)) {
+        e = launch(ctx, s, "k_encode", [&] { return launch_encode(v, r, ef, et, fused, s); });
+        if (e != hipSuccess) return device_fail(ctx, e);
+    }
     return run_lowrank_sender(ctx, first, count, v, r, fused, s);
 }
 
@@ -712,8 +721,11 @@ cf_status cf_decompress(cf_ctx *ctx, int32_t first, int32_t count, const void *c
     st = sync_ptrs(ctx, first, count, nullptr, recon, nullptr, const_cast<void *const *>(codes),
                    const_cast<void *const *>(scales), s);
     if (st != CF_OK) return st;
-    hipError_t e = launch(ctx, s, "k_decode", [&] { return launch_decode(ctx->view(), ctx->range(first, count), s); });
-    if (e != hipSuccess) return device_fail(ctx, e);
+    hipError_t e = hipSuccess;
+    if (ctx->range_has_elementwise(first, count)) {
+        e = launch(ctx, s, "k_decode", [&] { return launch_decode(ctx->view(), ctx->range(first, count), s); });
+        if (e != hipSuccess) return device_fail(ctx, e);
+    }
     if (ctx->range_lowrank_iters(first, count) >= 0) {
         e = launch(ctx, s, "k_lr_apply", [&] { return launch_lr_decode(ctx->view(), ctx->range(first, count), s); });
         if (e != hipSuccess) return device_fail(ctx, e);

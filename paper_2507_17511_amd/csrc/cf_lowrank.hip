@@ -70,37 +70,76 @@ __device__ __forceinline__ uint8_t *wire_v(const TensorDev &d, const TensorPtrs 
 
 // ---------------------------------------------------------------- P = A Q  (and U on the wire)
 
-// A wave owns 64 tokens (two accumulator tiles that share the Q operand), a workgroup 256.
+// A wave owns 64 tokens (two accumulator tiles that share the Q operand), a workgroup of two waves 128, and walks
+// the channels 64 at a time.  The MFMA wants a lane to hold one token's channels, memory wants
+// neighbouring lanes on neighbouring channels: the wave reads its [64 tokens][64 channels] of x and
+// recon row-major (8 lanes = 128 bytes of a bf16 row), leaves the residual in its own LDS patch and
+// picks it up again with lane (m, h) on token m (and m + 32), channels 16 * h ... of each 32-channel step.
 // Q is read in its per-lane order: step s (32 channels), lane l, 16 floats at ((s * 64 + l) * 16).
+constexpr int kProjThreads = 128;                           // two waves: their LDS patches stay under 64 KB at four workgroups per CU
+constexpr int kProjTokens = 128;
+constexpr int kProjChannels = 64;
+constexpr int kProjPitch = kProjChannels + 4;               // floats per token row of the patch
+
 template <int DT>
-__device__ __forceinline__ void lr_project_body(const BatchView &v, const TensorDev &d, const TensorPtrs &p, bool wire)
+__device__ __forceinline__ void lr_project_body(const BatchView &v, const TensorDev &d, const TensorPtrs &p, bool wire, float *patch)
 {
     const int lane = (int)threadIdx.x & 63, wave = (int)threadIdx.x >> 6;
     const int m = lane & 31, h = lane >> 5;
-    const int64_t row_base = (int64_t)blockIdx.x * 256 + wave * 64;
+    const int64_t row_base = (int64_t)blockIdx.x * kProjTokens + wave * 64;
     if (row_base >= d.n_tokens) return;                     // uniform over the wave
-    const int64_t r0 = row_base + m, r1 = r0 + 32;
-    const bool ok0 = r0 < d.n_tokens, ok1 = r1 < d.n_tokens;
     const int64_t C = d.n_channels;
     const CF_GLOBAL f32x4 *qs = gconst<f32x4>(v.workspace + d.lr_q_off);
     f32x16 acc0 = {}, acc1 = {};
     const int steps = d.n_channels / 32;
-    for (int s = 0; s < steps; ++s) {
-        const int64_t cb = (int64_t)s * 32 + 16 * h;
-        float z0[16], z1[16], q[16];
-        residual16<DT>(p, r0 * C + cb, ok0, z0);
-        residual16<DT>(p, r1 * C + cb, ok1, z1);
-        const CF_GLOBAL f32x4 *qp = qs + ((int64_t)s * 64 + lane) * 4;
+    const int chunk = lane & 7, trow = lane >> 3;           // row-major side: 8 chunks of 8 channels, 8 tokens per sweep
+    for (int s0 = 0; s0 < steps; s0 += 2) {
+        const int ch = s0 * 32 + chunk * 8;
+        Raw8<DT> xr[8], br[8];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const f32x4 w = qp[k];
-            q[4 * k] = w.x; q[4 * k + 1] = w.y; q[4 * k + 2] = w.z; q[4 * k + 3] = w.w;
+        for (int it = 0; it < 8; ++it) {
+            const int64_t tok = row_base + trow + 8 * it;
+            if (tok < d.n_tokens && ch < d.n_channels) {
+                xr[it].load(p.x, tok * C + ch);
+                br[it].load(p.recon, tok * C + ch);
+            } else {
+                xr[it].zero();
+                br[it].zero();
+            }
         }
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            acc0 = mfma32(z0[j], q[j], acc0);
-            acc1 = mfma32(z1[j], q[j], acc1);
+        for (int it = 0; it < 8; ++it) {
+            const F8 x = xr[it].widen(), b = br[it].widen();
+            f32x4 lo, hi;
+            lo.x = x.v[0] - b.v[0]; lo.y = x.v[1] - b.v[1]; lo.z = x.v[2] - b.v[2]; lo.w = x.v[3] - b.v[3];
+            hi.x = x.v[4] - b.v[4]; hi.y = x.v[5] - b.v[5]; hi.z = x.v[6] - b.v[6]; hi.w = x.v[7] - b.v[7];
+            f32x4 *dst = reinterpret_cast<f32x4 *>(patch + (trow + 8 * it) * kProjPitch + chunk * 8);
+            dst[0] = lo;
+            dst[1] = hi;
         }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (s0 + u < steps) {                           // uniform over the wave
+                float z0[16], z1[16], q[16];
+                const f32x4 *a0 = reinterpret_cast<const f32x4 *>(patch + m * kProjPitch + 32 * u + 16 * h);
+                const f32x4 *a1 = reinterpret_cast<const f32x4 *>(patch + (m + 32) * kProjPitch + 32 * u + 16 * h);
+                const CF_GLOBAL f32x4 *qp = qs + ((int64_t)(s0 + u) * 64 + lane) * 4;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const f32x4 w0 = a0[k], w1 = a1[k], wq = qp[k];
+                    z0[4 * k] = w0.x; z0[4 * k + 1] = w0.y; z0[4 * k + 2] = w0.z; z0[4 * k + 3] = w0.w;
+                    z1[4 * k] = w1.x; z1[4 * k + 1] = w1.y; z1[4 * k + 2] = w1.z; z1[4 * k + 3] = w1.w;
+                    q[4 * k] = wq.x; q[4 * k + 1] = wq.y; q[4 * k + 2] = wq.z; q[4 * k + 3] = wq.w;
+                }
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    acc0 = mfma32(z0[j], q[j], acc0);
+                    acc1 = mfma32(z1[j], q[j], acc1);
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
     }
     // accumulator register i of lane (m, h): row 8 * (i / 4) + 4 * h + i % 4 of the tile, column m
     CF_GLOBAL float *P = gmut<float>(v.workspace + d.lr_p_off);
@@ -124,14 +163,16 @@ __device__ __forceinline__ void lr_project_body(const BatchView &v, const Tensor
 }
 
 // min_iters: tensors that asked for fewer subspace iterations than this sit the launch out.
-__global__ __launch_bounds__(256) void k_lr_project(BatchView v, LaunchRange r, int wire, int min_iters)
+__global__ __launch_bounds__(kProjThreads, 2) void k_lr_project(BatchView v, LaunchRange r, int wire, int min_iters)
 {
+    __shared__ __attribute__((aligned(16))) float patches[kProjThreads / 64][64 * kProjPitch];
     const int t = r.first + (int)blockIdx.y;
     const TensorDev d = v.descs[t];
     if (d.scale != LOWRANK || d.bits < min_iters) return;
     const TensorPtrs p = v.ptrs[t];
-    if (d.dtype == BF16) lr_project_body<BF16>(v, d, p, wire != 0);
-    else lr_project_body<F32>(v, d, p, wire != 0);
+    float *patch = patches[(int)threadIdx.x >> 6];
+    if (d.dtype == BF16) lr_project_body<BF16>(v, d, p, wire != 0, patch);
+    else lr_project_body<F32>(v, d, p, wire != 0, patch);
 }
 
 // ---------------------------------------------------------------- Z = A^T P
@@ -337,83 +378,100 @@ __global__ __launch_bounds__(kOrthThreads) void k_lr_orth(BatchView v, LaunchRan
 // 16 consecutive rank entries (16 * h ...) of one row of a factor on the wire, widened.
 template <int DT> __device__ __forceinline__ void factor16(const uint8_t *base, int64_t row, int h, bool valid, float (&out)[16])
 {
-    if (valid) {
-        load16<DT>(base, row * kRank + 16 * h, out);
-    } else {
+    load16<DT>(base, (valid ? row : 0) * kRank + 16 * h, out);      // row 0 always exists; its values are discarded
 #pragma unroll
-        for (int k = 0; k < 16; ++k) out[k] = 0.0f;
-    }
+    for (int k = 0; k < 16; ++k) out[k] = valid ? out[k] : 0.0f;
 }
 
-// A wave owns 32 tokens and walks the channels in tiles of 32.  MFMA rows are channels, relabelled
-// rho -> 16 * ((rho / 4) % 2) + 4 * (rho / 8) + rho % 4 so that the 16 accumulator registers of lane
-// (token, h) are the 16 consecutive channels 16 * h ... of the tile.
-// SENDER: also forms A again and writes e = A - D.  UPDATE: writes recon + D (or D alone when `replace`).
+// A wave owns 32 tokens and walks the channels in tiles of 64.  The MFMA leaves lane (n, h) with
+// channel n of 16 tokens, which is the wrong way round for row-major memory, so the tile of D goes
+// through the wave's own LDS patch [32 tokens][64 channels] and comes back as 8 consecutive channels
+// of one token per lane: 8 lanes then cover 128 bytes of a bf16 row (256 of the fp32 error row).
+// SENDER: also forms A again and writes e = A - D.  UPDATE: writes recon + D.
+constexpr int kApplyChannels = 64;
+constexpr int kApplyPitch = kApplyChannels + 4;             // floats per token row of the patch
+
 template <int DT, int ET, bool SENDER, bool UPDATE>
-__device__ __forceinline__ void lr_apply_body(const TensorDev &d, const TensorPtrs &p)
+__device__ __forceinline__ void lr_apply_body(const TensorDev &d, const TensorPtrs &p, float *patch)
 {
     const int lane = (int)threadIdx.x & 63, wave = (int)threadIdx.x >> 6;
     const int n = lane & 31, h = lane >> 5;
     const int64_t tok_base = (int64_t)blockIdx.x * 128 + wave * 32;
     if (tok_base >= d.n_tokens) return;                     // uniform over the wave
-    const int64_t tok = tok_base + n;
-    const bool tvalid = tok < d.n_tokens;
     const int64_t C = d.n_channels;
     float u[16];
-    factor16<DT>(wire_u(p), tok, h, tvalid, u);
-    const int rho = lane & 31;
-    const int pi = 16 * ((rho >> 2) & 1) + 4 * (rho >> 3) + (rho & 3);
+    factor16<DT>(wire_u(p), tok_base + n, h, tok_base + n < d.n_tokens, u);
     const uint8_t *V = wire_v(d, p);
-    const int tiles = d.n_channels / 32;
-    for (int tile = 0; tile < tiles; ++tile) {
-        float vv[16];
-        factor16<DT>(V, (int64_t)tile * 32 + pi, h, true, vv);
-        f32x16 acc = {};
+    const int n_sub = d.n_channels / 32;
+    const int chunk = lane & 7, trow = lane >> 3;           // row-major side: 8 chunks of 8 channels, 8 tokens per sweep
+    for (int sub0 = 0; sub0 < n_sub; sub0 += 2) {
+        const int cnt = n_sub - sub0 < 2 ? 1 : 2;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) acc = mfma32(vv[j], u[j], acc);
-        if (!tvalid) continue;
-        const int64_t e0 = tok * C + (int64_t)tile * 32 + 16 * h;
-        float b[16];
-        load16<DT>(p.recon, e0, b);
-        if (SENDER) {
-            float x[16];
-            load16<DT>(p.x, e0, x);
+        for (int c = 0; c < 2; ++c) {
+            if (c < cnt) {                                  // uniform over the wave
+                float vv[16];
+                factor16<DT>(V, (int64_t)(sub0 + c) * 32 + n, h, true, vv);
+                f32x16 acc = {};
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                F8 lost;
+                for (int j = 0; j < 16; ++j) acc = mfma32(u[j], vv[j], acc);
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const float z = x[8 * half + k] - b[8 * half + k];
-                    lost.v[k] = z - acc[8 * half + k];
+                for (int i = 0; i < 16; ++i) patch[(8 * (i >> 2) + 4 * h + (i & 3)) * kApplyPitch + c * 32 + n] = acc[i];
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int tl = trow + 8 * it;
+            const int64_t tok = tok_base + tl;
+            if (tok < d.n_tokens && chunk * 8 < cnt * 32) {
+                const f32x4 *src = reinterpret_cast<const f32x4 *>(patch + tl * kApplyPitch + chunk * 8);
+                const f32x4 d0 = src[0], d1 = src[1];
+                F8 D;
+                D.v[0] = d0.x; D.v[1] = d0.y; D.v[2] = d0.z; D.v[3] = d0.w;
+                D.v[4] = d1.x; D.v[5] = d1.y; D.v[6] = d1.z; D.v[7] = d1.w;
+                const int64_t e0 = tok * C + (int64_t)sub0 * 32 + chunk * 8;
+                Raw8<DT> br;
+                br.load(p.recon, e0);
+                const F8 b = br.widen();
+                if (SENDER) {
+                    Raw8<DT> xr;
+                    xr.load(p.x, e0);
+                    const F8 x = xr.widen();
+                    F8 lost;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const float z = x.v[k] - b.v[k];
+                        lost.v[k] = z - D.v[k];
+                    }
+                    Raw8<ET> eo;
+                    eo.narrow(lost);
+                    eo.store(p.err, e0);
                 }
-                Raw8<ET> eo;
-                eo.narrow(lost);
-                eo.store(p.err, e0 + 8 * half);
+                if (UPDATE) {
+                    F8 nb;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) nb.v[k] = b.v[k] + D.v[k];
+                    Raw8<DT> out;
+                    out.narrow(nb);
+                    out.store(p.recon, e0);
+                }
             }
         }
-        if (UPDATE) {
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                F8 nb;
-#pragma unroll
-                for (int k = 0; k < 8; ++k) nb.v[k] = b[8 * half + k] + acc[8 * half + k];
-                Raw8<DT> out;
-                out.narrow(nb);
-                out.store(p.recon, e0 + 8 * half);
-            }
-        }
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
 template <int ET, bool SENDER, bool UPDATE>
 __global__ __launch_bounds__(256) void k_lr_apply(BatchView v, LaunchRange r)
 {
+    __shared__ __attribute__((aligned(16))) float patches[4][32 * kApplyPitch];
     const int t = r.first + (int)blockIdx.y;
     const TensorDev d = v.descs[t];
     if (d.scale != LOWRANK) return;
     const TensorPtrs p = v.ptrs[t];
-    if (d.dtype == BF16) lr_apply_body<BF16, ET, SENDER, UPDATE>(d, p);
-    else lr_apply_body<F32, ET, SENDER, UPDATE>(d, p);
+    float *patch = patches[(int)threadIdx.x >> 6];
+    if (d.dtype == BF16) lr_apply_body<BF16, ET, SENDER, UPDATE>(d, p, patch);
+    else lr_apply_body<F32, ET, SENDER, UPDATE>(d, p, patch);
 }
 
 }  // namespace
@@ -428,8 +486,8 @@ hipError_t launch_lr_orth(const BatchView &v, const LaunchRange &r, bool from_q0
 hipError_t launch_lr_project(const BatchView &v, const LaunchRange &r, bool wire, int min_iters, hipStream_t s)
 {
     if (r.count == 0 || r.lr_max_tokens == 0) return hipSuccess;
-    dim3 grid((unsigned)((r.lr_max_tokens + 255) / 256), (unsigned)r.count);
-    hipLaunchKernelGGL(k_lr_project, grid, dim3(256), 0, s, v, r, wire ? 1 : 0, min_iters);
+    dim3 grid((unsigned)((r.lr_max_tokens + kProjTokens - 1) / kProjTokens), (unsigned)r.count);
+    hipLaunchKernelGGL(k_lr_project, grid, dim3(kProjThreads), 0, s, v, r, wire ? 1 : 0, min_iters);
     return hipGetLastError();
 }
 
