@@ -137,13 +137,21 @@ typedef struct {
                             library, else 1..64 (a tuning knob as well) */
 } cf_options;
 
-/* Channel scales are normally reduced by one kernel and the codes written by
- * a second one, which reads x and recon again.  With this flag (CF_EF_RECON
- * only) a single persistent kernel keeps them in registers across the
- * reduction instead: half the reads, but workgroups wait for each other.
- * Results are bit-identical either way; the two-kernel path is the faster one
- * on MI355X as measured so far. */
+/* A channel scale needs every token of a channel before any code of that
+ * channel.  With CF_EF_RECON a single persistent kernel keeps x and recon in
+ * registers across that reduction (each is read once; workgroups of one
+ * 256-channel stripe wait for each other's partial sums, every wait bounded:
+ * see cf_check_device).  It applies to CF_EF_RECON, CF_SCALE_CHANNEL tensors, no
+ * CF_SCALE_RANK1 tensor in the context, N / 128 workgroups co-resident under a
+ * cooperative launch.  Otherwise one kernel reduces and a second one, which
+ * reads x and recon again, writes the codes.  Results are bit-identical either
+ * way.  By default a call takes the single pass where it applies and the call
+ * covers at least 64 work items of 128 rows x 256 channels (it is about 7 %
+ * faster on MI355X at the sizes of the paper's models and slower on tiny
+ * batches); CF_FLAG_SINGLE_PASS takes it whenever it applies, CF_FLAG_TWO_KERNEL
+ * never. */
 #define CF_FLAG_SINGLE_PASS 0x1u
+#define CF_FLAG_TWO_KERNEL 0x2u
 
 /* Byte sizes of one tensor's buffers.  Any output pointer may be NULL.
  * CF_ERR_SHAPE / CF_ERR_UNSUPPORTED as for cf_init. */

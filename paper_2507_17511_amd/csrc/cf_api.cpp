@@ -41,7 +41,7 @@ cf_status check_opts(const cf_options *o, cf_options &out)
     if (!o) return CF_OK;
     if (o->ef != CF_EF_RECON && o->ef != CF_EF_LITERAL && o->ef != CF_EF_OFF && o->ef != CF_EF_NAIVE) return CF_ERR_UNSUPPORTED;
     if (o->err_dtype != CF_F32 && o->err_dtype != CF_BF16) return CF_ERR_UNSUPPORTED;
-    if (o->flags & ~CF_FLAG_SINGLE_PASS) return CF_ERR_UNSUPPORTED;
+    if (o->flags & ~(CF_FLAG_SINGLE_PASS | CF_FLAG_TWO_KERNEL)) return CF_ERR_UNSUPPORTED;
     if (o->tile_rows != 0 && o->tile_rows != 8 && o->tile_rows != 16 && o->tile_rows != 32 && o->tile_rows != 64)
         return CF_ERR_UNSUPPORTED;
     if (o->encode_rows < 0 || o->encode_rows > 64) return CF_ERR_UNSUPPORTED;
@@ -116,7 +116,7 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     size_t partial_bytes = 0, p_partial_bytes = 0;
     L.item_prefix.assign(n + 1, 0);
     L.group_prefix.assign(n + 1, 0);
-    L.single_pass = o.ef == CF_EF_RECON && (o.flags & CF_FLAG_SINGLE_PASS) != 0;
+    L.single_pass = o.ef == CF_EF_RECON && (o.flags & CF_FLAG_TWO_KERNEL) == 0;
     for (int32_t t = 0; t < n; ++t)
         if (descs[t].scale == CF_SCALE_RANK1) L.single_pass = false;   // the single-pass kernel knows channel scales only
     for (int32_t t = 0; t < n; ++t) {
@@ -275,6 +275,16 @@ struct cf_ctx {
         r.dts = descs[first].dtype;
         r.lr_max_channels = 0;
         r.lr_max_tokens = 0;
+        r.p_partial_lo = ~(uint64_t)0;
+        r.p_partial_hi = 0;
+        for (int32_t t = first; t < first + count; ++t) {
+            const TensorDev &dv = L.dev[t];
+            if (dv.p_rows == 0) continue;
+            const uint64_t bytes = align_up((size_t)dv.p_n_rb * (size_t)dv.n_channels * sizeof(float));
+            if (dv.p_partial_off < r.p_partial_lo) r.p_partial_lo = dv.p_partial_off;
+            if (dv.p_partial_off + bytes > r.p_partial_hi) r.p_partial_hi = dv.p_partial_off + bytes;
+        }
+        if (r.p_partial_hi == 0) r.p_partial_lo = 0;
         for (int32_t t = first; t < first + count; ++t) {
             if (descs[t].dtype != descs[first].dtype) r.dts = 2;
             if (descs[t].scale == CF_LOWRANK) {
@@ -477,9 +487,10 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
     const int ef = ctx->opts.ef, et = ctx->opts.err_dtype;
     hipError_t e;
     const int grid = ctx->persist_grid[et == CF_BF16 ? 1 : 0][fused ? 1 : 0];
-    if (ctx->L.single_pass && grid >= ctx->L.max_group_items && r.item_hi > r.item_lo) {
+    const uint32_t min_items = (ctx->opts.flags & CF_FLAG_SINGLE_PASS) ? 1u : 64u;      // tiny batches: the wait chain costs more than a second read
+    if (ctx->L.single_pass && grid >= ctx->L.max_group_items && r.item_hi - r.item_lo >= min_items) {
         // channel-scale tensors: one pass, x and recon stay in registers across the scale reduction
-        e = launch(ctx, s, "k_zero_counters", [&] { return launch_zero_counters(v, r, s); });
+        e = launch(ctx, s, "k_reset_partials", [&] { return launch_reset_partials(v, r, s); });
         if (e != hipSuccess) return device_fail(ctx, e);
         e = launch(ctx, s, "k_persistent", [&] { return launch_persistent(v, r, et, fused, grid, s); });
         if (e != hipSuccess) return device_fail(ctx, e);

@@ -52,6 +52,7 @@ template <> struct Raw8<BF16> {
     __device__ __forceinline__ void load(const void *base, int64_t elem) { w = *gconst<u32x4>(static_cast<const uint16_t *>(base) + elem); }
     __device__ __forceinline__ void load_stream(const void *base, int64_t elem) { w = __builtin_nontemporal_load(gconst<u32x4>(static_cast<const uint16_t *>(base) + elem)); }
     __device__ __forceinline__ void store(void *base, int64_t elem) const { *gmut<u32x4>(static_cast<uint16_t *>(base) + elem) = w; }
+    __device__ __forceinline__ void store_stream(void *base, int64_t elem) const { __builtin_nontemporal_store(w, gmut<u32x4>(static_cast<uint16_t *>(base) + elem)); }
     // Uniform base pointer plus a 32-bit per-lane byte offset: the scalar-base form of the global
     // instructions, which needs no 64-bit address arithmetic in vector registers.
     __device__ __forceinline__ void load_at(const void *ubase, uint32_t off) { w = *gconst<u32x4>(static_cast<const char *>(ubase) + off); }
@@ -95,6 +96,12 @@ template <> struct Raw8<F32> {
         CF_GLOBAL f32x4 *p = gmut<f32x4>(static_cast<float *>(base) + elem);
         p[0] = a;
         p[1] = b;
+    }
+    __device__ __forceinline__ void store_stream(void *base, int64_t elem) const
+    {
+        CF_GLOBAL f32x4 *p = gmut<f32x4>(static_cast<float *>(base) + elem);
+        __builtin_nontemporal_store(a, p);
+        __builtin_nontemporal_store(b, p + 1);
     }
     __device__ __forceinline__ void load_at(const void *ubase, uint32_t off)
     {

@@ -91,6 +91,7 @@ struct LaunchRange {
     uint32_t fin_lo, fin_hi;    // finalise blocks
     uint32_t item_lo, item_hi;  // single-pass items
     uint32_t group_lo, group_hi;
+    uint64_t p_partial_lo, p_partial_hi;    // workspace bytes holding the single-pass partials of the range
     int32_t dts;                // storage dtype of every tensor in the range (cf_dtype), or 2 if mixed
     int32_t only_group_scale;   // tiled encode: skip tensors the single-pass kernel covers
     int32_t naive;              // decode: recon_t = D instead of recon_{t-1} + D (CF_EF_NAIVE)
@@ -121,6 +122,6 @@ hipError_t launch_lr_decode(const BatchView &v, const LaunchRange &r, hipStream_
 // Single-pass kernel (channel scales, CF_EF_RECON).  `grid` workgroups must be co-resident.
 int persistent_max_blocks_per_cu(int err_dtype, bool fused);
 hipError_t launch_persistent(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, int grid, hipStream_t s);
-hipError_t launch_zero_counters(const BatchView &v, const LaunchRange &r, hipStream_t s);
+hipError_t launch_reset_partials(const BatchView &v, const LaunchRange &r, hipStream_t s);
 
 }  // namespace cf

@@ -33,6 +33,48 @@ using namespace dev;
 __device__ __forceinline__ void publish(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ float fetch(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
+// A partial that has not been published yet reads as this pattern: a negative NaN with every
+// mantissa bit set, which neither a sum of magnitudes nor a maximum of magnitudes can produce.
+constexpr uint32_t kUnpublished = 0xFFFFFFFFu;
+
+// tree_over whose leaves are other workgroups' partials: a leaf that still reads as kUnpublished is
+// fetched again (bounded) until its owner has stored it.  The data word is its own ready flag, so
+// a group needs no counter and no second round trip.
+template <bool IS_MAX, int LV>
+__device__ __forceinline__ float tree_over_published(int n, const float *mine, int64_t stride, bool &ok)
+{
+    constexpr int NB = 8;                           // leaves fetched (and re-fetched) together
+    float stack[LV];
+#pragma unroll
+    for (int l = 0; l < LV; ++l) stack[l] = 0.0f;
+    const int nbatch = (n + NB - 1) / NB;
+    int bpad = 1;
+    while (bpad < nbatch) bpad <<= 1;
+    for (int b = 0; b < bpad; ++b) {
+        float vals[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) vals[u] = (b * NB + u < n) ? fetch(mine + (int64_t)(b * NB + u) * stride) : 0.0f;
+        uint32_t spins = 0;
+        for (;;) {
+            uint32_t pending = 0;
+#pragma unroll
+            for (int u = 0; u < NB; ++u) pending |= (__float_as_uint(vals[u]) == kUnpublished ? 1u : 0u) << u;
+            if (pending == 0) break;
+            if (spins >= kSpinLimit) { ok = false; break; }
+            __builtin_amdgcn_s_sleep(1);
+#pragma unroll
+            for (int u = 0; u < NB; ++u)
+                if ((pending >> u) & 1u) vals[u] = fetch(mine + (int64_t)(b * NB + u) * stride);
+            ++spins;
+        }
+        float p2[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) p2[u] = comb<IS_MAX>(vals[2 * u], vals[2 * u + 1]);
+        tree_push<LV, IS_MAX>(stack, comb<IS_MAX>(comb<IS_MAX>(p2[0], p2[1]), comb<IS_MAX>(p2[2], p2[3])), b);
+    }
+    return tree_top<LV, IS_MAX>(stack);
+}
+
 struct alignas(16) Shared {
     float red[kRowLanes][kStripeChannels];
     float scale[kStripeChannels];
@@ -58,8 +100,8 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
         const int64_t row = row0 + k;
         if (cvalid && row < d.n_tokens) {
             const int64_t e = row * C + (int64_t)chunk * kChunk;
-            xr[k].load(p.x, e);
-            br[k].load(p.recon, e);
+            xr[k].load_stream(p.x, e);       // read once: keep the caches for the partials and the outputs
+            br[k].load_stream(p.recon, e);
         } else {                                    // zero padding of the tree / masked lanes
             xr[k].zero();
             br[k].zero();
@@ -101,6 +143,7 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
         dst[0] = lo;
         dst[1] = hi;
     }
+    if (tid == 0) sh.ok = 1u;
     __syncthreads();
 
     // ---- level 2: tree over the 8 row-lanes (consecutive RPT-row blocks); one lane per channel
@@ -112,37 +155,23 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
         float item = comb<IS_MAX>(comb<IS_MAX>(s01, s23), comb<IS_MAX>(s45, s67));
         if (col < C) publish(partial + (int64_t)rb * C + col, item);
     }
-    // The partials were stored with agent-scope atomic stores (written through to where the other
-    // XCDs read them), and the barrier below drains them; so the arrival needs no cache write-back,
-    // which would also flush every output line this CU's L2 still holds.
-    __builtin_amdgcn_s_waitcnt(0);                  // this lane's stores have completed
-    __syncthreads();
+    // The partials are agent-scope atomic stores (written through to where the other XCDs read them)
+    // and every partial is its own ready flag: nothing to drain, no arrival to count.
 
-    // ---- arrive, then wait (bounded) for the rest of the group
-    if (tid == 0) {
-        const uint32_t need = (uint32_t)d.p_n_rb;
-        uint32_t seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
-        uint32_t spins = 0;
-        while (seen < need && spins < kSpinLimit) {
-            __builtin_amdgcn_s_sleep(2);
-            seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            ++spins;
-        }
-        sh.ok = seen >= need ? 1u : 0u;
-        if (seen < need) __hip_atomic_store(v.error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();
-    if (!sh.ok) return false;
-
-    // ---- level 3: the same tree continued over the group's item partials, then the scale
+    // ---- level 3: the same tree continued over the group's item partials as they appear, then the scale
     if (col < C) {
-        const float *mine = partial + col;
-        const float res = tree_over<IS_MAX, 9>(d.p_n_rb, [&](int i) { return fetch(mine + (int64_t)i * C); });
+        bool ok = true;
+        const float res = tree_over_published<IS_MAX, 10>(d.p_n_rb, partial + col, C, ok);
         const float s = IS_MAX ? res / 7.0f : res / (float)d.n_tokens;
         sh.scale[tid] = s;
         if (rb == 0) gmut<float>(p.scales)[col] = s;
+        if (!ok) {                                  // a bounded wait expired: flag it and leave
+            sh.ok = 0u;
+            __hip_atomic_store(v.error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     __syncthreads();
+    if (!sh.ok) return false;
 
     // ---- a4-a8 from the registers.  z is formed again from the raw operands: keeping the first
     // phase's fp32 residuals alive across the wait would double the register footprint.
@@ -222,10 +251,12 @@ __global__ __launch_bounds__(kPersistThreads, 2) void k_persistent(BatchView v, 
     }
 }
 
-// Group counters start every call at zero (a fill kernel, so the call can be captured in a graph).
-__global__ void k_zero_counters(uint32_t *counters, uint32_t lo, uint32_t hi)
+// Every partial starts a call as "unpublished" (a fill kernel, so the call can be captured in a graph).
+__global__ void k_reset_partials(u32x4 *words, uint64_t n_vec)
 {
-    for (uint32_t i = lo + blockIdx.x * blockDim.x + threadIdx.x; i < hi; i += gridDim.x * blockDim.x) counters[i] = 0u;
+    const u32x4 fill = (u32x4)(kUnpublished);
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += (uint64_t)gridDim.x * blockDim.x)
+        *gmut<u32x4>(words + i) = fill;
 }
 
 template <int ET, bool FUSED> const void *persistent_fn() { return reinterpret_cast<const void *>(&k_persistent<ET, FUSED>); }
@@ -246,12 +277,13 @@ int persistent_max_blocks_per_cu(int err_dtype, bool fused)
     return n;
 }
 
-hipError_t launch_zero_counters(const BatchView &v, const LaunchRange &r, hipStream_t s)
+hipError_t launch_reset_partials(const BatchView &v, const LaunchRange &r, hipStream_t s)
 {
-    if (r.group_hi == r.group_lo) return hipSuccess;
-    uint32_t n = r.group_hi - r.group_lo;
-    hipLaunchKernelGGL(k_zero_counters, dim3((n + 255) / 256 < 64 ? (n + 255) / 256 : 64), dim3(256), 0, s,
-                       v.group_counters, r.group_lo, r.group_hi);
+    if (r.p_partial_hi <= r.p_partial_lo) return hipSuccess;
+    const uint64_t n_vec = (r.p_partial_hi - r.p_partial_lo) / 16;      // offsets are multiples of 256
+    const uint64_t want = (n_vec + 255) / 256;
+    hipLaunchKernelGGL(k_reset_partials, dim3((unsigned)(want < 2048 ? want : 2048)), dim3(256), 0, s,
+                       reinterpret_cast<u32x4 *>(v.workspace + r.p_partial_lo), n_vec);
     return hipGetLastError();
 }
 

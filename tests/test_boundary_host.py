@@ -50,8 +50,9 @@ def test_sizes_follow_the_layouts():
     d = cf.desc(4096, 3072, cf.CF_BF16, 2, cf.CF_SCALE_RANK1)          # v[C] then u[N]
     assert cf.cf_sizes(d)[1] == (3072 + 4096) * 4
     # the workspace of a rank-1 tensor also holds one partial row sum per token and column tile
-    ch = cf.cf_workspace_bytes([cf.desc(4096, 3072, cf.CF_BF16, 2, cf.CF_SCALE_CHANNEL)])
-    assert cf.cf_workspace_bytes([d]) >= ch + 4096 * 3 * 4
+    two = cf.options(flags=cf.CF_FLAG_TWO_KERNEL)
+    ch = cf.cf_workspace_bytes([cf.desc(4096, 3072, cf.CF_BF16, 2, cf.CF_SCALE_CHANNEL)], two)
+    assert cf.cf_workspace_bytes([d], two) >= ch + 4096 * 3 * 4
 
 
 BAD = [

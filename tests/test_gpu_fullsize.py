@@ -95,6 +95,7 @@ def test_cfg5_batched_mixed_full():
     run_full("cfg5_batched_mixed", sampled=(0, 28, 56))        # bits 1, 2, 4
 
 
-def test_cfg5_single_pass_kernel_full():
-    """The opt-in single-pass kernel at full size (its reduction groups span 32 workgroups)."""
-    run_full("cfg5_batched_mixed", sampled=(3, 31, 53), follow_steps=4, flags=cf.CF_FLAG_SINGLE_PASS)
+def test_cfg5_two_kernel_path_full():
+    """The two-kernel path at full size (the default runs the single-pass kernel, whose reduction groups
+    span 32 workgroups here)."""
+    run_full("cfg5_batched_mixed", sampled=(3, 31, 53), follow_steps=4, flags=cf.CF_FLAG_TWO_KERNEL)

@@ -33,11 +33,11 @@ COMBOS = [(1, CH), (2, CH), (4, CH), (4, GR)]
 @pytest.mark.parametrize("bits,scale", COMBOS)
 @pytest.mark.parametrize("dtype", [cf.CF_BF16, cf.CF_F32])
 @pytest.mark.parametrize("mode", ["fused", "split"])
-@pytest.mark.parametrize("flags", [0, cf.CF_FLAG_SINGLE_PASS])
+@pytest.mark.parametrize("flags", [cf.CF_FLAG_SINGLE_PASS, cf.CF_FLAG_TWO_KERNEL])
 def test_parity_shapes(bits, scale, dtype, mode, flags):
-    """flags: the two-kernel path (default) and the single-pass kernel must both match the oracle."""
-    if scale == GR and flags:
-        pytest.skip("group scales never use the single-pass kernel")
+    """flags: the single-pass kernel (default where it applies) and the two-kernel path must both match the oracle."""
+    if scale == GR and flags == cf.CF_FLAG_TWO_KERNEL:
+        pytest.skip("group scales take the same path either way")
     for k, (n, c) in enumerate(SHAPES):
         if scale == GR and c % 128:
             continue
@@ -97,7 +97,7 @@ def _mixed_batch():
 
 
 @pytest.mark.parametrize("mode", ["fused", "split"])
-@pytest.mark.parametrize("flags", [0, cf.CF_FLAG_SINGLE_PASS])
+@pytest.mark.parametrize("flags", [cf.CF_FLAG_SINGLE_PASS, cf.CF_FLAG_TWO_KERNEL])
 def test_parity_batched_mixed_launch(mode, flags):
     """One call covers tensors of different shapes, dtypes, widths and scale kinds."""
     say(f"mixed batch mode={mode} flags={flags}")
@@ -115,6 +115,7 @@ def test_single_pass_many_row_blocks_and_stripes():
                for k, d in enumerate(descs)]
     xs = [[streams[t][s] for t in range(len(descs))] for s in range(3)]
     run_parity(descs, cf.options(flags=cf.CF_FLAG_SINGLE_PASS), xs, mode="fused")
+    run_parity(descs, cf.options(flags=cf.CF_FLAG_TWO_KERNEL), xs, mode="fused")
     run_parity(descs, cf.options(), xs, mode="fused")
 
 
@@ -333,7 +334,7 @@ def test_configs_reduced(name, shrink):
     xs = [[x.clone() for x in stream.current]]
     for _ in range(1, wl.steps):
         xs.append([x.clone() for x in stream.advance()])
-    for flags in (0, cf.CF_FLAG_SINGLE_PASS):
+    for flags in (0, cf.CF_FLAG_SINGLE_PASS, cf.CF_FLAG_TWO_KERNEL):
         run_parity(descs, cf.options(flags=flags), xs, mode="fused", tag=f"{name} flags={flags}")
 
 
@@ -391,7 +392,7 @@ def test_parity_rank1_zero_residual_and_mixed_batch():
     descs = [cf.desc(203, 1096, cf.CF_BF16, 2, R1), cf.desc(64, 256, cf.CF_F32, 4, GR), cf.desc(67, 3072, cf.CF_BF16, 1, CH),
              cf.desc(1500, 136, cf.CF_F32, 1, R1), cf.desc(9, 8, cf.CF_BF16, 2, R1)]
     streams = [token_outlier_stream((int(d.n_tokens), int(d.n_channels)), int(d.dtype), 4, 40 + t) for t, d in enumerate(descs)]
-    for flags in (0, cf.CF_FLAG_SINGLE_PASS):
+    for flags in (0, cf.CF_FLAG_SINGLE_PASS, cf.CF_FLAG_TWO_KERNEL):
         say(f"rank1 mixed batch flags={flags}")
         run_parity(descs, cf.options(flags=flags), [[s[k] for s in streams] for k in range(4)], tag="rank1 mixed")
 
@@ -502,7 +503,7 @@ def test_parity_nm_in_a_mixed_batch():
     descs = [cf.desc(203, 1096, cf.CF_BF16, 2, NMK, 8), cf.desc(64, 256, cf.CF_F32, 4, GR), cf.desc(300, 1024, cf.CF_BF16, 1, CH),
              cf.desc(67, 3072, cf.CF_F32, 1, NMK, 8), cf.desc(9, 8, cf.CF_BF16, 4, NMK, 8), cf.desc(130, 264, cf.CF_BF16, 2, CH)]
     streams = [drift_stream((int(d.n_tokens), int(d.n_channels)), int(d.dtype), 4, 60 + t, device=DEV) for t, d in enumerate(descs)]
-    for flags in (0, cf.CF_FLAG_SINGLE_PASS):
+    for flags in (0, cf.CF_FLAG_SINGLE_PASS, cf.CF_FLAG_TWO_KERNEL):
         for mode in ("fused", "split"):
             say(f"nm mixed batch flags={flags} mode={mode}")
             run_parity(descs, cf.options(flags=flags), [[s[k] for s in streams] for k in range(4)], mode=mode, tag="nm mixed")
