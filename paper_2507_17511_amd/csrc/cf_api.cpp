@@ -231,7 +231,7 @@ struct cf_ctx {
     std::vector<uint8_t> warm;
     int32_t last_hip = 0;
     int device = 0;
-    int persist_grid[2][2] = {{0, 0}, {0, 0}};   // co-resident workgroups of k_persistent<err dtype, fused>
+    int persist_grid[2][2] = {{0, 0}, {0, 0}};   // co-resident workgroups of k_single_pass<err dtype, fused>
 
     // benchmark instrumentation (cf_profile_next_call)
     std::vector<hipEvent_t> prof_events;
@@ -492,7 +492,8 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
         // channel-scale tensors: one pass, x and recon stay in registers across the scale reduction
         e = launch(ctx, s, "k_reset_partials", [&] { return launch_reset_partials(v, r, s); });
         if (e != hipSuccess) return device_fail(ctx, e);
-        e = launch(ctx, s, "k_persistent", [&] { return launch_persistent(v, r, et, fused, grid, s); });
+        const bool one_shot = ctx->L.max_group_items * 8 <= grid;       // an XCD's share of the resident workgroups holds a whole group
+        e = launch(ctx, s, "k_single_pass", [&] { return launch_single_pass(v, r, et, fused, grid, one_shot, s); });
         if (e != hipSuccess) return device_fail(ctx, e);
         if (ctx->range_has_group_scale(first, count)) {
             r.only_group_scale = 1;

@@ -23,7 +23,7 @@ constexpr int kPersistThreads = 256;
 constexpr int kStripeChannels = 256;
 constexpr int kStripeChunks = kStripeChannels / kChunk;     // 32
 constexpr int kRowLanes = kPersistThreads / kStripeChunks;  // 8
-constexpr uint32_t kSpinLimit = 1u << 22;                   // bounded wait (about seconds), then the error flag
+constexpr uint32_t kSpinLimit = 1u << 20;                   // bounded wait (about seconds), then the error flag
 
 // Static description of one tensor; built at cf_init, lives in the workspace.
 struct alignas(16) TensorDev {
@@ -121,7 +121,8 @@ hipError_t launch_lr_decode(const BatchView &v, const LaunchRange &r, hipStream_
 
 // Single-pass kernel (channel scales, CF_EF_RECON).  `grid` workgroups must be co-resident.
 int persistent_max_blocks_per_cu(int err_dtype, bool fused);
-hipError_t launch_persistent(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, int grid, hipStream_t s);
+hipError_t launch_single_pass(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, int grid, bool one_shot,
+                             hipStream_t s);
 hipError_t launch_reset_partials(const BatchView &v, const LaunchRange &r, hipStream_t s);
 
 }  // namespace cf

@@ -8,22 +8,33 @@
 //           128 VGPRs of raw data per lane), owned by one workgroup of 256 lanes
 //           (32 chunks of 8 channels x 8 row-lanes);
 //   group = the items of one 256-channel stripe of one tensor; only they have
-//           to agree on that stripe's scales, so there is no grid-wide barrier:
-//           a group synchronises through one arrival counter, and different
-//           groups drift apart, which keeps HBM busy while some workgroups wait.
+//           to agree on that stripe's scales, so there is no grid-wide barrier,
+//           and different groups drift apart, which keeps HBM busy while some
+//           workgroups wait.
 // Per item: load -> |z| tree over the lane's rows -> LDS tree over row-lanes
 // -> publish the item's partial (an aligned power-of-two block of the channel
-// tree) -> arrive -> wait for the group -> every workgroup of the group
-// finishes the tree over the group's partials itself -> scales -> codes,
-// error and reconstruction straight from the registers.
+// tree) -> every workgroup of the group fetches the group's partials as they
+// appear and finishes the tree itself -> scales -> codes, error and
+// reconstruction straight from the registers.
 //
-// The grid is persistent (items are dealt round-robin, group-major), must be
-// co-resident (cooperative launch) and at least as large as the largest group;
-// then the lowest unfinished item's group always has all its items in flight,
-// so every wait ends.  Waits are bounded all the same: on expiry the
-// workgroup raises the error flag and leaves.
+// A partial is its own ready flag: the buffer is filled with a pattern no
+// partial can take before the kernel starts, and a reader fetches a slot again
+// until it has changed.  One store and one load per hop; no counter.
+//
+// Items are numbered group-major and dealt to the workgroups XCD-major, so the
+// items of a group run on one XCD at about the same time.  Every wait ends
+// because the waited-for items are running or about to start: under a
+// cooperative launch (a co-resident grid that loops over the items, at least
+// as large as the largest group) by construction; under an ordinary launch of
+// one workgroup per item because workgroups start in index order (see
+// launch_single_pass).  Waits are bounded all the same: on expiry the workgroup
+// raises the error flag and leaves.
 #include "cf_device.h"
 #include "cf_internal.h"
+
+#ifndef CF_POLL_BATCH
+#define CF_POLL_BATCH 8
+#endif
 
 namespace cf {
 namespace {
@@ -43,7 +54,7 @@ constexpr uint32_t kUnpublished = 0xFFFFFFFFu;
 template <bool IS_MAX, int LV>
 __device__ __forceinline__ float tree_over_published(int n, const float *mine, int64_t stride, bool &ok)
 {
-    constexpr int NB = 8;                           // leaves fetched (and re-fetched) together
+    constexpr int NB = CF_POLL_BATCH;               // leaves fetched (and re-fetched) together
     float stack[LV];
 #pragma unroll
     for (int l = 0; l < LV; ++l) stack[l] = 0.0f;
@@ -67,10 +78,12 @@ __device__ __forceinline__ float tree_over_published(int n, const float *mine, i
                 if ((pending >> u) & 1u) vals[u] = fetch(mine + (int64_t)(b * NB + u) * stride);
             ++spins;
         }
-        float p2[4];
+        // balanced tree over the batch: neighbours, then neighbours of neighbours, ...
 #pragma unroll
-        for (int u = 0; u < 4; ++u) p2[u] = comb<IS_MAX>(vals[2 * u], vals[2 * u + 1]);
-        tree_push<LV, IS_MAX>(stack, comb<IS_MAX>(comb<IS_MAX>(p2[0], p2[1]), comb<IS_MAX>(p2[2], p2[3])), b);
+        for (int w = 1; w < NB; w <<= 1)
+#pragma unroll
+            for (int u = 0; u < NB; u += 2 * w) vals[u] = comb<IS_MAX>(vals[u], vals[u + w]);
+        tree_push<LV, IS_MAX>(stack, vals[0], b);
     }
     return tree_top<LV, IS_MAX>(stack);
 }
@@ -83,7 +96,7 @@ struct alignas(16) Shared {
 
 template <int DT, int BITS, int ET, bool FUSED>
 __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev &d, const TensorPtrs &p, int stripe,
-                                             int rb, uint32_t *counter, Shared &sh)
+                                             int rb, Shared &sh)
 {
     constexpr int RPT = (DT == BF16) ? 16 : 8;      // rows per lane
     constexpr bool IS_MAX = BITS == 4;
@@ -222,7 +235,7 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
 }
 
 template <int ET, bool FUSED>
-__global__ __launch_bounds__(kPersistThreads, 2) void k_persistent(BatchView v, LaunchRange r)
+__global__ __launch_bounds__(kPersistThreads, 2) void k_single_pass(BatchView v, LaunchRange r)
 {
     __shared__ Shared sh;
     // Workgroups are handed to the 8 XCDs in turn (blockIdx.x % 8).  Numbering them XCD-major puts
@@ -236,16 +249,15 @@ __global__ __launch_bounds__(kPersistThreads, 2) void k_persistent(BatchView v, 
         const uint32_t local = item - d.p_item_begin;               // group-major: stripe, then row block
         const int stripe = (int)(local / (uint32_t)d.p_n_rb);
         const int rb = (int)(local % (uint32_t)d.p_n_rb);
-        uint32_t *counter = v.group_counters + d.p_group_begin + stripe;
         bool ok;
         if (d.dtype == BF16) {
-            if (d.bits == 1) ok = persist_item<BF16, 1, ET, FUSED>(v, d, p, stripe, rb, counter, sh);
-            else if (d.bits == 2) ok = persist_item<BF16, 2, ET, FUSED>(v, d, p, stripe, rb, counter, sh);
-            else ok = persist_item<BF16, 4, ET, FUSED>(v, d, p, stripe, rb, counter, sh);
+            if (d.bits == 1) ok = persist_item<BF16, 1, ET, FUSED>(v, d, p, stripe, rb, sh);
+            else if (d.bits == 2) ok = persist_item<BF16, 2, ET, FUSED>(v, d, p, stripe, rb, sh);
+            else ok = persist_item<BF16, 4, ET, FUSED>(v, d, p, stripe, rb, sh);
         } else {
-            if (d.bits == 1) ok = persist_item<F32, 1, ET, FUSED>(v, d, p, stripe, rb, counter, sh);
-            else if (d.bits == 2) ok = persist_item<F32, 2, ET, FUSED>(v, d, p, stripe, rb, counter, sh);
-            else ok = persist_item<F32, 4, ET, FUSED>(v, d, p, stripe, rb, counter, sh);
+            if (d.bits == 1) ok = persist_item<F32, 1, ET, FUSED>(v, d, p, stripe, rb, sh);
+            else if (d.bits == 2) ok = persist_item<F32, 2, ET, FUSED>(v, d, p, stripe, rb, sh);
+            else ok = persist_item<F32, 4, ET, FUSED>(v, d, p, stripe, rb, sh);
         }
         if (!ok) return;                                            // uniform over the workgroup
     }
@@ -259,7 +271,7 @@ __global__ void k_reset_partials(u32x4 *words, uint64_t n_vec)
         *gmut<u32x4>(words + i) = fill;
 }
 
-template <int ET, bool FUSED> const void *persistent_fn() { return reinterpret_cast<const void *>(&k_persistent<ET, FUSED>); }
+template <int ET, bool FUSED> const void *persistent_fn() { return reinterpret_cast<const void *>(&k_single_pass<ET, FUSED>); }
 
 const void *pick(int err_dtype, bool fused)
 {
@@ -287,7 +299,17 @@ hipError_t launch_reset_partials(const BatchView &v, const LaunchRange &r, hipSt
     return hipGetLastError();
 }
 
-hipError_t launch_persistent(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, int grid, hipStream_t s)
+// one_shot: one workgroup per item under an ordinary launch instead of a co-resident grid that loops.
+// A workgroup that loops has to drain its stores before its next loads count as returned (the loads and
+// stores of a wave share one in-order counter); one that exits leaves the draining to the memory system
+// while the next workgroup already loads.  Without co-residency every wait still ends because workgroups
+// are started in index order: with items numbered XCD-major each XCD walks its own contiguous run of
+// items in order, so the members of its oldest unfinished group are the oldest workgroups it holds or
+// the next it starts, and whatever else it holds belongs to older groups, publishes without waiting and
+// leaves.  The caller passes one_shot only when an XCD's share of `grid` (the co-resident capacity) holds
+// a whole group.  Should the assumption ever fail, the bounded wait raises the error flag.
+hipError_t launch_single_pass(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, int grid, bool one_shot,
+                             hipStream_t s)
 {
     if (r.item_hi == r.item_lo) return hipSuccess;
     uint32_t items = r.item_hi - r.item_lo;
@@ -295,6 +317,7 @@ hipError_t launch_persistent(const BatchView &v, const LaunchRange &r, int err_d
     BatchView vv = v;
     LaunchRange rr = r;
     void *args[] = {&vv, &rr};
+    if (one_shot) return hipLaunchKernel(pick(err_dtype, fused), dim3(items), dim3(kPersistThreads), args, 0, s);
     return hipLaunchCooperativeKernel(pick(err_dtype, fused), dim3(grid), dim3(kPersistThreads), args, 0, s);
 }
 

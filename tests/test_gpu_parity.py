@@ -119,6 +119,17 @@ def test_single_pass_many_row_blocks_and_stripes():
     run_parity(descs, cf.options(), xs, mode="fused")
 
 
+def test_single_pass_looping_grid():
+    """Groups of 71 items (N = 9000) are too large for one workgroup per item to be safe, so the
+    single-pass kernel runs as a co-resident grid that loops over the items (cooperative launch)."""
+    say("single pass, looping grid")
+    descs = [cf.desc(9000, 264, cf.CF_BF16, (1, 2, 4)[t % 3], CH) for t in range(9)]
+    streams = [drift_stream((d.n_tokens, d.n_channels), d.dtype, steps=3, seed=170 + k, device=DEV)
+               for k, d in enumerate(descs)]
+    xs = [[streams[t][s] for t in range(len(descs))] for s in range(3)]
+    run_parity(descs, cf.options(flags=cf.CF_FLAG_SINGLE_PASS), xs, mode="fused")
+
+
 def test_subrange_calls_match_whole_batch():
     """Calling [first, first+count) pieces, in any order, equals one whole-batch call."""
     say("subrange")
