@@ -341,7 +341,7 @@ def main():
         kb = kernel_algorithmic_bytes(kname, wl, args.ef)
         achieved = kb / (kms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBPS, "traffic": None if (args.scale or args.bits or args.tensors or args.ef or args.flags) else read_traffic(kname, head),
+                    "frac": achieved / HBM_PEAK_GBPS, "traffic": None if (args.scale or args.bits or args.tensors or args.ef) else read_traffic(kname, head),
                     "algorithmic_bytes_per_launch": kb, "avg_launch_ms": kms}
     mfma = None
     if wl.scale == "lowrank" and r.get("kernel_ms"):        # the dense contractions: 2 * 32 flops per element and launch
