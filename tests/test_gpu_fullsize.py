@@ -99,3 +99,45 @@ def test_cfg5_two_kernel_path_full():
     """The two-kernel path at full size (the default runs the single-pass kernel, whose reduction groups
     span 32 workgroups here)."""
     run_full("cfg5_batched_mixed", sampled=(3, 31, 53), follow_steps=4, flags=cf.CF_FLAG_TWO_KERNEL)
+
+
+# ---------------------------------------------------------------- the widened rows at the size of configuration 3
+
+def _full_shape_case(name, descs, opts, seed, steps=3):
+    """A few [4096, 3072] bf16 tensors, every one checked against the oracle at every step."""
+    t0 = time.time()
+    wl = CONFIGS["cfg3_kv_fullseq"].scaled(n_tensors=len(descs), seed=seed)
+    stream = ActivationStream(wl, device=DEV)
+    sess = CodecSession(descs, opts, device=DEV)
+    everything = list(range(len(descs)))
+    orc = OracleState(descs, opts, everything)
+    try:
+        sess.warmup(stream.current)
+        with ThreadPoolExecutor(max_workers=8) as pool:
+            list(pool.map(lambda t: orc.warmup(t, as_numpy(stream.current[t])), everything))
+            for s in range(1, steps + 1):
+                xs = stream.advance()
+                sess.step_fused(xs)
+                cf.cf_check_device(sess.ctx, sess.stream_handle)
+                list(pool.map(lambda t: orc.step(t, as_numpy(xs[t])), everything))
+                for t in everything:
+                    compare_tensor(f"{name} step {s}", sess, orc, t)
+                say(f"{name}: step {s}/{steps}: {len(descs)} tensors bit-exact ({time.time() - t0:.0f}s)")
+    finally:
+        sess.close()
+
+
+def test_rank1_scales_full_shape():
+    descs = [cf.desc(4096, 3072, cf.CF_BF16, 1 + t % 2, cf.CF_SCALE_RANK1) for t in range(6)]
+    _full_shape_case("rank-1 scales", descs, cf.options(), seed=21)
+
+
+def test_nm_sparsifier_full_shape():
+    descs = [cf.desc(4096, 3072, cf.CF_BF16, (1, 2, 4)[t % 3], cf.CF_SPARSE_NM, 8) for t in range(6)]
+    _full_shape_case("N:M sparsifier", descs, cf.options(), seed=22)
+
+
+def test_naive_and_no_feedback_full_shape():
+    descs = [cf.desc(4096, 3072, cf.CF_BF16, (1, 2, 4)[t % 3], cf.CF_SCALE_CHANNEL) for t in range(3)]
+    _full_shape_case("naive", descs, cf.options(ef=cf.CF_EF_NAIVE), seed=23, steps=2)
+    _full_shape_case("no feedback", descs, cf.options(ef=cf.CF_EF_OFF), seed=24, steps=2)

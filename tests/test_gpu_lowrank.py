@@ -195,3 +195,27 @@ def test_lowrank_rejections():
     good = cf.desc(64, 128, cf.CF_BF16, 1, cf.CF_LOWRANK, R)
     assert cf.cf_sizes(good)[:2] == ((64 + 128) * R * 2, 128 * R * 4)
     assert cf.cf_workspace_bytes([good], cf.options(ef=cf.CF_EF_OFF)) == 0     # only the default feedback mode
+
+
+def test_lowrank_full_shape():
+    """[4096, 3072] bf16, rank 32, T = 1 and 2, in one batch: factors against the fp64 oracle, error and
+    reconstruction re-derived from the travelled factors."""
+    n, c = 4096, 3072
+    descs = [cf.desc(n, c, cf.CF_BF16, 1 + t % 2, cf.CF_LOWRANK, R) for t in range(4)]
+    xs = [stream(n, c, cf.CF_BF16, 3, 300 + t) for t in range(4)]
+    q0s = [start_matrices(c, 3, 400 + t) for t in range(4)]
+    sess = CodecSession(descs, cf.options(), device=DEV)
+    try:
+        sess.warmup([x[0] for x in xs])
+        for s in (1, 2):
+            before = [as_numpy(sess.recon[t]).copy() for t in range(4)]
+            for t in range(4):
+                sess.scales[t].copy_(q0s[t][s].reshape(-1))
+            sess.step_fused([x[s] for x in xs])
+            cf.cf_check_device(sess.ctx, sess.stream_handle)
+            for t in range(4):
+                cfg = lr.LowRankConfig(n, c, dtype=lr.BF16, rank=R, iters=1 + t % 2)
+                du, dv = check_step(f"full t{t} step {s}", cfg, sess, t, as_numpy(xs[t][s]), before[t], as_numpy(q0s[t][s]))
+                say(f"lowrank full shape tensor {t} step {s}: factors within {du:.1e} (U, relative), {dv:.1e} (V, absolute)")
+    finally:
+        sess.close()
