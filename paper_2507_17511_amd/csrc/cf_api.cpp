@@ -29,6 +29,7 @@ struct Layout {
     std::vector<uint32_t> tile_prefix, fin_prefix, ew_prefix;
     size_t off_ew_prefix = 0;
     bool any_channel = false, any_rank1 = false, any_lowrank = false;
+    int64_t min_channel_scale_tokens = INT64_MAX;
 };
 
 cf_status check_opts(const cf_options *o, cf_options &out)
@@ -169,8 +170,9 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
         }
         L.item_prefix[t] = (uint32_t)items;
         L.group_prefix[t] = (uint32_t)groups;
+        if (d.scale == CF_SCALE_CHANNEL && d.n_tokens < L.min_channel_scale_tokens) L.min_channel_scale_tokens = d.n_tokens;
         if (d.scale == CF_SCALE_CHANNEL && L.single_pass) {
-            v.p_rows = d.dtype == CF_BF16 ? 128 : 64;        // 8 row-lanes x 16 (bf16) or 8 (fp32) rows
+            v.p_rows = kRowLanes * (d.dtype == CF_BF16 ? 16 : 8);    // row-lanes x 16 (bf16) or 8 (fp32) rows per lane
             v.p_n_rb = (int32_t)((d.n_tokens + v.p_rows - 1) / v.p_rows);
             v.p_n_stripes = (int32_t)((d.n_channels + kStripeChannels - 1) / kStripeChannels);
             v.p_item_begin = (uint32_t)items;
@@ -487,8 +489,11 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
     const int ef = ctx->opts.ef, et = ctx->opts.err_dtype;
     hipError_t e;
     const int grid = ctx->persist_grid[et == CF_BF16 ? 1 : 0][fused ? 1 : 0];
-    const uint32_t min_items = (ctx->opts.flags & CF_FLAG_SINGLE_PASS) ? 1u : 64u;      // tiny batches: the wait chain costs more than a second read
-    if (ctx->L.single_pass && grid >= ctx->L.max_group_items && r.item_hi - r.item_lo >= min_items) {
+    // unless asked for: not for tiny batches (the wait chain costs more than a second read) nor for short tensors
+    // (an item is 256 or 512 rows tall: most of its lanes would idle)
+    const bool forced = (ctx->opts.flags & CF_FLAG_SINGLE_PASS) != 0;
+    const bool worth_it = forced || (r.item_hi - r.item_lo >= 64u && ctx->L.min_channel_scale_tokens >= 256);
+    if (ctx->L.single_pass && grid >= ctx->L.max_group_items && r.item_hi > r.item_lo && worth_it) {
         // channel-scale tensors: one pass, x and recon stay in registers across the scale reduction
         e = launch(ctx, s, "k_reset_partials", [&] { return launch_reset_partials(v, r, s); });
         if (e != hipSuccess) return device_fail(ctx, e);

@@ -4,10 +4,10 @@
 //
 // A two-kernel design reads x and recon twice from HBM.  Here a workgroup
 // keeps its share of x and recon in registers across the reduction instead:
-//   item  = p_rows x 256 channels of one tensor (128 rows of bf16, 64 of fp32:
+//   item  = p_rows x 64 channels of one tensor (512 rows of bf16, 256 of fp32:
 //           128 VGPRs of raw data per lane), owned by one workgroup of 256 lanes
-//           (32 chunks of 8 channels x 8 row-lanes);
-//   group = the items of one 256-channel stripe of one tensor; only they have
+//           (8 chunks of 8 channels x 32 row-lanes);
+//   group = the items of one 64-channel stripe of one tensor; only they have
 //           to agree on that stripe's scales, so there is no grid-wide barrier,
 //           and different groups drift apart, which keeps HBM busy while some
 //           workgroups wait.
@@ -100,7 +100,7 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
 {
     constexpr int RPT = (DT == BF16) ? 16 : 8;      // rows per lane
     constexpr bool IS_MAX = BITS == 4;
-    const int tid = (int)threadIdx.x, cl = tid & (kStripeChunks - 1), rl = tid >> 5;
+    const int tid = (int)threadIdx.x, cl = tid & (kStripeChunks - 1), rl = tid / kStripeChunks;
     const int chunk = stripe * kStripeChunks + cl;
     const bool cvalid = chunk < d.n_chunks;
     const int64_t row0 = (int64_t)rb * d.p_rows + rl * RPT;
@@ -159,14 +159,19 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
     if (tid == 0) sh.ok = 1u;
     __syncthreads();
 
-    // ---- level 2: tree over the 8 row-lanes (consecutive RPT-row blocks); one lane per channel
-    const int64_t col = (int64_t)stripe * kStripeChannels + tid;
+    // ---- level 2: tree over the row-lanes (consecutive RPT-row blocks); one lane per channel
+    const bool owner = tid < kStripeChannels;
+    const int64_t col = owner ? (int64_t)stripe * kStripeChannels + tid : C;
     float *partial = reinterpret_cast<float *>(v.workspace + d.p_partial_off);
-    {
-        float s01 = comb<IS_MAX>(sh.red[0][tid], sh.red[1][tid]), s23 = comb<IS_MAX>(sh.red[2][tid], sh.red[3][tid]);
-        float s45 = comb<IS_MAX>(sh.red[4][tid], sh.red[5][tid]), s67 = comb<IS_MAX>(sh.red[6][tid], sh.red[7][tid]);
-        float item = comb<IS_MAX>(comb<IS_MAX>(s01, s23), comb<IS_MAX>(s45, s67));
-        if (col < C) publish(partial + (int64_t)rb * C + col, item);
+    if (owner) {
+        float lanes[kRowLanes];
+#pragma unroll
+        for (int q = 0; q < kRowLanes; ++q) lanes[q] = sh.red[q][tid];
+#pragma unroll
+        for (int w = 1; w < kRowLanes; w <<= 1)
+#pragma unroll
+            for (int q = 0; q < kRowLanes; q += 2 * w) lanes[q] = comb<IS_MAX>(lanes[q], lanes[q + w]);
+        if (col < C) publish(partial + (int64_t)rb * C + col, lanes[0]);
     }
     // The partials are agent-scope atomic stores (written through to where the other XCDs read them)
     // and every partial is its own ready flag: nothing to drain, no arrival to count.

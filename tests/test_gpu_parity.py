@@ -106,7 +106,7 @@ def test_parity_batched_mixed_launch(mode, flags):
 
 
 def test_single_pass_many_row_blocks_and_stripes():
-    """Reduction groups of many items (N = 1500: 12 row blocks of 128, ragged) over 5 stripes (C = 1096),
+    """Reduction groups of several items (N = 1500: 3 row blocks of 512, ragged) over 18 stripes (C = 1096),
     several tensors deep, so that workgroups take more than one item each."""
     say("single pass, deep")
     descs = [cf.desc(1500, 1096, cf.CF_BF16, (1, 2, 4)[t % 3], CH) for t in range(6)]
@@ -120,10 +120,10 @@ def test_single_pass_many_row_blocks_and_stripes():
 
 
 def test_single_pass_looping_grid():
-    """Groups of 71 items (N = 9000) are too large for one workgroup per item to be safe, so the
+    """Groups of 79 items (N = 40000) are too large for one workgroup per item to be safe, so the
     single-pass kernel runs as a co-resident grid that loops over the items (cooperative launch)."""
     say("single pass, looping grid")
-    descs = [cf.desc(9000, 264, cf.CF_BF16, (1, 2, 4)[t % 3], CH) for t in range(9)]
+    descs = [cf.desc(40000, 72, cf.CF_BF16, (1, 2, 4)[t % 3], CH) for t in range(6)]
     streams = [drift_stream((d.n_tokens, d.n_channels), d.dtype, steps=3, seed=170 + k, device=DEV)
                for k, d in enumerate(descs)]
     xs = [[streams[t][s] for t in range(len(descs))] for s in range(3)]
