@@ -383,12 +383,17 @@ template <int DT> __device__ __forceinline__ void factor16(const uint8_t *base, 
     for (int k = 0; k < 16; ++k) out[k] = valid ? out[k] : 0.0f;
 }
 
-// A wave owns 32 tokens and walks the channels in tiles of 64.  The MFMA leaves lane (n, h) with
+// A wave owns 32 tokens and kApplySpan channels, which it walks in tiles of 64 (a workgroup that
+// looped over all channels would have to drain its stores before each tile's loads count as returned).  The MFMA leaves lane (n, h) with
 // channel n of 16 tokens, which is the wrong way round for row-major memory, so the tile of D goes
 // through the wave's own LDS patch [32 tokens][64 channels] and comes back as 8 consecutive channels
 // of one token per lane: 8 lanes then cover 128 bytes of a bf16 row (256 of the fp32 error row).
 // SENDER: also forms A again and writes e = A - D.  UPDATE: writes recon + D.
 constexpr int kApplyChannels = 64;
+#ifndef CF_APPLY_SPAN
+#define CF_APPLY_SPAN 128
+#endif
+constexpr int kApplySpan = CF_APPLY_SPAN;                   // channels per workgroup
 constexpr int kApplyPitch = kApplyChannels + 4;             // floats per token row of the patch
 
 template <int DT, int ET, bool SENDER, bool UPDATE>
@@ -396,15 +401,18 @@ __device__ __forceinline__ void lr_apply_body(const TensorDev &d, const TensorPt
 {
     const int lane = (int)threadIdx.x & 63, wave = (int)threadIdx.x >> 6;
     const int n = lane & 31, h = lane >> 5;
-    const int64_t tok_base = (int64_t)blockIdx.x * 128 + wave * 32;
+    const int n_spans = (d.n_channels + kApplySpan - 1) / kApplySpan;
+    const int span = (int)(blockIdx.x % (unsigned)n_spans);
+    const int64_t tok_base = (int64_t)(blockIdx.x / (unsigned)n_spans) * 128 + wave * 32;
     if (tok_base >= d.n_tokens) return;                     // uniform over the wave
     const int64_t C = d.n_channels;
     float u[16];
     factor16<DT>(wire_u(p), tok_base + n, h, tok_base + n < d.n_tokens, u);
     const uint8_t *V = wire_v(d, p);
-    const int n_sub = d.n_channels / 32;
+    const int sub_lo = span * (kApplySpan / 32);
+    const int n_sub = d.n_channels / 32 < sub_lo + kApplySpan / 32 ? d.n_channels / 32 : sub_lo + kApplySpan / 32;
     const int chunk = lane & 7, trow = lane >> 3;           // row-major side: 8 chunks of 8 channels, 8 tokens per sweep
-    for (int sub0 = 0; sub0 < n_sub; sub0 += 2) {
+    for (int sub0 = sub_lo; sub0 < n_sub; sub0 += 2) {
         const int cnt = n_sub - sub0 < 2 ? 1 : 2;
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
@@ -499,10 +507,17 @@ hipError_t launch_lr_backproject(const BatchView &v, const LaunchRange &r, int m
     return hipGetLastError();
 }
 
+// Blocks of 128 tokens x kApplySpan channels, for the largest low-rank tensor of the range; a tensor with
+// fewer channel spans sees block indices beyond its own and returns at once (tok_base >= n_tokens).
+static unsigned apply_blocks(const LaunchRange &r)
+{
+    return (unsigned)((r.lr_max_tokens + 127) / 128) * (unsigned)((r.lr_max_channels + kApplySpan - 1) / kApplySpan);
+}
+
 hipError_t launch_lr_encode(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, hipStream_t s)
 {
     if (r.count == 0 || r.lr_max_tokens == 0) return hipSuccess;
-    dim3 grid((unsigned)((r.lr_max_tokens + 127) / 128), (unsigned)r.count), block(256);
+    dim3 grid(apply_blocks(r), (unsigned)r.count), block(256);
     if (err_dtype == BF16) {
         if (fused) hipLaunchKernelGGL((k_lr_apply<BF16, true, true>), grid, block, 0, s, v, r);
         else hipLaunchKernelGGL((k_lr_apply<BF16, true, false>), grid, block, 0, s, v, r);
@@ -516,7 +531,7 @@ hipError_t launch_lr_encode(const BatchView &v, const LaunchRange &r, int err_dt
 hipError_t launch_lr_decode(const BatchView &v, const LaunchRange &r, hipStream_t s)
 {
     if (r.count == 0 || r.lr_max_tokens == 0) return hipSuccess;
-    dim3 grid((unsigned)((r.lr_max_tokens + 127) / 128), (unsigned)r.count);
+    dim3 grid(apply_blocks(r), (unsigned)r.count);
     hipLaunchKernelGGL((k_lr_apply<F32, false, true>), grid, dim3(256), 0, s, v, r);
     return hipGetLastError();
 }
