@@ -106,9 +106,6 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
     const int64_t row0 = (int64_t)rb * d.p_rows + rl * RPT;
     const int64_t C = d.n_channels;
 
-#ifdef CF_PHASE_TIMING
-    const long long t_start = clock64();
-#endif
     // ---- load the lane's rows (raw), all in flight at once
     Raw8<DT> xr[RPT], br[RPT];
 #pragma unroll
@@ -161,9 +158,6 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
     }
     if (tid == 0) sh.ok = 1u;
     __syncthreads();
-#ifdef CF_PHASE_TIMING
-    const long long t_loaded = clock64();
-#endif
 
     // ---- level 2: tree over the row-lanes (consecutive RPT-row blocks); one lane per channel
     const bool owner = tid < kStripeChannels;
@@ -182,9 +176,6 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
     // The partials are agent-scope atomic stores (written through to where the other XCDs read them)
     // and every partial is its own ready flag: nothing to drain, no arrival to count.
 
-#ifdef CF_PHASE_TIMING
-    const long long t_published = clock64();
-#endif
     // ---- level 3: the same tree continued over the group's item partials as they appear, then the scale
     if (col < C) {
         bool ok = true;
@@ -199,9 +190,6 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
     }
     __syncthreads();
     if (!sh.ok) return false;
-#ifdef CF_PHASE_TIMING
-    const long long t_scaled = clock64();
-#endif
 
     // ---- a4-a8 from the registers.  z is formed again from the raw operands: keeping the first
     // phase's fp32 residuals alive across the wait would double the register footprint.
@@ -248,15 +236,6 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
             }
         }
     }
-#ifdef CF_PHASE_TIMING
-    if (tid == 0 && (blockIdx.x % 4001u) == 0) {
-        const long long t_end = clock64();
-        __builtin_amdgcn_s_waitcnt(0);
-        const long long t_drained = clock64();
-        printf("item blk %u rb %d: load+tree %lld  publish %lld  wait+fetch %lld  encode+issue %lld  drain %lld cycles\n", blockIdx.x, rb,
-               t_loaded - t_start, t_published - t_loaded, t_scaled - t_published, t_end - t_scaled, t_drained - t_end);
-    }
-#endif
     return true;
 }
 
