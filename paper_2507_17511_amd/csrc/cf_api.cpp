@@ -19,9 +19,8 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
     size_t off_descs = 0, off_ptrs = 0, off_tile_prefix = 0, off_fin_prefix = 0, off_partials = 0;
-    size_t off_item_prefix = 0, off_counters = 0, off_error = 0, off_p_partials = 0;
-    std::vector<uint32_t> item_prefix, group_prefix;
-    uint32_t n_groups = 0;
+    size_t off_item_prefix = 0, off_error = 0, off_p_partials = 0;
+    std::vector<uint32_t> item_prefix;
     int32_t max_group_items = 0;   // largest reduction group of the single-pass path
     bool single_pass = false;      // every channel-scale tensor has single-pass geometry
     size_t total = 0;
@@ -113,10 +112,9 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     L.ew_prefix.assign(n + 1, 0);
     uint64_t ew_tiles = 0;
     L.fin_prefix.assign(n + 1, 0);
-    uint64_t tiles = 0, fins = 0, items = 0, groups = 0;
+    uint64_t tiles = 0, fins = 0, items = 0;
     size_t partial_bytes = 0, p_partial_bytes = 0;
     L.item_prefix.assign(n + 1, 0);
-    L.group_prefix.assign(n + 1, 0);
     L.single_pass = o.ef == CF_EF_RECON && (o.flags & CF_FLAG_TWO_KERNEL) == 0;
     for (int32_t t = 0; t < n; ++t)
         if (descs[t].scale == CF_SCALE_RANK1) L.single_pass = false;   // the single-pass kernel knows channel scales only
@@ -169,18 +167,15 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
             partial_bytes += align_up((size_t)d.n_tokens * (size_t)v.n_colblocks * sizeof(float));
         }
         L.item_prefix[t] = (uint32_t)items;
-        L.group_prefix[t] = (uint32_t)groups;
         if (d.scale == CF_SCALE_CHANNEL && d.n_tokens < L.min_channel_scale_tokens) L.min_channel_scale_tokens = d.n_tokens;
         if (d.scale == CF_SCALE_CHANNEL && L.single_pass) {
             v.p_rows = kRowLanes * (d.dtype == CF_BF16 ? 16 : 8);    // row-lanes x 16 (bf16) or 8 (fp32) rows per lane
             v.p_n_rb = (int32_t)((d.n_tokens + v.p_rows - 1) / v.p_rows);
             v.p_n_stripes = (int32_t)((d.n_channels + kStripeChannels - 1) / kStripeChannels);
             v.p_item_begin = (uint32_t)items;
-            v.p_group_begin = (uint32_t)groups;
             v.p_partial_off = p_partial_bytes;               // relative; rebased below
             p_partial_bytes += align_up((size_t)v.p_n_rb * (size_t)d.n_channels * sizeof(float));
             items += (uint64_t)v.p_n_rb * (uint64_t)v.p_n_stripes;
-            groups += (uint64_t)v.p_n_stripes;
             if (v.p_n_rb > L.max_group_items) L.max_group_items = v.p_n_rb;
             if (items > 0x7fffffffull) return CF_ERR_SHAPE;
         }
@@ -189,8 +184,6 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     L.ew_prefix[n] = (uint32_t)ew_tiles;
     L.fin_prefix[n] = (uint32_t)fins;
     L.item_prefix[n] = (uint32_t)items;
-    L.group_prefix[n] = (uint32_t)groups;
-    L.n_groups = (uint32_t)groups;
 
     size_t off = 0;
     L.off_descs = off;        off = align_up(off + sizeof(TensorDev) * (size_t)n);
@@ -200,7 +193,6 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     L.off_ew_prefix = off;    off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
     L.off_partials = off;     off = align_up(off + partial_bytes);
     L.off_item_prefix = off;  off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
-    L.off_counters = off;     off = align_up(off + sizeof(uint32_t) * (size_t)(groups + 1));
     L.off_error = off;        off = align_up(off + sizeof(uint32_t));
     L.off_p_partials = off;   off = align_up(off + p_partial_bytes);
     L.total = off;
@@ -250,7 +242,6 @@ struct cf_ctx {
         v.fin_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_fin_prefix);
         v.ew_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_ew_prefix);
         v.item_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_item_prefix);
-        v.group_counters = reinterpret_cast<uint32_t *>(ws + L.off_counters);
         v.error_flag = reinterpret_cast<uint32_t *>(ws + L.off_error);
         v.workspace = ws;
         v.n_tensors = (int32_t)descs.size();
@@ -270,8 +261,6 @@ struct cf_ctx {
         r.fin_hi = L.fin_prefix[first + count];
         r.item_lo = L.item_prefix[first];
         r.item_hi = L.item_prefix[first + count];
-        r.group_lo = L.group_prefix[first];
-        r.group_hi = L.group_prefix[first + count];
         r.only_group_scale = 0;
         r.naive = opts.ef == CF_EF_NAIVE;
         r.dts = descs[first].dtype;
@@ -621,7 +610,7 @@ cf_status cf_init(cf_ctx **out, const cf_tensor_desc *descs, int32_t n_tensors, 
     if (e == hipSuccess)
         e = hipMemsetAsync(ctx->ws + ctx->L.off_ptrs, 0, sizeof(TensorPtrs) * (size_t)n_tensors, s);
     if (e == hipSuccess)
-        e = hipMemsetAsync(ctx->ws + ctx->L.off_counters, 0, ctx->L.off_p_partials - ctx->L.off_counters, s);
+        e = hipMemsetAsync(ctx->ws + ctx->L.off_error, 0, sizeof(uint32_t), s);
     if (e == hipSuccess && ctx->L.single_pass && ctx->L.max_group_items > 0) {
         hipDeviceProp_t prop;
         e = hipGetDeviceProperties(&prop, ctx->device);

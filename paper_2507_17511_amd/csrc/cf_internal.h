@@ -52,7 +52,7 @@ struct alignas(16) TensorDev {
     int32_t p_n_rb;         // ceil(N / p_rows): items per reduction group
     int32_t p_n_stripes;    // ceil(C / kStripeChannels): reduction groups of this tensor
     uint32_t p_item_begin;  // id of this tensor's first item
-    uint32_t p_group_begin; // index of its first group counter
+    uint32_t p_pad_;
     // element-wise kernels (warm-up, encode, decode): short tiles of ew_rows x 1024 channels
     int32_t ew_rows;
     int32_t ew_n_rowblocks; // ceil(N / ew_rows)
@@ -85,7 +85,6 @@ struct BatchView {
     const uint32_t *ew_prefix;      // [n_tensors + 1] element-wise tiles
     const uint32_t *fin_prefix;     // [n_tensors + 1]
     const uint32_t *item_prefix;    // [n_tensors + 1] items of the single-pass path
-    uint32_t *group_counters;       // one arrival counter per (tensor, stripe)
     uint32_t *error_flag;           // set when a bounded wait expired
     uint8_t *workspace;
     int32_t n_tensors;
@@ -97,7 +96,6 @@ struct LaunchRange {
     uint32_t ew_lo, ew_hi;      // element-wise tiles
     uint32_t fin_lo, fin_hi;    // finalise blocks
     uint32_t item_lo, item_hi;  // single-pass items
-    uint32_t group_lo, group_hi;
     uint64_t p_partial_lo, p_partial_hi;    // workspace bytes holding the single-pass partials of the range
     int32_t dts;                // storage dtype of every tensor in the range (cf_dtype), or 2 if mixed
     int32_t only_group_scale;   // tiled encode: skip tensors the single-pass kernel covers

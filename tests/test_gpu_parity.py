@@ -518,3 +518,55 @@ def test_parity_nm_in_a_mixed_batch():
         for mode in ("fused", "split"):
             say(f"nm mixed batch flags={flags} mode={mode}")
             run_parity(descs, cf.options(flags=flags), [[s[k] for s in streams] for k in range(4)], mode=mode, tag="nm mixed")
+
+
+# ---------------------------------------------------------------- HIP graph capture
+
+@pytest.mark.parametrize("flags", [0, cf.CF_FLAG_TWO_KERNEL])
+def test_step_replays_from_a_hip_graph(flags):
+    """A serving loop can capture one cf_step_fused call in a HIP graph and replay it every step: the call
+    allocates nothing, clears its scratch with a fill kernel and passes its pointers in kernel arguments.  Every
+    replay is checked against an eager context fed the same inputs (default path: the single-pass kernel, one
+    workgroup per item; and the two-kernel path), with eager work and synchronisations between the replays."""
+    descs = [cf.desc(2048, 1024, cf.CF_BF16, (1, 2, 4)[t % 3], CH) for t in range(3)]
+    descs += [cf.desc(300, 1152, cf.CF_BF16, 4, GR), cf.desc(203, 1096, cf.CF_BF16, 2, NMK, 8)]
+    steps = 6
+    streams = [drift_stream((int(d.n_tokens), int(d.n_channels)), int(d.dtype), steps, 800 + t, device=DEV) for t, d in enumerate(descs)]
+    eager = CodecSession(descs, cf.options(flags=flags), device=DEV)
+    graphed = CodecSession(descs, cf.options(flags=flags), device=DEV)
+    try:
+        first = [s[0] for s in streams]
+        eager.warmup(first)
+        graphed.warmup(first)
+        static_x = [s[1].clone() for s in streams]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):                     # step 1 eagerly on the capture stream's side (uploads the pointer table)
+            graphed.step_fused(static_x)
+        torch.cuda.current_stream().wait_stream(side)
+        eager.step_fused([s[1] for s in streams])
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            graphed.step_fused(static_x)
+        for k in range(2, steps):
+            for t in range(len(descs)):
+                static_x[t].copy_(streams[t][k])
+            g.replay()
+            cf.cf_check_device(graphed.ctx, graphed.stream_handle)
+            eager.step_fused([s[k] for s in streams])
+            cf.cf_check_device(eager.ctx, eager.stream_handle)
+            for t in range(len(descs)):
+                for name in ("codes", "scales", "recon", "err"):
+                    a, b = getattr(graphed, name)[t], getattr(eager, name)[t]
+                    if name == "codes" and descs[t].scale == NMK:      # the pad between masks and values is never written
+                        n_mask = int(descs[t].n_tokens) * int(descs[t].n_channels) // 8
+                        a, b = a.clone(), b.clone()
+                        a[n_mask:(n_mask + 15) // 16 * 16] = 0
+                        b[n_mask:(n_mask + 15) // 16 * 16] = 0
+                    assert torch.equal(a.view(torch.uint8).reshape(-1), b.view(torch.uint8).reshape(-1)), \
+                        f"replay {k}: {name}[{t}] differs from the eager run"
+            say(f"graph replay {k} (flags={flags}) matches the eager run")
+    finally:
+        eager.close()
+        graphed.close()
