@@ -93,13 +93,15 @@ __device__ __forceinline__ void lr_project_body(const BatchView &v, const Tensor
     f32x16 acc0 = {}, acc1 = {};
     const int steps = d.n_channels / 32;
     const int chunk = lane & 7, trow = lane >> 3;           // row-major side: 8 chunks of 8 channels, 8 tokens per sweep
-    for (int s0 = 0; s0 < steps; s0 += 2) {
+    // The loads of the next 64 channels are issued as soon as the current ones have gone to the patch,
+    // so that they are in flight while the 64 MFMAs of the current ones run.
+    Raw8<DT> xr[8], br[8];
+    auto fetch = [&](int s0) {
         const int ch = s0 * 32 + chunk * 8;
-        Raw8<DT> xr[8], br[8];
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
             const int64_t tok = row_base + trow + 8 * it;
-            if (tok < d.n_tokens && ch < d.n_channels) {
+            if (s0 < steps && tok < d.n_tokens && ch < d.n_channels) {
                 xr[it].load(p.x, tok * C + ch);
                 br[it].load(p.recon, tok * C + ch);
             } else {
@@ -107,6 +109,9 @@ __device__ __forceinline__ void lr_project_body(const BatchView &v, const Tensor
                 br[it].zero();
             }
         }
+    };
+    fetch(0);
+    for (int s0 = 0; s0 < steps; s0 += 2) {
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
             const F8 x = xr[it].widen(), b = br[it].widen();
@@ -117,6 +122,7 @@ __device__ __forceinline__ void lr_project_body(const BatchView &v, const Tensor
             dst[0] = lo;
             dst[1] = hi;
         }
+        fetch(s0 + 2);
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -195,10 +201,10 @@ __device__ __forceinline__ void lr_backproject_body(const BatchView &v, const Te
     f32x16 acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = (f32x16){};
-    constexpr int U = 2;                                    // token pairs in flight
-    for (int64_t pair0 = lo; pair0 < hi; pair0 += U) {
-        Raw8<DT> xr[U], br[U];
-        float pv[U];
+    constexpr int U = 4;                                    // token pairs per batch; the next batch is in flight during the MFMAs
+    Raw8<DT> xr[U], br[U];
+    float pv[U];
+    auto fetch = [&](int64_t pair0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t row = 2 * (pair0 + u) + h;
@@ -212,12 +218,22 @@ __device__ __forceinline__ void lr_backproject_body(const BatchView &v, const Te
             }
             pv[u] = rvalid ? P[row * kRank + q] : 0.0f;
         }
+    };
+    fetch(lo);
+    for (int64_t pair0 = lo; pair0 < hi; pair0 += U) {
+        float z[U][8], pn[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const F8 x = xr[u].widen(), b = br[u].widen();
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] = mfma32(x.v[j] - b.v[j], pv[u], acc[j]);
+            for (int j = 0; j < 8; ++j) z[u][j] = x.v[j] - b.v[j];
+            pn[u] = pv[u];
         }
+        fetch(pair0 + U);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = mfma32(z[u][j], pn[u], acc[j]);
     }
     // tile j, register i of lane (q, h): channel 8 * rho + j of the stripe with rho = 8 * (i / 4) + 4 * h + i % 4, column q
     for (int w = 0; w < 4; ++w) {
