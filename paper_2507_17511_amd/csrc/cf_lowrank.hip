@@ -122,26 +122,35 @@ __device__ __forceinline__ void lr_project_body(const BatchView &v, const Tensor
             dst[0] = lo;
             dst[1] = hi;
         }
+        // Q first, then the prefetch: loads return in issue order, so the MFMAs below wait for Q only
+        float q[2][16];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const CF_GLOBAL f32x4 *qp = qs + ((int64_t)(s0 + u < steps ? s0 + u : s0) * 64 + lane) * 4;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const f32x4 wq = qp[k];
+                q[u][4 * k] = wq.x; q[u][4 * k + 1] = wq.y; q[u][4 * k + 2] = wq.z; q[u][4 * k + 3] = wq.w;
+            }
+        }
         fetch(s0 + 2);
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             if (s0 + u < steps) {                           // uniform over the wave
-                float z0[16], z1[16], q[16];
+                float z0[16], z1[16];
                 const f32x4 *a0 = reinterpret_cast<const f32x4 *>(patch + m * kProjPitch + 32 * u + 16 * h);
                 const f32x4 *a1 = reinterpret_cast<const f32x4 *>(patch + (m + 32) * kProjPitch + 32 * u + 16 * h);
-                const CF_GLOBAL f32x4 *qp = qs + ((int64_t)(s0 + u) * 64 + lane) * 4;
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    const f32x4 w0 = a0[k], w1 = a1[k], wq = qp[k];
+                    const f32x4 w0 = a0[k], w1 = a1[k];
                     z0[4 * k] = w0.x; z0[4 * k + 1] = w0.y; z0[4 * k + 2] = w0.z; z0[4 * k + 3] = w0.w;
                     z1[4 * k] = w1.x; z1[4 * k + 1] = w1.y; z1[4 * k + 2] = w1.z; z1[4 * k + 3] = w1.w;
-                    q[4 * k] = wq.x; q[4 * k + 1] = wq.y; q[4 * k + 2] = wq.z; q[4 * k + 3] = wq.w;
                 }
 #pragma unroll
                 for (int j = 0; j < 16; ++j) {
-                    acc0 = mfma32(z0[j], q[j], acc0);
-                    acc1 = mfma32(z1[j], q[j], acc1);
+                    acc0 = mfma32(z0[j], q[u][j], acc0);
+                    acc1 = mfma32(z1[j], q[u][j], acc1);
                 }
             }
         }
@@ -430,14 +439,32 @@ __device__ __forceinline__ void lr_apply_body(const TensorDev &d, const TensorPt
     const int chunk = lane & 7, trow = lane >> 3;           // row-major side: 8 chunks of 8 channels, 8 tokens per sweep
     for (int sub0 = sub_lo; sub0 < n_sub; sub0 += 2) {
         const int cnt = n_sub - sub0 < 2 ? 1 : 2;
+        // Issue order matters because loads return in order: first the V rows the MFMAs need, then the
+        // tile's x and recon, which are only needed once D has come back through the patch.
+        float vv[2][16];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) factor16<DT>(V, (int64_t)(sub0 + (c < cnt ? c : 0)) * 32 + n, h, true, vv[c]);
+        Raw8<DT> xr[4], br[4];
+        bool live[4];
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int64_t tok = tok_base + trow + 8 * it;
+            live[it] = tok < d.n_tokens && chunk * 8 < cnt * 32;
+            const int64_t e0 = tok * C + (int64_t)sub0 * 32 + chunk * 8;
+            if (live[it]) {
+                br[it].load(p.recon, e0);
+                if (SENDER) xr[it].load(p.x, e0); else xr[it].zero();
+            } else {
+                br[it].zero();
+                xr[it].zero();
+            }
+        }
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
             if (c < cnt) {                                  // uniform over the wave
-                float vv[16];
-                factor16<DT>(V, (int64_t)(sub0 + c) * 32 + n, h, true, vv);
                 f32x16 acc = {};
 #pragma unroll
-                for (int j = 0; j < 16; ++j) acc = mfma32(u[j], vv[j], acc);
+                for (int j = 0; j < 16; ++j) acc = mfma32(u[j], vv[c][j], acc);
 #pragma unroll
                 for (int i = 0; i < 16; ++i) patch[(8 * (i >> 2) + 4 * h + (i & 3)) * kApplyPitch + c * 32 + n] = acc[i];
             }
@@ -447,20 +474,16 @@ __device__ __forceinline__ void lr_apply_body(const TensorDev &d, const TensorPt
         for (int it = 0; it < 4; ++it) {
             const int tl = trow + 8 * it;
             const int64_t tok = tok_base + tl;
-            if (tok < d.n_tokens && chunk * 8 < cnt * 32) {
+            if (live[it]) {
                 const f32x4 *src = reinterpret_cast<const f32x4 *>(patch + tl * kApplyPitch + chunk * 8);
                 const f32x4 d0 = src[0], d1 = src[1];
                 F8 D;
                 D.v[0] = d0.x; D.v[1] = d0.y; D.v[2] = d0.z; D.v[3] = d0.w;
                 D.v[4] = d1.x; D.v[5] = d1.y; D.v[6] = d1.z; D.v[7] = d1.w;
                 const int64_t e0 = tok * C + (int64_t)sub0 * 32 + chunk * 8;
-                Raw8<DT> br;
-                br.load(p.recon, e0);
-                const F8 b = br.widen();
+                const F8 b = br[it].widen();
                 if (SENDER) {
-                    Raw8<DT> xr;
-                    xr.load(p.x, e0);
-                    const F8 x = xr.widen();
+                    const F8 x = xr[it].widen();
                     F8 lost;
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
