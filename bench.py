@@ -44,6 +44,7 @@ def parse_args():
     ap.add_argument("--tensors", type=int, default=0, help="override the workload's tensor count (exploration only)")
     ap.add_argument("--scale", default="", choices=("", "channel", "group", "rank1", "nm", "lowrank"), help="override the workload's scale kind (exploration only)")
     ap.add_argument("--bits", type=int, default=0, help="override the workload's code width (exploration only)")
+    ap.add_argument("--split", action="store_true", help="time cf_compress + cf_decompress (sender and receiver halves) instead of cf_step_fused (exploration only)")
     ap.add_argument("--sub-batch", type=int, default=0, help="issue the step as calls over ranges of this many tensors (exploration only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
@@ -182,11 +183,23 @@ def run_workload(name: str, args, events: HipEvents | None):
         sub_ptrs = [[(lo, hi - lo, sl(pr, lo, hi), sl(sess.p_recon, lo, hi), sl(sess.p_err, lo, hi),
                       sl(sess.p_codes, lo, hi), sl(sess.p_scales, lo, hi)) for lo, hi in ranges] for pr in p_ring]
 
-    def step(k):
+    def step(k, on_call=None):
+        """on_call(i): called before the i-th entry-point call of the step (the instrumented pass arms its events there)."""
+        if on_call is None:
+            on_call = lambda i: None
         if sub:
             for lo, cnt, px, pr, pe, pc, ps in sub_ptrs[order[k % len(order)]]:
                 cf.cf_step_fused(sess.ctx, lo, cnt, px, pr, pe, pc, ps, sess.stream_handle)
             return
+        if args.split:
+            on_call(0)
+            cf.cf_compress(sess.ctx, 0, sess.n, p_ring[order[k % len(order)]], sess.p_recon, sess.p_err,
+                           sess.p_codes, sess.p_scales, sess.stream_handle)
+            on_call(1)
+            cf.cf_decompress(sess.ctx, 0, sess.n, sess.p_codes, sess.p_scales, sess.p_recon, sess.stream_handle)
+            on_call(2)
+            return
+        on_call(0)
         cf.cf_step_fused(sess.ctx, 0, sess.n, p_ring[order[k % len(order)]], sess.p_recon, sess.p_err,
                          sess.p_codes, sess.p_scales, sess.stream_handle)
 
@@ -217,18 +230,33 @@ def run_workload(name: str, args, events: HipEvents | None):
     # second, instrumented pass: HIP events around every kernel the library launches, on its stream
     if events is not None:
         n_prof = min(args.steps, 10)
-        sets = [events.create(32) for _ in range(n_prof)]
-        names = []
+        # one event set per entry-point call (a split step makes two; a sub-batched one is not instrumented per call)
+        sets = [[events.create(32) for _ in range(2)] for _ in range(n_prof)]
+        names = [[[], []] for _ in range(n_prof)]
         for s in range(n_prof):
-            cf.cf_profile_next_call(sess.ctx, sets[s], 16)
-            step(k); k += 1
-            n_launch = min(cf.cf_profile_launch_count(sess.ctx), 16)
-            names.append([cf.cf_profile_kernel_name(sess.ctx, i) for i in range(n_launch)])
+            def on_call(i, s=s):
+                if i > 0:           # collect the names of the call that just ended
+                    n_launch = min(cf.cf_profile_launch_count(sess.ctx), 16)
+                    names[s][i - 1] = [cf.cf_profile_kernel_name(sess.ctx, j) for j in range(n_launch)]
+                if i < 2 and (i == 0 or args.split):
+                    cf.cf_profile_next_call(sess.ctx, sets[s][i], 16)
+            if sub:
+                cf.cf_profile_next_call(sess.ctx, sets[s][0], 16)
+                step(k)
+            else:
+                step(k, on_call)
+                if not args.split:
+                    on_call(1)
+            k += 1
+            if sub:
+                n_launch = min(cf.cf_profile_launch_count(sess.ctx), 16)
+                names[s][0] = [cf.cf_profile_kernel_name(sess.ctx, j) for j in range(n_launch)]
         torch.cuda.synchronize()
         per_kernel = {}
         for s in range(n_prof):
-            for i, nm in enumerate(names[s]):
-                per_kernel.setdefault(nm, []).append(events.elapsed_ms(sets[s][2 * i], sets[s][2 * i + 1]))
+            for c in range(2):
+                for i, nm in enumerate(names[s][c]):
+                    per_kernel.setdefault(nm, []).append(events.elapsed_ms(sets[s][c][2 * i], sets[s][c][2 * i + 1]))
         res["kernel_ms"] = {nm: sum(v) / len(v) for nm, v in per_kernel.items()}
         res["kernel_launches_per_step"] = {nm: len(v) / n_prof for nm, v in per_kernel.items()}
     sess.close()

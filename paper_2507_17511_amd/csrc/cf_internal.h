@@ -57,6 +57,11 @@ struct alignas(16) TensorDev {
     int32_t ew_rows;
     int32_t ew_n_rowblocks; // ceil(N / ew_rows)
     uint32_t ew_tile_begin;
+    // the receiver's kernel does less per row and likes taller tiles: dec_rows x 1024 channels
+    int32_t dec_rows;
+    int32_t dec_n_rowblocks;
+    uint32_t dec_tile_begin;
+    uint32_t dec_pad_;
     // rank-1 scales: per-row sums of |z| over each 1024-channel tile, rowpart[N][n_colblocks]
     uint32_t r1_pad_;
     uint64_t rowpart_off;
@@ -83,6 +88,7 @@ struct BatchView {
     const TensorPtrs *ptrs;     // [n_tensors]
     const uint32_t *tile_prefix;    // [n_tensors + 1] reduction tiles
     const uint32_t *ew_prefix;      // [n_tensors + 1] element-wise tiles
+    const uint32_t *dec_prefix;     // [n_tensors + 1] decode tiles
     const uint32_t *fin_prefix;     // [n_tensors + 1]
     const uint32_t *item_prefix;    // [n_tensors + 1] items of the single-pass path
     uint32_t *error_flag;           // set when a bounded wait expired
@@ -94,6 +100,7 @@ struct LaunchRange {
     int32_t first, count;       // tensors
     uint32_t tile_lo, tile_hi;  // reduction tiles of [first, first+count)
     uint32_t ew_lo, ew_hi;      // element-wise tiles
+    uint32_t dec_lo, dec_hi;    // decode tiles
     uint32_t fin_lo, fin_hi;    // finalise blocks
     uint32_t item_lo, item_hi;  // single-pass items
     uint64_t p_partial_lo, p_partial_hi;    // workspace bytes holding the single-pass partials of the range

@@ -33,20 +33,30 @@ struct TileCtx {
 // dtype's code is then not even compiled in, which keeps the register count down), 2 when mixed.
 template <int DTS> __device__ __forceinline__ bool is_bf16(const TensorDev &d) { return DTS == 2 ? d.dtype == BF16 : DTS == BF16; }
 
-// EW: element-wise tiling (short tiles), else the reduction tiling.
-template <bool EW>
-__device__ __forceinline__ TileCtx locate_tile(const BatchView &v, const LaunchRange &r)
+// Which tiling of a tensor a kernel walks: the reduction's, the element-wise one (short tiles) or the receiver's.
+constexpr int TILES_REDUCE = 0, TILES_EW = 1, TILES_DECODE = 2;
+
+template <int KIND>
+__device__ __forceinline__ TileCtx locate_tile_of(const BatchView &v, const LaunchRange &r)
 {
-    uint32_t tile = (EW ? r.ew_lo : r.tile_lo) + blockIdx.x;
-    int t = find_slot(EW ? v.ew_prefix : v.tile_prefix, r.first, r.first + r.count, tile);
+    const uint32_t lo = KIND == TILES_EW ? r.ew_lo : KIND == TILES_DECODE ? r.dec_lo : r.tile_lo;
+    const uint32_t *prefix = KIND == TILES_EW ? v.ew_prefix : KIND == TILES_DECODE ? v.dec_prefix : v.tile_prefix;
+    uint32_t tile = lo + blockIdx.x;
+    int t = find_slot(prefix, r.first, r.first + r.count, tile);
     TileCtx c;
     c.d = v.descs[t];
     c.p = v.ptrs[t];
-    uint32_t local = tile - (EW ? c.d.ew_tile_begin : c.d.tile_begin);
+    uint32_t local = tile - (KIND == TILES_EW ? c.d.ew_tile_begin : KIND == TILES_DECODE ? c.d.dec_tile_begin : c.d.tile_begin);
     c.colblock = (int)(local % (uint32_t)c.d.n_colblocks);
     c.rowblock = (int)(local / (uint32_t)c.d.n_colblocks);
-    c.rows = EW ? c.d.ew_rows : c.d.rb_rows;
+    c.rows = KIND == TILES_EW ? c.d.ew_rows : KIND == TILES_DECODE ? c.d.dec_rows : c.d.rb_rows;
     return c;
+}
+
+template <bool EW>
+__device__ __forceinline__ TileCtx locate_tile(const BatchView &v, const LaunchRange &r)
+{
+    return locate_tile_of<EW ? TILES_EW : TILES_REDUCE>(v, r);
 }
 
 // ---------------------------------------------------------------- a0 warm-up
@@ -528,20 +538,38 @@ __device__ __forceinline__ void nm_decode_tile(const TileCtx &c, bool replace)
     const int64_t C = d.n_channels;
     constexpr int kValueBytes = KEEP * (DT == BF16 ? 2 : 4);
     const uint8_t *values = p.codes + ((d.n_tokens * d.n_chunks + 15) / 16) * 16;
-    for (int64_t i = row0; i < row1; ++i) {
-        Raw8<DT> br;
-        if (!replace) br.load(p.recon, i * C + (int64_t)chunk * kChunk); else br.zero();
-        const uint32_t mask = load_codes<1>(p.codes + i * d.n_chunks, chunk);
-        uint32_t vals[KEEP];
-        nm_load_values<DT, KEEP>(values + (i * d.n_chunks + chunk) * kValueBytes, vals);
-        F8 dq, nb;
-        nm_scatter8<DT, KEEP>(mask, vals, dq);
-        const F8 b = br.widen();
+    constexpr int U = 2;                                    // rows loaded together, then stored together
+    for (int64_t i0 = row0; i0 < row1; i0 += U) {
+        Raw8<DT> br[U];
+        uint32_t mask[U];
+        uint32_t vals[U][KEEP];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) nb.v[k] = replace ? dq.v[k] : b.v[k] + dq.v[k];
-        Raw8<DT> out;
-        out.narrow(nb);
-        out.store(p.recon, i * C + (int64_t)chunk * kChunk);
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = i0 + u;
+            if (i < row1) {
+                if (!replace) br[u].load(p.recon, i * C + (int64_t)chunk * kChunk); else br[u].zero();
+                mask[u] = load_codes<1>(p.codes + i * d.n_chunks, chunk);
+                nm_load_values<DT, KEEP>(values + (i * d.n_chunks + chunk) * kValueBytes, vals[u]);
+            } else {
+                br[u].zero();
+                mask[u] = 0;
+#pragma unroll
+                for (int q = 0; q < KEEP; ++q) vals[u][q] = 0;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = i0 + u;
+            if (i >= row1) break;                           // uniform over the workgroup
+            F8 dq, nb;
+            nm_scatter8<DT, KEEP>(mask[u], vals[u], dq);
+            const F8 b = br[u].widen();
+#pragma unroll
+            for (int k = 0; k < 8; ++k) nb.v[k] = replace ? dq.v[k] : b.v[k] + dq.v[k];
+            Raw8<DT> out;
+            out.narrow(nb);
+            out.store(p.recon, i * C + (int64_t)chunk * kChunk);
+        }
     }
 }
 
@@ -567,7 +595,7 @@ template <int DT> __device__ __forceinline__ void decode_dispatch(const TileCtx 
 template <int DTS>
 __global__ __launch_bounds__(kTileThreads) void k_decode(BatchView v, LaunchRange r)
 {
-    TileCtx c = locate_tile<true>(v, r);
+    TileCtx c = locate_tile_of<TILES_DECODE>(v, r);
     if (c.d.scale == LOWRANK) return;
     if (is_bf16<DTS>(c.d)) decode_dispatch<BF16>(c, r.naive != 0); else decode_dispatch<F32>(c, r.naive != 0);
 }
@@ -659,7 +687,7 @@ hipError_t launch_encode(const BatchView &v, const LaunchRange &r, int ef, int e
 
 hipError_t launch_decode(const BatchView &v, const LaunchRange &r, hipStream_t s)
 {
-    dim3 grid(r.ew_hi - r.ew_lo), block(kTileThreads);
+    dim3 grid(r.dec_hi - r.dec_lo), block(kTileThreads);
     if (grid.x == 0) return hipSuccess;
     if (r.dts == 0) hipLaunchKernelGGL(k_decode<0>, grid, block, 0, s, v, r);
     else if (r.dts == 1) hipLaunchKernelGGL(k_decode<1>, grid, block, 0, s, v, r);
