@@ -141,6 +141,35 @@ def test_lowrank_exact_for_residuals_of_small_rank():
         sess.close()
 
 
+def test_lowrank_four_iterations_and_zero_residual():
+    """T = 4 (the basis is re-orthogonalised after every product, so the conditioning does not compound), and an
+    unchanged tensor: A = 0 gives Z = 0, every column is dropped, the factors and D are zero and the state stays."""
+    n, c = 300, 1024
+    d = cf.desc(n, c, cf.CF_BF16, 4, cf.CF_LOWRANK, R)
+    cfg = lr.LowRankConfig(n, c, dtype=lr.BF16, rank=R, iters=4)
+    xs = stream(n, c, cf.CF_BF16, 3, 77)
+    q0s = start_matrices(c, 4, 78)
+    sess = CodecSession([d], cf.options(), device=DEV)
+    try:
+        sess.warmup([xs[0]])
+        for s in (1, 2):
+            before = as_numpy(sess.recon[0]).copy()
+            sess.scales[0].copy_(q0s[s].reshape(-1))
+            sess.step_fused([xs[s]])
+            cf.cf_check_device(sess.ctx, sess.stream_handle)
+            check_step(f"T4 step {s}", cfg, sess, 0, as_numpy(xs[s]), before, as_numpy(q0s[s]))
+        # now feed the reconstruction itself: the residual is exactly zero
+        same = sess.recon[0].clone()
+        sess.scales[0].copy_(q0s[3].reshape(-1))
+        sess.step_fused([same])
+        cf.cf_check_device(sess.ctx, sess.stream_handle)
+        U, V = split_wire(as_numpy(sess.codes[0]), n, c, cf.CF_BF16)
+        assert not U.any() and not V.any()
+        assert torch.equal(sess.recon[0], same) and not bool(sess.err[0].any())
+    finally:
+        sess.close()
+
+
 def test_lowrank_in_a_mixed_batch_and_receiver():
     """Low-rank tensors next to quantised and sparsified ones in one call; a receiver fed the wire reaches the
     sender's reconstruction bit for bit (both ends add the same D)."""

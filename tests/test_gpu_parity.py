@@ -508,6 +508,18 @@ def test_parity_nm_ef_modes_err_dtypes_heights(ef):
                 run_parity([d], cf.options(ef=ef, err_dtype=err_dtype, encode_rows=encode_rows), [[x] for x in xs])
 
 
+def test_parity_nm_zero_residual():
+    """An unchanged tensor: every magnitude in a block ties at zero, the lowest channels are 'kept' with value 0,
+    D = 0, and the state stays as it is."""
+    n, c = 130, 1152
+    x = drift_stream((n, c), cf.CF_BF16, steps=1, seed=5, device=DEV)[0]
+    for keep in (1, 2, 4):
+        say(f"nm zero residual keep={keep}")
+        sess, orc = run_parity([cf.desc(n, c, cf.CF_BF16, keep, NMK, 8)], cf.options(), [[x], [x], [x]], tag="nm zero")
+        masks = orc.codes[0][:n * c // 8]
+        assert np.all(masks == (1 << keep) - 1) and not orc.codes[0][(n * c // 8 + 15) // 16 * 16:].any()
+
+
 def test_parity_nm_in_a_mixed_batch():
     """Sparsified tensors share a batch with quantised ones, with and without the single-pass kernel
     taking the channel-scaled tensors."""
