@@ -123,7 +123,8 @@ typedef struct {
     int64_t n_channels; /* C >= 8, multiple of 8 (and of group for CF_SCALE_GROUP) */
     int32_t dtype;      /* cf_dtype of x and recon */
     int32_t bits;       /* 1, 2 or 4 (CF_SPARSE_NM: values kept per block; CF_LOWRANK: subspace iterations) */
-    int32_t scale;      /* cf_scale_kind; supported pairs: (1|2|4, CHANNEL), (4, GROUP), (1|2, RANK1) */
+    int32_t scale;      /* cf_scale_kind; supported (bits, scale): (1|2|4, CHANNEL), (4, GROUP), (1|2, RANK1),
+                           (1|2|4, SPARSE_NM), (1|2|4, LOWRANK) */
     int32_t group;      /* 128 when scale == CF_SCALE_GROUP, 8 when CF_SPARSE_NM, 32 when CF_LOWRANK, ignored otherwise */
 } cf_tensor_desc;
 

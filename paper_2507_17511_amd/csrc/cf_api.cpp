@@ -1,9 +1,10 @@
 // C-ABI layer of the residual codec: argument validation, workspace layout,
 // per-call pointer tables and kernel sequencing.  No arithmetic of the method
-// happens here; see cf_kernels.hip.  Declarations and their citations of
+// happens here; see cf_kernels.hip, cf_single_pass.hip and cf_lowrank.hip.  Declarations and their citations of
 // arxiv 2507.17511 are in include/compactfusion.h.
 #include "compactfusion.h"
 
+#include <cstdint>
 #include <cstring>
 #include <new>
 #include <vector>
