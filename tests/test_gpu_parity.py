@@ -130,6 +130,24 @@ def test_single_pass_looping_grid():
     run_parity(descs, cf.options(flags=cf.CF_FLAG_SINGLE_PASS), xs, mode="fused")
 
 
+@pytest.mark.parametrize("case", [0, 1, 2, 3])
+def test_single_pass_random_shapes(case):
+    """Seeded random batches: token counts that leave ragged items (items are 512 rows of bf16, 256 of fp32),
+    channel counts that leave ragged stripes (64 channels) and ragged lane quads, mixed dtypes and widths."""
+    rng = np.random.default_rng(1000 + case)
+    descs = []
+    for t in range(7):
+        n = int(rng.integers(1, 2600))
+        c = 8 * int(rng.integers(1, 260))
+        descs.append(cf.desc(n, c, int(rng.integers(0, 2)), (1, 2, 4)[int(rng.integers(0, 3))], CH))
+    say("single pass, random shapes: " + ", ".join(f"[{d.n_tokens},{d.n_channels}]{'bf16' if d.dtype else 'f32'}/{d.bits}" for d in descs))
+    streams = [drift_stream((int(d.n_tokens), int(d.n_channels)), int(d.dtype), steps=3, seed=1100 + 10 * case + k, device=DEV)
+               for k, d in enumerate(descs)]
+    xs = [[streams[t][s] for t in range(len(descs))] for s in range(3)]
+    for mode in ("fused", "split"):
+        run_parity(descs, cf.options(flags=cf.CF_FLAG_SINGLE_PASS), xs, mode=mode)
+
+
 def test_subrange_calls_match_whole_batch():
     """Calling [first, first+count) pieces, in any order, equals one whole-batch call."""
     say("subrange")
