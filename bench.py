@@ -9,9 +9,13 @@ every output written once, per element
     x + recon(read) + recon(write) + err(write) + bits/8 + scales,
 divided by the wall time of a step; it is reported against the 8 TB/s HBM peak.
 
-Prints ONE JSON line (see README for the fields).  Inputs are seeded
-synthetic activation streams (workloads/), standing in for FLUX.1-dev and
-CogVideoX-2b activations.
+Prints ONE JSON line: metric, value (GB/s), ms_per_step, config, per-kernel times
+from HIP events, `roofline` (the dominant kernel: its algorithmic bytes per launch
+over its measured duration against the HBM peak, plus the HBM traffic a committed
+rocprofv3 counter run recorded for it), `cpu_baseline` (the CPU oracle on a bounded
+sample) and, with the default --workload all, one entry per configuration.  Inputs
+are seeded synthetic activation streams (workloads/), standing in for FLUX.1-dev
+and CogVideoX-2b activations.
 """
 from __future__ import annotations
 
