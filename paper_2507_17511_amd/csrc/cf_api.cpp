@@ -20,8 +20,8 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
     size_t off_descs = 0, off_ptrs = 0, off_tile_prefix = 0, off_fin_prefix = 0, off_partials = 0;
-    size_t off_item_prefix = 0, off_error = 0, off_p_partials = 0;
-    std::vector<uint32_t> item_prefix;
+    size_t off_item_prefix = 0, off_item_tensor = 0, off_error = 0, off_p_partials = 0;
+    std::vector<uint32_t> item_prefix, item_tensor;
     int32_t max_group_items = 0;   // largest reduction group of the single-pass path
     bool single_pass = false;      // every channel-scale tensor has single-pass geometry
     size_t total = 0;
@@ -204,6 +204,10 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     L.off_dec_prefix = off;   off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
     L.off_partials = off;     off = align_up(off + partial_bytes);
     L.off_item_prefix = off;  off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
+    L.off_item_tensor = off;  off = align_up(off + sizeof(uint32_t) * (size_t)items);
+    L.item_tensor.resize((size_t)items);
+    for (int32_t t = 0; t < n; ++t)
+        for (uint32_t i = L.item_prefix[t]; i < L.item_prefix[t + 1]; ++i) L.item_tensor[i] = (uint32_t)t;
     L.off_error = off;        off = align_up(off + sizeof(uint32_t));
     L.off_p_partials = off;   off = align_up(off + p_partial_bytes);
     L.total = off;
@@ -254,6 +258,7 @@ struct cf_ctx {
         v.ew_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_ew_prefix);
         v.dec_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_dec_prefix);
         v.item_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_item_prefix);
+        v.item_tensor = reinterpret_cast<const uint32_t *>(ws + L.off_item_tensor);
         v.error_flag = reinterpret_cast<uint32_t *>(ws + L.off_error);
         v.workspace = ws;
         v.n_tensors = (int32_t)descs.size();
@@ -624,6 +629,9 @@ cf_status cf_init(cf_ctx **out, const cf_tensor_desc *descs, int32_t n_tensors, 
     if (e == hipSuccess)
         e = hipMemcpyAsync(ctx->ws + ctx->L.off_item_prefix, ctx->L.item_prefix.data(),
                            sizeof(uint32_t) * (size_t)(n_tensors + 1), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess && !ctx->L.item_tensor.empty())
+        e = hipMemcpyAsync(ctx->ws + ctx->L.off_item_tensor, ctx->L.item_tensor.data(),
+                           sizeof(uint32_t) * ctx->L.item_tensor.size(), hipMemcpyHostToDevice, s);
     if (e == hipSuccess)
         e = hipMemsetAsync(ctx->ws + ctx->L.off_ptrs, 0, sizeof(TensorPtrs) * (size_t)n_tensors, s);
     if (e == hipSuccess)

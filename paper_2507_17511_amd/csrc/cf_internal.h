@@ -91,6 +91,7 @@ struct BatchView {
     const uint32_t *dec_prefix;     // [n_tensors + 1] decode tiles
     const uint32_t *fin_prefix;     // [n_tensors + 1]
     const uint32_t *item_prefix;    // [n_tensors + 1] items of the single-pass path
+    const uint32_t *item_tensor;    // [n_items] tensor of every item: one load where a search over the prefix would be seven
     uint32_t *error_flag;           // set when a bounded wait expired
     uint8_t *workspace;
     int32_t n_tensors;

@@ -248,7 +248,7 @@ __global__ __launch_bounds__(kPersistThreads, 2) void k_single_pass(BatchView v,
     const uint32_t q = gridDim.x >> 3, rem = gridDim.x & 7u, xcd = blockIdx.x & 7u;
     const uint32_t vb = xcd * q + (xcd < rem ? xcd : rem) + (blockIdx.x >> 3);
     for (uint32_t item = r.item_lo + vb; item < r.item_hi; item += gridDim.x) {
-        const int t = find_slot(v.item_prefix, r.first, r.first + r.count, item);
+        const int t = (int)v.item_tensor[item];
         const TensorDev d = v.descs[t];                             // by value: scalar registers, never re-read
         const TensorPtrs p = v.ptrs[t];
         const uint32_t local = item - d.p_item_begin;               // group-major: stripe, then row block
