@@ -46,6 +46,7 @@ def parse_args():
     ap.add_argument("--tile-rows", type=int, default=0)
     ap.add_argument("--encode-rows", type=int, default=0)
     ap.add_argument("--tensors", type=int, default=0, help="override the workload's tensor count (exploration only)")
+    ap.add_argument("--nm-block", type=int, default=8, choices=(8, 16), help="with --scale nm: channels per block")
     ap.add_argument("--scale", default="", choices=("", "channel", "group", "rank1", "nm", "lowrank"), help="override the workload's scale kind (exploration only)")
     ap.add_argument("--bits", type=int, default=0, help="override the workload's code width (exploration only)")
     ap.add_argument("--split", action="store_true", help="time cf_compress + cf_decompress (sender and receiver halves) instead of cf_step_fused (exploration only)")
@@ -108,8 +109,8 @@ def bytes_per_element(wl, bits: int, ef: int, err_bytes: int = 4) -> float:
 
 
 def code_bytes_per_element(wl, bits: int) -> float:
-    if wl.scale == "nm":                                # a mask byte and `bits` values per block of 8
-        return (1 + bits * (4 if wl.dtype == "f32" else 2)) / 8.0
+    if wl.scale == "nm":                                # a mask bit per channel and `bits` values per block of `group`
+        return 1 / 8.0 + bits * (4 if wl.dtype == "f32" else 2) / float(wl.group)
     if wl.scale == "lowrank":                           # U [N, 32] and V [C, 32] in the storage dtype
         return (wl.n_tokens + wl.n_channels) * 32 * (4 if wl.dtype == "f32" else 2) / (wl.n_tokens * wl.n_channels)
     return bits / 8.0
@@ -136,7 +137,7 @@ def apply_overrides(wl, args):
     if args.tensors:
         wl = wl.scaled(n_tensors=args.tensors)
     if args.scale:
-        wl = wl.scaled(scale=args.scale, group={"nm": 8, "lowrank": 32}.get(args.scale, wl.group))
+        wl = wl.scaled(scale=args.scale, group={"nm": args.nm_block, "lowrank": 32}.get(args.scale, wl.group))
     if args.bits:
         wl = wl.scaled(bits=(args.bits,))
     return wl

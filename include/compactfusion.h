@@ -37,7 +37,7 @@
  *   codes with CF_SPARSE_NM: [N, C/8] mask bytes (bit m of byte k = channel 8k+m
  *              kept), then, from the next multiple of 16 bytes on (the bytes in
  *              between are never written), the kept values in
- *              `dtype`, token-major, `bits` per block of 8 channels in channel order
+ *              `dtype`, token-major, `bits` per block of `group` channels in channel order
  * x must not alias recon or err; codes and scales must alias nothing.
  *
  * Codes.  1-bit: bit = 1 for z < 0.  2-bit: bit1 = sign, bit0 = magnitude
@@ -85,7 +85,8 @@ typedef enum { CF_F32 = 0, CF_BF16 = 1 } cf_dtype;
  * single-pass flag is ignored for a context that holds such a tensor).
  *
  * CF_SPARSE_NM is not a scale but the other compressor of the paper's kernel set
- * (Sec. 3.4, N:M block sparsifier): of every `group` = 8 consecutive channels of a
+ * (Sec. 3.4, N:M block sparsifier): of every `group` = M in {8, 16} consecutive
+ * channels (C a multiple of M) of a
  * token the `bits` = N in {1, 2, 4} of largest magnitude are kept and travel in
  * `dtype` (bf16 values rounded to nearest even), the rest are dropped into the
  * error.  Magnitudes are ordered by the bit pattern of |z| (NaN above infinity),
@@ -125,7 +126,7 @@ typedef struct {
     int32_t bits;       /* 1, 2 or 4 (CF_SPARSE_NM: values kept per block; CF_LOWRANK: subspace iterations) */
     int32_t scale;      /* cf_scale_kind; supported (bits, scale): (1|2|4, CHANNEL), (4, GROUP), (1|2, RANK1),
                            (1|2|4, SPARSE_NM), (1|2|4, LOWRANK) */
-    int32_t group;      /* 128 when scale == CF_SCALE_GROUP, 8 when CF_SPARSE_NM, 32 when CF_LOWRANK, ignored otherwise */
+    int32_t group;      /* 128 when scale == CF_SCALE_GROUP, 8 or 16 when CF_SPARSE_NM, 32 when CF_LOWRANK, ignored otherwise */
 } cf_tensor_desc;
 
 typedef struct {

@@ -69,7 +69,8 @@ cf_status check_desc(const cf_tensor_desc &d)
         return CF_OK;
     }
     if (d.scale == CF_SPARSE_NM) {      // bits = N values kept of every group = M channels
-        if (d.group != 8) return CF_ERR_UNSUPPORTED;
+        if (d.group != 8 && d.group != 16) return CF_ERR_UNSUPPORTED;
+        if (d.n_channels % d.group != 0) return CF_ERR_SHAPE;
         return CF_OK;                   // bits in {1, 2, 4} was checked above
     }
     if (d.scale == CF_SCALE_RANK1) {
@@ -130,6 +131,7 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
         v.dtype = d.dtype;
         v.bits = d.bits;
         v.scale = d.scale;
+        v.nm_block = d.scale == CF_SPARSE_NM ? (uint32_t)d.group : 0u;
         v.rb_rows = rb;
         v.n_rowblocks = (int32_t)((d.n_tokens + rb - 1) / rb);
         v.n_colblocks = (v.n_chunks + kTileThreads - 1) / kTileThreads;
@@ -563,7 +565,8 @@ cf_status cf_sizes(const cf_tensor_desc *desc, const cf_options *opts, size_t *c
         if (codes_bytes) *codes_bytes = (n + c) * kLowRankRank * dtype_size(desc->dtype);
         if (scales_bytes) *scales_bytes = c * kLowRankRank * sizeof(float);
     } else if (desc->scale == CF_SPARSE_NM) {      // one mask byte per block of 8, then (16-byte aligned) bits values per block
-        if (codes_bytes) *codes_bytes = (n * (c / 8) + 15) / 16 * 16 + n * (c / 8) * (size_t)desc->bits * dtype_size(desc->dtype);
+        if (codes_bytes)
+            *codes_bytes = (n * (c / 8) + 15) / 16 * 16 + n * (c / (size_t)desc->group) * (size_t)desc->bits * dtype_size(desc->dtype);
         if (scales_bytes) *scales_bytes = 0;
     } else {
         if (codes_bytes) *codes_bytes = n * (c * (size_t)desc->bits / 8);

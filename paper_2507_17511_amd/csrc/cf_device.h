@@ -267,7 +267,9 @@ __device__ __forceinline__ F8 load_scales8(const float *scales, int64_t first)
 // the mask of the KEEP elements of largest magnitude (bit k = channel k).  Magnitudes are ordered
 // by the bit pattern of |z|, equal ones by channel: element k is kept iff fewer than KEEP elements
 // come before it.  28 comparisons, no cross-lane traffic.
-template <int KEEP> __device__ __forceinline__ uint32_t nm_select8(const F8 &z)
+// PAIR: the block is 16 channels, this lane's 8 and those of the lane next to it (lane ^ 1; the even lane
+// holds the lower channels); both lanes must be active.  The neighbour's magnitudes come over DPP.
+template <int KEEP, bool PAIR = false> __device__ __forceinline__ uint32_t nm_select8(const F8 &z)
 {
     uint32_t key[8];
     int before[8];
@@ -284,6 +286,42 @@ template <int KEEP> __device__ __forceinline__ uint32_t nm_select8(const F8 &z)
             before[k] += j_first ? 1 : 0;
             before[j] += j_first ? 0 : 1;
         }
+    if (PAIR) {
+        // Only a lane's own first KEEP can be among the block's first KEEP, and an element that some other
+        // element of the neighbour precedes is preceded by all of the neighbour's first KEEP too (or is out
+        // anyway), so the lanes exchange their first KEEP magnitudes only.  The receiver counts `theirs > mine`:
+        // the even lane's channels win ties, so it sends magnitude + 1 (at most 0x80000000, no wrap); a zero
+        // stands for "nothing" and precedes no one.
+        const uint32_t bias = (threadIdx.x & 1u) ? 0u : 1u;
+        int extra[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) extra[k] = 0;
+        if (KEEP <= 2) {
+            uint32_t first[KEEP];
+#pragma unroll
+            for (int q = 0; q < KEEP; ++q) first[q] = 0u;
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+#pragma unroll
+                for (int q = 0; q < KEEP; ++q) first[q] = before[k] == q ? key[k] + bias : first[q];
+#pragma unroll
+            for (int q = 0; q < KEEP; ++q) {
+                const uint32_t theirs = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)first[q], 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+#pragma unroll
+                for (int k = 0; k < 8; ++k) extra[k] += theirs > key[k] ? 1 : 0;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t send = before[j] < KEEP ? key[j] + bias : 0u;
+                const uint32_t theirs = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send, 0xB1, 0xF, 0xF, false);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) extra[k] += theirs > key[k] ? 1 : 0;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) before[k] += extra[k];
+    }
     uint32_t mask = 0;
 #pragma unroll
     for (int k = 0; k < 8; ++k) mask |= (before[k] < KEEP ? 1u : 0u) << k;
@@ -310,9 +348,10 @@ template <int DT, int KEEP> __device__ __forceinline__ void nm_values8(const F8 
 }
 
 // Receiver side: D from the mask and the travelled values.  Mask bits beyond the KEEP-th are ignored.
-template <int DT, int KEEP> __device__ __forceinline__ void nm_scatter8(uint32_t mask, const uint32_t (&vals)[KEEP], F8 &d)
+// `first`: how many of the block's values belong to lower channels than this lane's (16-channel blocks).
+template <int DT, int KEEP> __device__ __forceinline__ void nm_scatter8(uint32_t mask, const uint32_t (&vals)[KEEP], F8 &d, int first = 0)
 {
-    int r = 0;
+    int r = first;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
         const bool set = ((mask >> k) & 1u) && r < KEEP;

@@ -63,7 +63,7 @@ struct alignas(16) TensorDev {
     uint32_t dec_tile_begin;
     uint32_t dec_pad_;
     // rank-1 scales: per-row sums of |z| over each 1024-channel tile, rowpart[N][n_colblocks]
-    uint32_t r1_pad_;
+    uint32_t nm_block;      // N:M sparsifier: M, channels per block (8 or 16)
     uint64_t rowpart_off;
     // low-rank compressor: P = A Q [N][32], Z = A^T P [C][32], Q in the order k_lr_project reads it (all fp32)
     uint64_t lr_p_off, lr_z_off, lr_q_off;

@@ -368,7 +368,7 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
 
 // N:M block sparsifier (Sec. 3.4), blocks of 8 channels: one lane selects, packs and decodes its own
 // block; the row's mask bytes go where 1-bit codes would, the kept values behind all masks.
-template <int DT, int KEEP, int EF, int ET, bool FUSED>
+template <int DT, int KEEP, bool PAIR, int EF, int ET, bool FUSED>
 __device__ __forceinline__ void nm_encode_tile(const TileCtx &c)
 {
     const TensorDev &d = c.d;
@@ -406,12 +406,35 @@ __device__ __forceinline__ void nm_encode_tile(const TileCtx &c)
             const F8 b = br[u].widen();
             const F8 eold = er[u].widen();
             const F8 z = residual8<EF>(xr[u].widen(), b, eold);
-            const uint32_t mask = nm_select8<KEEP>(z);
+            const uint32_t mask = nm_select8<KEEP, PAIR>(z);
             uint32_t vals[KEEP];
             F8 dq;
             nm_values8<DT, KEEP>(z, mask, vals, dq);
             store_codes_wide<1>(p.codes + i * d.n_chunks, chunk, mask, wide);
-            nm_store_values<DT, KEEP>(values + (i * d.n_chunks + chunk) * kValueBytes, chunk, vals, wide);
+            if (PAIR) {
+                // the even lane writes the block: its own kept values, then the odd lane's
+                const int mine = __builtin_popcount(mask);
+                uint32_t theirs[KEEP], block[KEEP];
+#pragma unroll
+                for (int q = 0; q < KEEP; ++q) theirs[q] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)vals[q], 0xB1, 0xF, 0xF, false);
+#pragma unroll
+                for (int q = 0; q < KEEP; ++q) {
+                    uint32_t from_theirs = 0u;
+#pragma unroll
+                    for (int t = 0; t < KEEP; ++t) from_theirs = (q - mine == t) ? theirs[t] : from_theirs;
+                    block[q] = q < mine ? vals[q] : from_theirs;
+                }
+                uint8_t *dst = values + (i * (d.n_chunks >> 1) + (chunk >> 1)) * kValueBytes;
+                if (DT == BF16 && KEEP == 1 && wide) {
+                    // two blocks of a lane quad share one dword (whole quads are active: 32 | C)
+                    const uint32_t next = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)block[0], 0xAA, 0xF, 0xF, false);   // quad_perm [2,2,2,2]
+                    if ((chunk & 3) == 0) *gmut<uint32_t>(dst) = (block[0] & 0xFFFFu) | (next << 16);
+                } else if ((chunk & 1) == 0) {
+                    nm_store_values<DT, KEEP>(dst, chunk >> 1, block, false);
+                }
+            } else {
+                nm_store_values<DT, KEEP>(values + (i * d.n_chunks + chunk) * kValueBytes, chunk, vals, wide);
+            }
             const int64_t e = i * C + (int64_t)chunk * kChunk;
             F8 enew;
 #pragma unroll
@@ -440,9 +463,15 @@ __device__ __forceinline__ void encode_dispatch(const TileCtx &c)
 {
     const TensorDev &d = c.d;
     if (d.scale == SPARSE_NM) {
-        if (d.bits == 1) nm_encode_tile<DT, 1, EF, ET, FUSED>(c);
-        else if (d.bits == 2) nm_encode_tile<DT, 2, EF, ET, FUSED>(c);
-        else nm_encode_tile<DT, 4, EF, ET, FUSED>(c);
+        if (d.nm_block == 16) {
+            if (d.bits == 1) nm_encode_tile<DT, 1, true, EF, ET, FUSED>(c);
+            else if (d.bits == 2) nm_encode_tile<DT, 2, true, EF, ET, FUSED>(c);
+            else nm_encode_tile<DT, 4, true, EF, ET, FUSED>(c);
+        } else {
+            if (d.bits == 1) nm_encode_tile<DT, 1, false, EF, ET, FUSED>(c);
+            else if (d.bits == 2) nm_encode_tile<DT, 2, false, EF, ET, FUSED>(c);
+            else nm_encode_tile<DT, 4, false, EF, ET, FUSED>(c);
+        }
         return;
     }
     if (d.scale == SCALE_GROUP) { encode_tile<DT, 4, 1, EF, ET, FUSED>(c); return; }
@@ -526,7 +555,7 @@ __device__ __forceinline__ void decode_tile(const TileCtx &c, bool replace)
     }
 }
 
-template <int DT, int KEEP>
+template <int DT, int KEEP, bool PAIR>
 __device__ __forceinline__ void nm_decode_tile(const TileCtx &c, bool replace)
 {
     const TensorDev &d = c.d;
@@ -549,7 +578,8 @@ __device__ __forceinline__ void nm_decode_tile(const TileCtx &c, bool replace)
             if (i < row1) {
                 if (!replace) br[u].load(p.recon, i * C + (int64_t)chunk * kChunk); else br[u].zero();
                 mask[u] = load_codes<1>(p.codes + i * d.n_chunks, chunk);
-                nm_load_values<DT, KEEP>(values + (i * d.n_chunks + chunk) * kValueBytes, vals[u]);
+                if (PAIR) nm_load_values<DT, KEEP>(values + (i * (d.n_chunks >> 1) + (chunk >> 1)) * kValueBytes, vals[u]);
+                else nm_load_values<DT, KEEP>(values + (i * d.n_chunks + chunk) * kValueBytes, vals[u]);
             } else {
                 br[u].zero();
                 mask[u] = 0;
@@ -562,7 +592,12 @@ __device__ __forceinline__ void nm_decode_tile(const TileCtx &c, bool replace)
             const int64_t i = i0 + u;
             if (i >= row1) break;                           // uniform over the workgroup
             F8 dq, nb;
-            nm_scatter8<DT, KEEP>(mask[u], vals[u], dq);
+            int first = 0;
+            if (PAIR) {     // the odd lane's values come after the even lane's
+                const int lower = __builtin_popcount((uint32_t)__builtin_amdgcn_update_dpp(0, (int)mask[u], 0xB1, 0xF, 0xF, false));
+                first = (chunk & 1) ? lower : 0;
+            }
+            nm_scatter8<DT, KEEP>(mask[u], vals[u], dq, first);
             const F8 b = br[u].widen();
 #pragma unroll
             for (int k = 0; k < 8; ++k) nb.v[k] = replace ? dq.v[k] : b.v[k] + dq.v[k];
@@ -577,9 +612,15 @@ template <int DT> __device__ __forceinline__ void decode_dispatch(const TileCtx 
 {
     const TensorDev &d = c.d;
     if (d.scale == SPARSE_NM) {
-        if (d.bits == 1) nm_decode_tile<DT, 1>(c, replace);
-        else if (d.bits == 2) nm_decode_tile<DT, 2>(c, replace);
-        else nm_decode_tile<DT, 4>(c, replace);
+        if (d.nm_block == 16) {
+            if (d.bits == 1) nm_decode_tile<DT, 1, true>(c, replace);
+            else if (d.bits == 2) nm_decode_tile<DT, 2, true>(c, replace);
+            else nm_decode_tile<DT, 4, true>(c, replace);
+        } else {
+            if (d.bits == 1) nm_decode_tile<DT, 1, false>(c, replace);
+            else if (d.bits == 2) nm_decode_tile<DT, 2, false>(c, replace);
+            else nm_decode_tile<DT, 4, false>(c, replace);
+        }
         return;
     }
     if (d.scale == SCALE_GROUP) { decode_tile<DT, 4, 1>(c, replace); return; }

@@ -123,10 +123,14 @@ def test_calls_on_null_context_fail_cleanly():
 
 
 def test_nm_sizes_and_block_lengths():
-    for group in (4, 16, 32):
+    for group in (4, 32):
         with pytest.raises(cf.CFError) as ei:
             cf.cf_sizes(cf.desc(16, 64, cf.CF_BF16, 2, cf.CF_SPARSE_NM, group))
         assert ei.value.status == cf.CF_ERR_UNSUPPORTED
+    with pytest.raises(cf.CFError) as ei:
+        cf.cf_sizes(cf.desc(16, 72, cf.CF_BF16, 2, cf.CF_SPARSE_NM, 16))       # 72 channels are not whole blocks of 16
+    assert ei.value.status == cf.CF_ERR_SHAPE
+    assert cf.cf_sizes(cf.desc(4096, 3072, cf.CF_BF16, 2, cf.CF_SPARSE_NM, 16))[0] == 4096 * 192 * (2 + 4)
     codes, scales, recon, err = cf.cf_sizes(cf.desc(4096, 3072, cf.CF_BF16, 2, cf.CF_SPARSE_NM, 8))
     assert scales == 0 and codes == 4096 * 384 * (1 + 4)           # 16-byte blocks travel as 5 bytes
     assert cf.cf_sizes(cf.desc(3, 8, cf.CF_F32, 1, cf.CF_SPARSE_NM, 8))[0] == 16 + 3 * 4

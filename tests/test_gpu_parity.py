@@ -496,16 +496,20 @@ def tie_stream(shape, dtype, steps, seed):
     return out
 
 
+@pytest.mark.parametrize("block", [8, 16])
 @pytest.mark.parametrize("keep", [1, 2, 4])
 @pytest.mark.parametrize("dtype", [cf.CF_BF16, cf.CF_F32])
 @pytest.mark.parametrize("mode", ["fused", "split"])
-def test_parity_nm_shapes(keep, dtype, mode):
+def test_parity_nm_shapes(keep, dtype, mode, block):
     """Masks, kept values, error and reconstruction, on continuous drifts and on drifts full of ties;
-    channel counts with (1152, 3072) and without (1096, 8) whole quads of lanes."""
-    for k, (n, c) in enumerate(SHAPES + [(33, 1152)]):
+    channel counts with (1152, 3072) and without (1096, 8; 16-channel blocks: 1104, 16) whole quads of lanes."""
+    shapes = SHAPES + [(33, 1152)]
+    if block == 16:
+        shapes = [s for s in shapes if s[1] % 16 == 0] + [(203, 1104), (9, 16), (131, 48)]
+    for k, (n, c) in enumerate(shapes):
         for maker in (drift_stream_local, tie_stream):
-            say(f"nm keep={keep} dtype={dtype} mode={mode} N={n} C={c} {maker.__name__}")
-            d = cf.desc(n, c, dtype, keep, NMK, 8)
+            say(f"nm keep={keep} of {block} dtype={dtype} mode={mode} N={n} C={c} {maker.__name__}")
+            d = cf.desc(n, c, dtype, keep, NMK, block)
             xs = maker((n, c), dtype, 4, 700 + k)
             run_parity([d], cf.options(), [[x] for x in xs], mode=mode, tag=f"nm N{n}C{c}")
 
@@ -516,12 +520,12 @@ def drift_stream_local(shape, dtype, steps, seed):
 
 @pytest.mark.parametrize("ef", [cf.CF_EF_RECON, cf.CF_EF_LITERAL, cf.CF_EF_OFF, cf.CF_EF_NAIVE])
 def test_parity_nm_ef_modes_err_dtypes_heights(ef):
-    n, c = 203, 1096
     for err_dtype in (cf.CF_F32, cf.CF_BF16):
         for encode_rows in (0, 3, 64):
-            for keep, dtype in ((1, cf.CF_BF16), (2, cf.CF_BF16), (4, cf.CF_F32)):
-                say(f"nm ef={ef} err_dtype={err_dtype} encode_rows={encode_rows} keep={keep} dtype={dtype}")
-                d = cf.desc(n, c, dtype, keep, NMK, 8)
+            for keep, dtype, block in ((1, cf.CF_BF16, 8), (2, cf.CF_BF16, 8), (4, cf.CF_F32, 8), (2, cf.CF_BF16, 16), (4, cf.CF_F32, 16)):
+                n, c = (203, 1096) if block == 8 else (203, 1104)
+                say(f"nm ef={ef} err_dtype={err_dtype} encode_rows={encode_rows} keep={keep} of {block} dtype={dtype}")
+                d = cf.desc(n, c, dtype, keep, NMK, block)
                 xs = drift_stream((n, c), dtype, steps=4, seed=31 + ef, device=DEV)
                 run_parity([d], cf.options(ef=ef, err_dtype=err_dtype, encode_rows=encode_rows), [[x] for x in xs])
 
@@ -536,13 +540,18 @@ def test_parity_nm_zero_residual():
         sess, orc = run_parity([cf.desc(n, c, cf.CF_BF16, keep, NMK, 8)], cf.options(), [[x], [x], [x]], tag="nm zero")
         masks = orc.codes[0][:n * c // 8]
         assert np.all(masks == (1 << keep) - 1) and not orc.codes[0][(n * c // 8 + 15) // 16 * 16:].any()
+        say(f"nm zero residual keep={keep} of 16")
+        sess, orc = run_parity([cf.desc(n, c, cf.CF_BF16, keep, NMK, 16)], cf.options(), [[x], [x], [x]], tag="nm zero 16")
+        masks = orc.codes[0][:n * c // 8].reshape(-1, 2)
+        assert np.all(masks[:, 0] == (1 << keep) - 1) and not masks[:, 1].any()
 
 
 def test_parity_nm_in_a_mixed_batch():
     """Sparsified tensors share a batch with quantised ones, with and without the single-pass kernel
     taking the channel-scaled tensors."""
     descs = [cf.desc(203, 1096, cf.CF_BF16, 2, NMK, 8), cf.desc(64, 256, cf.CF_F32, 4, GR), cf.desc(300, 1024, cf.CF_BF16, 1, CH),
-             cf.desc(67, 3072, cf.CF_F32, 1, NMK, 8), cf.desc(9, 8, cf.CF_BF16, 4, NMK, 8), cf.desc(130, 264, cf.CF_BF16, 2, CH)]
+             cf.desc(67, 3072, cf.CF_F32, 1, NMK, 8), cf.desc(9, 8, cf.CF_BF16, 4, NMK, 8), cf.desc(130, 264, cf.CF_BF16, 2, CH),
+             cf.desc(203, 1104, cf.CF_BF16, 2, NMK, 16), cf.desc(67, 3072, cf.CF_BF16, 1, NMK, 16)]
     streams = [drift_stream((int(d.n_tokens), int(d.n_channels)), int(d.dtype), 4, 60 + t, device=DEV) for t, d in enumerate(descs)]
     for flags in (0, cf.CF_FLAG_SINGLE_PASS, cf.CF_FLAG_TWO_KERNEL):
         for mode in ("fused", "split"):
