@@ -2,6 +2,12 @@
 // kernels (cf_kernels.hip).  Not installed; not part of the ABI.
 #pragma once
 
+#ifndef CF_SP_RPT
+#define CF_SP_RPT 16
+#endif
+#ifndef CF_SP_WAVES
+#define CF_SP_WAVES 2
+#endif
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -104,6 +110,7 @@ struct LaunchRange {
     uint32_t dec_lo, dec_hi;    // decode tiles
     uint32_t fin_lo, fin_hi;    // finalise blocks
     uint32_t item_lo, item_hi;  // single-pass items
+    uint32_t sp_xcd_major;      // single-pass kernel: deal the items XCD-major (a run of consecutive items per XCD)
     uint64_t p_partial_lo, p_partial_hi;    // workspace bytes holding the single-pass partials of the range
     int32_t dts;                // storage dtype of every tensor in the range (cf_dtype), or 2 if mixed
     int32_t only_group_scale;   // tiled encode: skip tensors the single-pass kernel covers

@@ -21,8 +21,9 @@
 // partial can take before the kernel starts, and a reader fetches a slot again
 // until it has changed.  One store and one load per hop; no counter.
 //
-// Items are numbered group-major and dealt to the workgroups XCD-major, so the
-// items of a group run on one XCD at about the same time.  Every wait ends
+// Items are numbered group-major and dealt to the workgroups in index order
+// (or, for short tensors, XCD-major: see the kernel), so the items of a group
+// start at about the same time.  Every wait ends
 // because the waited-for items are running or about to start: under a
 // cooperative launch (a co-resident grid that loops over the items, at least
 // as large as the largest group) by construction; under an ordinary launch of
@@ -98,7 +99,7 @@ template <int DT, int BITS, int ET, bool FUSED>
 __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev &d, const TensorPtrs &p, int stripe,
                                              int rb, Shared &sh)
 {
-    constexpr int RPT = (DT == BF16) ? 16 : 8;      // rows per lane
+    constexpr int RPT = (DT == BF16) ? CF_SP_RPT : CF_SP_RPT / 2;      // rows per lane
     constexpr bool IS_MAX = BITS == 4;
     const int tid = (int)threadIdx.x, cl = tid & (kStripeChunks - 1), rl = tid / kStripeChunks;
     const int chunk = stripe * kStripeChunks + cl;
@@ -124,7 +125,7 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
     // ---- a3, level 1: balanced tree over the lane's RPT consecutive rows
     // (a binary-counter stack: after row k the slots hold the partial trees of the rows seen so far;
     // k is a compile-time constant after unrolling, so every branch below folds away)
-    constexpr int LVR = (RPT == 16) ? 5 : 4;
+    constexpr int LVR = (RPT == 32) ? 6 : (RPT == 16) ? 5 : (RPT == 8) ? 4 : (RPT == 4) ? 3 : 2;
     F8 st[LVR];
     const F8 none = {};
 #pragma unroll
@@ -240,13 +241,18 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
 }
 
 template <int ET, bool FUSED>
-__global__ __launch_bounds__(kPersistThreads, 2) void k_single_pass(BatchView v, LaunchRange r)
+__global__ __launch_bounds__(kPersistThreads, CF_SP_WAVES) void k_single_pass(BatchView v, LaunchRange r)
 {
     __shared__ Shared sh;
-    // Workgroups are handed to the 8 XCDs in turn (blockIdx.x % 8).  Numbering them XCD-major puts
-    // the consecutive items of one reduction group on one XCD, behind one L2.
-    const uint32_t q = gridDim.x >> 3, rem = gridDim.x & 7u, xcd = blockIdx.x & 7u;
-    const uint32_t vb = xcd * q + (xcd < rem ? xcd : rem) + (blockIdx.x >> 3);
+    // Workgroups are handed to the 8 XCDs in turn (blockIdx.x % 8).  Taking item b in workgroup b runs the
+    // consecutive items of a reduction group on different XCDs at the same time, and a tensor with 8 row
+    // blocks keeps each of them on one XCD, whose L2 then sees all stripes of a code row.  Short tensors
+    // (few items per group) do better XCD-major, a run of consecutive items per XCD; the host chooses.
+    uint32_t vb = blockIdx.x;
+    if (r.sp_xcd_major) {
+        const uint32_t q = gridDim.x >> 3, rem = gridDim.x & 7u, xcd = blockIdx.x & 7u;
+        vb = xcd * q + (xcd < rem ? xcd : rem) + (blockIdx.x >> 3);
+    }
     for (uint32_t item = r.item_lo + vb; item < r.item_hi; item += gridDim.x) {
         const int t = (int)v.item_tensor[item];
         const TensorDev d = v.descs[t];                             // by value: scalar registers, never re-read
@@ -308,11 +314,12 @@ hipError_t launch_reset_partials(const BatchView &v, const LaunchRange &r, hipSt
 // A workgroup that loops has to drain its stores before its next loads count as returned (the loads and
 // stores of a wave share one in-order counter); one that exits leaves the draining to the memory system
 // while the next workgroup already loads.  Without co-residency every wait still ends because workgroups
-// are started in index order: with items numbered XCD-major each XCD walks its own contiguous run of
-// items in order, so the members of its oldest unfinished group are the oldest workgroups it holds or
-// the next it starts, and whatever else it holds belongs to older groups, publishes without waiting and
-// leaves.  The caller passes one_shot only when an XCD's share of `grid` (the co-resident capacity) holds
-// a whole group.  Should the assumption ever fail, the bounded wait raises the error flag.
+// are started in index order, each XCD taking those of its residue class in order, and under either dealing
+// an XCD walks its items in ascending order: take the oldest group with an unfinished item; every older
+// group has finished and left, so whatever an XCD still holds from before one of this group's unstarted
+// items belongs to this group too, and as long as the XCD's share of `grid` (the co-resident capacity)
+// exceeds the group a slot is free and the item starts.  The caller passes one_shot only when an XCD's
+// share of `grid` holds a whole group.  Should the assumption ever fail, the bounded wait raises the error flag.
 hipError_t launch_single_pass(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, int grid, bool one_shot,
                              hipStream_t s)
 {
