@@ -278,8 +278,9 @@ def dominant_kernel(res):
     return nm, km[nm]
 
 
-def kernel_algorithmic_bytes(nm: str, wl, ef: int) -> float:
-    """Algorithmic bytes one launch of kernel `nm` moves (every operand of that kernel once)."""
+def kernel_algorithmic_bytes(nm: str, wl, ef: int, split: bool = False) -> float:
+    """Algorithmic bytes one launch of kernel `nm` moves (every operand of that kernel once).  split: the step runs
+    as cf_compress + cf_decompress, so the sender's kernels do not write the reconstruction."""
     total = 0.0
     for t in range(wl.n_tensors):
         n = wl.n_tokens * wl.n_channels
@@ -288,16 +289,16 @@ def kernel_algorithmic_bytes(nm: str, wl, ef: int) -> float:
         scale_b = scale_bytes_per_element(wl)
         if nm == "k_colreduce":
             per = 2 * sx + (4 if ef else 0)
-        elif nm == "k_encode":          # reads x, recon (+err); writes codes, err, recon
-            per = 3 * sx + 4 + code_bytes_per_element(wl, bits) + (4 if ef else 0) + scale_b
+        elif nm in ("k_encode", "k_encode_nm"):     # reads x, recon (+err); writes codes, err, recon
+            per = (2 if split else 3) * sx + 4 + code_bytes_per_element(wl, bits) + (4 if ef else 0) + scale_b
         elif nm in ("k_lr_project", "k_lr_backproject"):     # re-form A from x and recon
             per = 2 * sx
         elif nm == "k_lr_apply":                            # reads x, recon and the factors; writes err, recon
-            per = 3 * sx + 4 + code_bytes_per_element(wl, bits)
+            per = (2 if split else 3) * sx + 4 + code_bytes_per_element(wl, bits)
         elif nm == "k_decode":
             per = 2 * sx + code_bytes_per_element(wl, bits) + scale_b
-        else:                            # a kernel that does the whole step
-            per = bytes_per_element(wl, bits, ef)
+        else:                            # a kernel that does the whole step (the sender's half of it when split)
+            per = bytes_per_element(wl, bits, ef) - (sx if split else 0)
         total += n * per
     return total
 
@@ -371,10 +372,10 @@ def main():
     kname, kms = dominant_kernel(r)
     roofline = None
     if kname is not None:
-        kb = kernel_algorithmic_bytes(kname, wl, args.ef)
+        kb = kernel_algorithmic_bytes(kname, wl, args.ef, args.split)
         achieved = kb / (kms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBPS, "traffic": None if (args.scale or args.bits or args.tensors or args.ef) else read_traffic(kname, head),
+                    "frac": achieved / HBM_PEAK_GBPS, "traffic": None if (args.scale or args.bits or args.tensors or args.ef or args.split) else read_traffic(kname, head),
                     "algorithmic_bytes_per_launch": kb, "avg_launch_ms": kms}
     mfma = None
     if wl.scale == "lowrank" and r.get("kernel_ms"):        # the dense contractions: 2 * 32 flops per element and launch

@@ -308,10 +308,20 @@ struct cf_ctx {
         return r;
     }
 
-    bool range_has_group_scale(int32_t first, int32_t count) const   // anything the single-pass kernel leaves to k_encode
+    // anything for k_encode (with_channel: channel-scale tensors too; not when the single-pass kernel took them)
+    bool range_has_quantised(int32_t first, int32_t count, bool with_channel) const
+    {
+        for (int32_t t = first; t < first + count; ++t) {
+            const int sc = descs[t].scale;
+            if (sc == CF_SCALE_GROUP || sc == CF_SCALE_RANK1 || (with_channel && sc == CF_SCALE_CHANNEL)) return true;
+        }
+        return false;
+    }
+
+    bool range_has_sparse(int32_t first, int32_t count, int block) const   // anything for k_encode_nm of that block length
     {
         for (int32_t t = first; t < first + count; ++t)
-            if (descs[t].scale != CF_SCALE_CHANNEL) return true;
+            if (descs[t].scale == CF_SPARSE_NM && descs[t].group == block) return true;
         return false;
     }
 
@@ -473,6 +483,24 @@ cf_status run_lowrank_sender(cf_ctx *ctx, int32_t first, int32_t count, const Ba
     return CF_OK;
 }
 
+// The row-local encoders over the element-wise tiles of the range: k_encode for the quantisers (channel-scale
+// tensors only when with_channel: not when the single-pass kernel already took them, r.only_group_scale),
+// k_encode_nm for the sparsifier (once per block length); each only if the range holds such a tensor.
+hipError_t run_row_local(cf_ctx *ctx, int32_t first, int32_t count, const BatchView &v, const LaunchRange &r, bool fused,
+                         bool with_channel, hipStream_t s)
+{
+    const int ef = ctx->opts.ef, et = ctx->opts.err_dtype;
+    hipError_t e = hipSuccess;
+    if (ctx->range_has_quantised(first, count, with_channel)) {
+        e = launch(ctx, s, "k_encode", [&] { return launch_encode(v, r, ef, et, fused, s); });
+        if (e != hipSuccess) return e;
+    }
+    for (int pair = 0; pair < 2 && e == hipSuccess; ++pair)
+        if (ctx->range_has_sparse(first, count, pair ? 16 : 8))
+            e = launch(ctx, s, "k_encode_nm", [&] { return launch_encode_nm(v, r, ef, et, fused, pair != 0, s); });
+    return e;
+}
+
 cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *const *x, void *const *recon,
                      void *const *err, void *const *codes, void *const *scales, void *stream, bool fused)
 {
@@ -514,11 +542,8 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
         const bool one_shot = ctx->L.max_group_items * 8 <= grid;       // an XCD's share of the resident workgroups holds a whole group
         e = launch(ctx, s, "k_single_pass", [&] { return launch_single_pass(v, r, et, fused, grid, one_shot, s); });
         if (e != hipSuccess) return device_fail(ctx, e);
-        if (ctx->range_has_group_scale(first, count)) {
-            r.only_group_scale = 1;
-            e = launch(ctx, s, "k_encode", [&] { return launch_encode(v, r, ef, et, fused, s); });
-            if (e != hipSuccess) return device_fail(ctx, e);
-        }
+        r.only_group_scale = 1;
+        if ((e = run_row_local(ctx, first, count, v, r, fused, false, s)) != hipSuccess) return device_fail(ctx, e);
         return run_lowrank_sender(ctx, first, count, v, r, fused, s);
     }
     if (ctx->range_has_channel(first, count)) {
@@ -531,10 +556,7 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
             if (e != hipSuccess) return device_fail(ctx, e);
         }
     }
-    if (ctx->range_has_elementwise(first, count)) {
-        e = launch(ctx, s, "k_encode", [&] { return launch_encode(v, r, ef, et, fused, s); });
-        if (e != hipSuccess) return device_fail(ctx, e);
-    }
+    if ((e = run_row_local(ctx, first, count, v, r, fused, true, s)) != hipSuccess) return device_fail(ctx, e);
     return run_lowrank_sender(ctx, first, count, v, r, fused, s);
 }
 

@@ -127,6 +127,7 @@ hipError_t launch_colreduce(const BatchView &v, const LaunchRange &r, int ef, in
 hipError_t launch_finalize(const BatchView &v, const LaunchRange &r, hipStream_t s);
 hipError_t launch_finalize_rank1(const BatchView &v, const LaunchRange &r, hipStream_t s);
 hipError_t launch_encode(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, bool fused, hipStream_t s);
+hipError_t launch_encode_nm(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, bool fused, bool pair, hipStream_t s);
 hipError_t launch_decode(const BatchView &v, const LaunchRange &r, hipStream_t s);
 
 // Low-rank compressor (cf_lowrank.hip): rank 32, C a multiple of 32 and at most kLowRankMaxChannels.

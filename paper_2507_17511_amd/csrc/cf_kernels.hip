@@ -458,22 +458,19 @@ __device__ __forceinline__ void nm_encode_tile(const TileCtx &c)
     }
 }
 
+template <int DT, bool PAIR, int EF, int ET, bool FUSED>
+__device__ __forceinline__ void nm_encode_dispatch(const TileCtx &c)
+{
+    const TensorDev &d = c.d;
+    if (d.bits == 1) nm_encode_tile<DT, 1, PAIR, EF, ET, FUSED>(c);
+    else if (d.bits == 2) nm_encode_tile<DT, 2, PAIR, EF, ET, FUSED>(c);
+    else nm_encode_tile<DT, 4, PAIR, EF, ET, FUSED>(c);
+}
+
 template <int DT, int EF, int ET, bool FUSED>
 __device__ __forceinline__ void encode_dispatch(const TileCtx &c)
 {
     const TensorDev &d = c.d;
-    if (d.scale == SPARSE_NM) {
-        if (d.nm_block == 16) {
-            if (d.bits == 1) nm_encode_tile<DT, 1, true, EF, ET, FUSED>(c);
-            else if (d.bits == 2) nm_encode_tile<DT, 2, true, EF, ET, FUSED>(c);
-            else nm_encode_tile<DT, 4, true, EF, ET, FUSED>(c);
-        } else {
-            if (d.bits == 1) nm_encode_tile<DT, 1, false, EF, ET, FUSED>(c);
-            else if (d.bits == 2) nm_encode_tile<DT, 2, false, EF, ET, FUSED>(c);
-            else nm_encode_tile<DT, 4, false, EF, ET, FUSED>(c);
-        }
-        return;
-    }
     if (d.scale == SCALE_GROUP) { encode_tile<DT, 4, 1, EF, ET, FUSED>(c); return; }
     if (d.scale == SCALE_RANK1) {
         if (d.bits == 1) encode_tile<DT, 1, 2, EF, ET, FUSED>(c);
@@ -490,9 +487,21 @@ __global__ __launch_bounds__(kTileThreads) void k_encode(BatchView v, LaunchRang
 {
     TileCtx c = locate_tile<true>(v, r);
     if (r.only_group_scale && c.d.scale == SCALE_CHANNEL) return;   // covered by the single-pass kernel
-    if (c.d.scale == LOWRANK) return;                               // has kernels of its own
+    if (c.d.scale == LOWRANK || c.d.scale == SPARSE_NM) return;     // have kernels of their own
     if (is_bf16<DTS>(c.d)) encode_dispatch<BF16, EF, ET, FUSED>(c);
     else encode_dispatch<F32, EF, ET, FUSED>(c);
+}
+
+// The sparsifier's tensors, over the same tiles; PAIR: those with 16-channel blocks, else those with 8-channel
+// blocks.  Kernels of their own: the selection over 16-channel blocks needs half as many registers again as the
+// quantisers, and in one kernel every tensor would pay for that in occupancy.
+template <int EF, int ET, bool FUSED, bool PAIR, int DTS>
+__global__ __launch_bounds__(kTileThreads) void k_encode_nm(BatchView v, LaunchRange r)
+{
+    TileCtx c = locate_tile<true>(v, r);
+    if (c.d.scale != SPARSE_NM || (c.d.nm_block == 16) != PAIR) return;
+    if (is_bf16<DTS>(c.d)) nm_encode_dispatch<BF16, PAIR, EF, ET, FUSED>(c);
+    else nm_encode_dispatch<F32, PAIR, EF, ET, FUSED>(c);
 }
 
 // ---------------------------------------------------------------- a6 + a8: receiver decode
@@ -723,6 +732,20 @@ hipError_t launch_encode(const BatchView &v, const LaunchRange &r, int ef, int e
     if (grid.x == 0) return hipSuccess;
     if (fused) CF_LAUNCH_EF_ET(k_encode, , true);
     else CF_LAUNCH_EF_ET(k_encode, , false);
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_nm(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, bool fused, bool pair, hipStream_t s)
+{
+    dim3 grid(r.ew_hi - r.ew_lo), block(kTileThreads);
+    if (grid.x == 0) return hipSuccess;
+    if (pair) {
+        if (fused) CF_LAUNCH_EF_ET(k_encode_nm, , true, true);
+        else CF_LAUNCH_EF_ET(k_encode_nm, , false, true);
+    } else {
+        if (fused) CF_LAUNCH_EF_ET(k_encode_nm, , true, false);
+        else CF_LAUNCH_EF_ET(k_encode_nm, , false, false);
+    }
     return hipGetLastError();
 }
 
