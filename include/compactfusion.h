@@ -142,14 +142,14 @@ typedef struct {
 /* A channel scale needs every token of a channel before any code of that
  * channel.  With CF_EF_RECON a single persistent kernel keeps x and recon in
  * registers across that reduction (each is read once; workgroups of one
- * 64-channel stripe wait for each other's partial sums, every wait bounded:
+ * 128-channel stripe wait for each other's partial sums, every wait bounded:
  * see cf_check_device).  It applies to CF_EF_RECON, CF_SCALE_CHANNEL tensors, no
- * CF_SCALE_RANK1 tensor in the context, N / 512 workgroups co-resident.
+ * CF_SCALE_RANK1 tensor in the context, N / 256 workgroups co-resident.
  * Otherwise one kernel reduces and a second one, which reads x and recon
  * again, writes the codes.  Results are bit-identical either way.  By default
  * a call takes the single pass where it applies, every channel-scale tensor
  * of the context has at least 256 tokens and the call covers at least 64 work
- * items of 512 rows x 64 channels (it is about 13 % faster on MI355X at the
+ * items of 256 rows x 128 channels (it is about 25 % faster on MI355X at the
  * sizes of the paper's models and slower on tiny batches);
  * CF_FLAG_SINGLE_PASS takes it whenever it applies, CF_FLAG_TWO_KERNEL never. */
 #define CF_FLAG_SINGLE_PASS 0x1u

@@ -529,7 +529,7 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
     hipError_t e;
     const int grid = ctx->persist_grid[et == CF_BF16 ? 1 : 0][fused ? 1 : 0];
     // unless asked for: not for tiny batches (the wait chain costs more than a second read) nor for short tensors
-    // (an item is 256 or 512 rows tall: most of its lanes would idle)
+    // (an item is 128 or 256 rows tall: most of its lanes would idle)
     const bool forced = (ctx->opts.flags & CF_FLAG_SINGLE_PASS) != 0;
     const bool worth_it = forced || (r.item_hi - r.item_lo >= 64u && ctx->L.min_channel_scale_tokens >= 256);
     if (ctx->L.single_pass && grid >= ctx->L.max_group_items && r.item_hi > r.item_lo && worth_it) {

@@ -22,20 +22,20 @@ constexpr int kFinalizeThreads = 256;                       // columns per final
 constexpr int kRank1Threads = 1024;                         // one block per tensor finishes the token scales u
 constexpr int kMaxRank1Colblocks = 128;                     // rank-1 scales: C <= 128 * 1024
 constexpr int kMaxUploadTensors = 64;                       // pointer sets per upload launch
-// Single-pass path: one workgroup of 256 lanes keeps an item of p_rows x 64
+// Single-pass path: one workgroup of 256 lanes keeps an item of p_rows x 128
 // channels (x and recon, raw) in registers between the scale reduction and the
-// encode; lanes are 8 chunks x 32 row-lanes, so a row segment is one 128-byte
-// line of bf16.  Narrow stripes mean few items per reduction group (8 at
-// N = 4096), which is what bounds how long an item waits for its group:
-// 256-channel stripes (32 items per group) were 5 % slower, 32-channel ones
-// (64-byte segments) 50 % slower.
+// encode; lanes are 16 chunks x 16 row-lanes, so a row segment is 256 bytes of
+// bf16 and a row's 1-bit codes of one item are 16 bytes.  Measured on 114 x
+// [4096, 3072] bf16: 64- / 128- / 256-channel stripes (8 / 16 / 32 items per
+// reduction group) 2.94 / 2.86 / 2.92 ms; 32-channel ones (64-byte segments)
+// were 50 % slower.
 constexpr int kPersistThreads = 256;
 #ifndef CF_STRIPE_CHANNELS
-#define CF_STRIPE_CHANNELS 64
+#define CF_STRIPE_CHANNELS 128
 #endif
 constexpr int kStripeChannels = CF_STRIPE_CHANNELS;
-constexpr int kStripeChunks = kStripeChannels / kChunk;     // 8
-constexpr int kRowLanes = kPersistThreads / kStripeChunks;  // 32
+constexpr int kStripeChunks = kStripeChannels / kChunk;     // 16
+constexpr int kRowLanes = kPersistThreads / kStripeChunks;  // 16
 constexpr uint32_t kSpinLimit = 1u << 20;                   // bounded wait (about seconds), then the error flag
 
 // Static description of one tensor; built at cf_init, lives in the workspace.
@@ -54,7 +54,7 @@ struct alignas(16) TensorDev {
     uint64_t partial_off;   // byte offset in the workspace of partial[n_rowblocks][C] (channel scales)
     // single-pass path (channel scales, CF_EF_RECON): items of p_rows x kStripeChannels
     uint64_t p_partial_off; // byte offset of partial[p_n_rb][C]
-    int32_t p_rows;         // rows per item (512 for bf16, 256 for fp32); 0 = tensor not on this path
+    int32_t p_rows;         // rows per item (256 for bf16, 128 for fp32); 0 = tensor not on this path
     int32_t p_n_rb;         // ceil(N / p_rows): items per reduction group
     int32_t p_n_stripes;    // ceil(C / kStripeChannels): reduction groups of this tensor
     uint32_t p_item_begin;  // id of this tensor's first item

@@ -4,10 +4,10 @@
 //
 // A two-kernel design reads x and recon twice from HBM.  Here a workgroup
 // keeps its share of x and recon in registers across the reduction instead:
-//   item  = p_rows x 64 channels of one tensor (512 rows of bf16, 256 of fp32:
+//   item  = p_rows x 128 channels of one tensor (256 rows of bf16, 128 of fp32:
 //           128 VGPRs of raw data per lane), owned by one workgroup of 256 lanes
-//           (8 chunks of 8 channels x 32 row-lanes);
-//   group = the items of one 64-channel stripe of one tensor; only they have
+//           (16 chunks of 8 channels x 16 row-lanes);
+//   group = the items of one 128-channel stripe of one tensor; only they have
 //           to agree on that stripe's scales, so there is no grid-wide barrier,
 //           and different groups drift apart, which keeps HBM busy while some
 //           workgroups wait.
@@ -245,8 +245,8 @@ __global__ __launch_bounds__(kPersistThreads, CF_SP_WAVES) void k_single_pass(Ba
 {
     __shared__ Shared sh;
     // Workgroups are handed to the 8 XCDs in turn (blockIdx.x % 8).  Taking item b in workgroup b runs the
-    // consecutive items of a reduction group on different XCDs at the same time, and a tensor with 8 row
-    // blocks keeps each of them on one XCD, whose L2 then sees all stripes of a code row.  Short tensors
+    // consecutive items of a reduction group on different XCDs at the same time, and a tensor whose row
+    // blocks number a multiple of 8 keeps each of them on one XCD, whose L2 then sees all stripes of a code row.  Short tensors
     // (few items per group) do better XCD-major, a run of consecutive items per XCD; the host chooses.
     uint32_t vb = blockIdx.x;
     if (r.sp_xcd_major) {

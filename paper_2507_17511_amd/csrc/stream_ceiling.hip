@@ -4,10 +4,10 @@
 // optionally 1/8 byte of codes) with no arithmetic to speak of, no reduction and no waiting, in the two shapes
 // the library uses:
 //   row-local      a lane loads one 16-byte vector of x and of recon and stores at once (the shape of k_encode);
-//   item-resident  a workgroup of 256 lanes loads a whole item of 512 rows x 64 channels (32 vectors per lane),
+//   item-resident  a workgroup of 256 lanes loads a whole item of 256 rows x 128 channels (32 vectors per lane),
 //                  passes a barrier, then stores (the shape of k_single_pass), with the items dealt to the
 //                  workgroups in index order or XCD-major, and the item's code bytes not written, written as
-//                  the 8-byte pieces of the wire layout, or written as one contiguous block per item.
+//                  the 16-byte pieces of the wire layout, or written as one contiguous block per item.
 // Prints one line per variant.  Usage: stream_ceiling [n_tensors, default 114]
 #include <hip/hip_runtime.h>
 
@@ -27,7 +27,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kTokens = 4096, kChannels = 3072, kRowsPerLane = 16;
 constexpr size_t kRowVecs = kChannels * 2 / 16;     // 16-byte vectors per row of x or recon (384)
-constexpr int kChunkLanes = 8, kRowLanes = 32;      // 8 lanes across the 128-byte row segment, 32 down the rows
+constexpr int kChunkLanes = 16, kRowLanes = 16;     // 16 lanes across the 256-byte row segment, 16 down the rows
 constexpr int kItemRows = kRowLanes * kRowsPerLane, kRowBlocks = kTokens / kItemRows, kStripes = (int)(kRowVecs / kChunkLanes);
 enum Codes { NONE = 0, WIRE_PIECES = 1, ITEM_BLOCK = 2 };
 
@@ -139,8 +139,8 @@ int main(int argc, char **argv)
             [&] { hipLaunchKernelGGL(k_row_local, dim3((unsigned)((b.n_vecs + 255) / 256)), dim3(256), 0, 0, b.x, b.r, b.e, b.n_vecs); });
     item_resident<false, NONE>("item-resident, index order, no codes", b);
     item_resident<true, NONE>("item-resident, XCD-major, no codes", b);
-    item_resident<false, WIRE_PIECES>("item-resident, index order, codes as 8-byte wire pieces", b);
-    item_resident<true, WIRE_PIECES>("item-resident, XCD-major, codes as 8-byte wire pieces", b);
+    item_resident<false, WIRE_PIECES>("item-resident, index order, codes as 16-byte wire pieces", b);
+    item_resident<true, WIRE_PIECES>("item-resident, XCD-major, codes as 16-byte wire pieces", b);
     item_resident<false, ITEM_BLOCK>("item-resident, index order, codes as one block per item", b);
     item_resident<true, ITEM_BLOCK>("item-resident, XCD-major, codes as one block per item", b);
     return 0;

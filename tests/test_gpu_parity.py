@@ -106,7 +106,7 @@ def test_parity_batched_mixed_launch(mode, flags):
 
 
 def test_single_pass_many_row_blocks_and_stripes():
-    """Reduction groups of several items (N = 1500: 3 row blocks of 512, ragged) over 18 stripes (C = 1096),
+    """Reduction groups of several items (N = 1500: 6 row blocks of 256, ragged) over 9 stripes (C = 1096),
     several tensors deep, so that workgroups take more than one item each."""
     say("single pass, deep")
     descs = [cf.desc(1500, 1096, cf.CF_BF16, (1, 2, 4)[t % 3], CH) for t in range(6)]
@@ -120,7 +120,7 @@ def test_single_pass_many_row_blocks_and_stripes():
 
 
 def test_single_pass_looping_grid():
-    """Groups of 79 items (N = 40000) are too large for one workgroup per item to be safe, so the
+    """Groups of 157 items (N = 40000) are too large for one workgroup per item to be safe, so the
     single-pass kernel runs as a co-resident grid that loops over the items (cooperative launch)."""
     say("single pass, looping grid")
     descs = [cf.desc(40000, 72, cf.CF_BF16, (1, 2, 4)[t % 3], CH) for t in range(6)]
@@ -132,8 +132,8 @@ def test_single_pass_looping_grid():
 
 @pytest.mark.parametrize("case", [0, 1, 2, 3])
 def test_single_pass_random_shapes(case):
-    """Seeded random batches: token counts that leave ragged items (items are 512 rows of bf16, 256 of fp32),
-    channel counts that leave ragged stripes (64 channels) and ragged lane quads, mixed dtypes and widths."""
+    """Seeded random batches: token counts that leave ragged items (items are 256 rows of bf16, 128 of fp32),
+    channel counts that leave ragged stripes (128 channels) and ragged lane quads, mixed dtypes and widths."""
     rng = np.random.default_rng(1000 + case)
     descs = []
     for t in range(7):
