@@ -8,6 +8,7 @@
 //                  passes a barrier, then stores (the shape of k_single_pass), with the items dealt to the
 //                  workgroups in index order or XCD-major, and the item's code bytes not written, written as
 //                  the 16-byte pieces of the wire layout, or written as one contiguous block per item.
+// For scale, two kernels that only read (x and recon) or only write (err and recon) the same buffers.
 // Prints one line per variant.  Usage: stream_ceiling [n_tensors, default 114]
 #include <hip/hip_runtime.h>
 
@@ -40,6 +41,29 @@ __global__ __launch_bounds__(256) void k_row_local(const u32x4 *x, u32x4 *r, u32
     *(GLOBAL u32x4 *)(e + 2 * i) = a - b;
     *(GLOBAL u32x4 *)(e + 2 * i + 1) = a ^ b;
     *(GLOBAL u32x4 *)(r + i) = a + b;
+}
+
+// 4 vectors of x and of recon per lane, folded into a value that is (practically) never stored
+__global__ __launch_bounds__(256) void k_read_only(const u32x4 *x, const u32x4 *r, u32x4 *sink, size_t n_vecs)
+{
+    const size_t i0 = (size_t)blockIdx.x * 1024 + threadIdx.x;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const size_t i = i0 + (size_t)k * 256;
+        if (i < n_vecs) acc ^= __builtin_nontemporal_load((const GLOBAL u32x4 *)(x + i)) + *(const GLOBAL u32x4 *)(r + i);
+    }
+    if (acc.x == 0x9e3779b9u && acc.y == 0x7f4a7c15u && acc.z == 0xf39cc060u) *(GLOBAL u32x4 *)sink = acc;
+}
+
+__global__ __launch_bounds__(256) void k_write_only(u32x4 *r, u32x4 *e, size_t n_vecs)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_vecs) return;
+    const u32x4 v = {(unsigned)i, 1u, 2u, 3u};
+    *(GLOBAL u32x4 *)(e + 2 * i) = v;
+    *(GLOBAL u32x4 *)(e + 2 * i + 1) = v;
+    *(GLOBAL u32x4 *)(r + i) = v;
 }
 
 template <bool XCD_MAJOR, int CODES>
@@ -135,6 +159,11 @@ int main(int argc, char **argv)
     CHECK(hipMemset(b.e, 0, b.n_vecs * 32));
     CHECK(hipMemset(b.codes, 0, b.n_vecs));
     printf("%d tensors of [%d, %d] bf16; 10 bytes per element (+ 1/8 with codes)\n", b.n_tensors, kTokens, kChannels);
+    time_it("read only (x and recon; 4 bytes per element)", b, 4.0, [&] {
+        hipLaunchKernelGGL(k_read_only, dim3((unsigned)((b.n_vecs / 4 + 255) / 256)), dim3(256), 0, 0, b.x, b.r, (u32x4 *)b.codes, b.n_vecs);
+    });
+    time_it("write only (err and recon; 6 bytes per element)", b, 6.0,
+            [&] { hipLaunchKernelGGL(k_write_only, dim3((unsigned)((b.n_vecs + 255) / 256)), dim3(256), 0, 0, b.r, b.e, b.n_vecs); });
     time_it("row-local, no codes", b, 10.0,
             [&] { hipLaunchKernelGGL(k_row_local, dim3((unsigned)((b.n_vecs + 255) / 256)), dim3(256), 0, 0, b.x, b.r, b.e, b.n_vecs); });
     item_resident<false, NONE>("item-resident, index order, no codes", b);
