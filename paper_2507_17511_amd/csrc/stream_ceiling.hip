@@ -8,6 +8,7 @@
 //                  passes a barrier, then stores (the shape of k_single_pass), with the items dealt to the
 //                  workgroups in index order or XCD-major, and the item's code bytes not written, written as
 //                  the 16-byte pieces of the wire layout, or written as one contiguous block per item.
+// And the receiver's mix (cf_decompress: read recon and the 1-bit codes, write recon in place).
 // For scale, two kernels that only read (x and recon) or only write (err and recon) the same buffers.
 // Prints one line per variant.  Usage: stream_ceiling [n_tensors, default 114]
 #include <hip/hip_runtime.h>
@@ -64,6 +65,16 @@ __global__ __launch_bounds__(256) void k_write_only(u32x4 *r, u32x4 *e, size_t n
     *(GLOBAL u32x4 *)(e + 2 * i) = v;
     *(GLOBAL u32x4 *)(e + 2 * i + 1) = v;
     *(GLOBAL u32x4 *)(r + i) = v;
+}
+
+// the receiver: a lane reads one vector of recon and its code byte and writes the vector back
+__global__ __launch_bounds__(256) void k_row_local_decode(u32x4 *r, const unsigned char *codes, size_t n_vecs)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_vecs) return;
+    const u32x4 b = *(const GLOBAL u32x4 *)(r + i);
+    const unsigned c = *(const GLOBAL unsigned char *)(codes + i);
+    *(GLOBAL u32x4 *)(r + i) = b + c;
 }
 
 template <bool XCD_MAJOR, int CODES>
@@ -128,7 +139,7 @@ template <typename Launch> void time_it(const char *what, const Buffers &b, doub
     CHECK(hipEventElapsedTime(&ms, b.e0, b.e1));
     const double bytes = (double)b.n_tensors * kTokens * kChannels * bytes_per_element;
     const double gbps = bytes / 1e9 / (ms / iters * 1e-3);
-    printf("%-64s %7.3f ms  %7.1f GB/s  %.1f %% of 8 TB/s\n", what, ms / iters, gbps, gbps / 80.0);
+    printf("%-72s %7.3f ms  %7.1f GB/s  %.1f %% of 8 TB/s\n", what, ms / iters, gbps, gbps / 80.0);
     fflush(stdout);
 }
 
@@ -166,6 +177,8 @@ int main(int argc, char **argv)
             [&] { hipLaunchKernelGGL(k_write_only, dim3((unsigned)((b.n_vecs + 255) / 256)), dim3(256), 0, 0, b.r, b.e, b.n_vecs); });
     time_it("row-local, no codes", b, 10.0,
             [&] { hipLaunchKernelGGL(k_row_local, dim3((unsigned)((b.n_vecs + 255) / 256)), dim3(256), 0, 0, b.x, b.r, b.e, b.n_vecs); });
+    time_it("row-local receiver (recon in place + codes; 4.125 bytes per element)", b, 4.125,
+            [&] { hipLaunchKernelGGL(k_row_local_decode, dim3((unsigned)((b.n_vecs + 255) / 256)), dim3(256), 0, 0, b.r, b.codes, b.n_vecs); });
     item_resident<false, NONE>("item-resident, index order, no codes", b);
     item_resident<true, NONE>("item-resident, XCD-major, no codes", b);
     item_resident<false, WIRE_PIECES>("item-resident, index order, codes as 16-byte wire pieces", b);
