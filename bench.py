@@ -43,6 +43,7 @@ def parse_args():
     ap.add_argument("--workload", default="all", help="one of workloads.CONFIGS, or all (every config; the headline is cfg3_kv_fullseq)")
     ap.add_argument("--ef", type=int, default=0, help="cf_ef_mode (0 = RECON)")
     ap.add_argument("--flags", type=int, default=0, help="cf_options.flags")
+    ap.add_argument("--err-dtype", default="f32", choices=("f32", "bf16"), help="dtype of the error buffer (the metric is quoted with f32)")
     ap.add_argument("--tile-rows", type=int, default=0)
     ap.add_argument("--encode-rows", type=int, default=0)
     ap.add_argument("--tensors", type=int, default=0, help="override the workload's tensor count (exploration only)")
@@ -99,7 +100,11 @@ class HipEvents:
 
 # ------------------------------------------------------------------ workload accounting
 
-def bytes_per_element(wl, bits: int, ef: int, err_bytes: int = 4) -> float:
+ERR_BYTES = 4       # bytes of one error-buffer element (set from --err-dtype)
+
+
+def bytes_per_element(wl, bits: int, ef: int) -> float:
+    err_bytes = ERR_BYTES
     sx = 4 if wl.dtype == "f32" else 2
     b = sx + sx + sx + err_bytes + code_bytes_per_element(wl, bits)     # x, recon read, recon write, err write, codes
     if ef != 0:
@@ -157,7 +162,8 @@ def run_workload(name: str, args, events: HipEvents | None):
     scale = {"group": cf.CF_SCALE_GROUP, "rank1": cf.CF_SCALE_RANK1, "nm": cf.CF_SPARSE_NM,
              "lowrank": cf.CF_LOWRANK}.get(wl.scale, cf.CF_SCALE_CHANNEL)
     descs = [cf.desc(wl.n_tokens, wl.n_channels, dt, wl.bits_of(t), scale, wl.group) for t in range(wl.n_tensors)]
-    opts = cf.options(ef=args.ef, flags=args.flags, tile_rows=args.tile_rows, encode_rows=args.encode_rows)
+    opts = cf.options(ef=args.ef, flags=args.flags, tile_rows=args.tile_rows, encode_rows=args.encode_rows,
+                      err_dtype=cf.CF_BF16 if args.err_dtype == "bf16" else cf.CF_F32)
 
     t0 = time.time()
     stream = ActivationStream(wl, device=dev)
@@ -288,13 +294,13 @@ def kernel_algorithmic_bytes(nm: str, wl, ef: int, split: bool = False) -> float
         bits = wl.bits_of(t)
         scale_b = scale_bytes_per_element(wl)
         if nm == "k_colreduce":
-            per = 2 * sx + (4 if ef else 0)
+            per = 2 * sx + (ERR_BYTES if ef else 0)
         elif nm in ("k_encode", "k_encode_nm"):     # reads x, recon (+err); writes codes, err, recon
-            per = (2 if split else 3) * sx + 4 + code_bytes_per_element(wl, bits) + (4 if ef else 0) + scale_b
+            per = (2 if split else 3) * sx + ERR_BYTES + code_bytes_per_element(wl, bits) + (ERR_BYTES if ef else 0) + scale_b
         elif nm in ("k_lr_project", "k_lr_backproject"):     # re-form A from x and recon
             per = 2 * sx
         elif nm == "k_lr_apply":                            # reads x, recon and the factors; writes err, recon
-            per = (2 if split else 3) * sx + 4 + code_bytes_per_element(wl, bits)
+            per = (2 if split else 3) * sx + ERR_BYTES + code_bytes_per_element(wl, bits)
         elif nm == "k_decode":
             per = 2 * sx + code_bytes_per_element(wl, bits) + scale_b
         else:                            # a kernel that does the whole step (the sender's half of it when split)
@@ -346,7 +352,9 @@ def read_traffic(kernel: str, workload: str):
 
 
 def main():
+    global ERR_BYTES
     args = parse_args()
+    ERR_BYTES = 2 if args.err_dtype == "bf16" else 4
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU only (the packed-code buffer in HBM stands in for the wire; "
               "there is no multi-GPU path): run with --gpus 1", file=sys.stderr)
@@ -375,14 +383,14 @@ def main():
         kb = kernel_algorithmic_bytes(kname, wl, args.ef, args.split)
         achieved = kb / (kms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBPS, "traffic": None if (args.scale or args.bits or args.tensors or args.ef or args.split) else read_traffic(kname, head),
+                    "frac": achieved / HBM_PEAK_GBPS, "traffic": None if (args.scale or args.bits or args.tensors or args.ef or args.split or args.err_dtype != "f32") else read_traffic(kname, head),
                     "algorithmic_bytes_per_launch": kb, "avg_launch_ms": kms}
     mfma = None
     if wl.scale == "lowrank" and r.get("kernel_ms"):        # the dense contractions: 2 * 32 flops per element and launch
         flops = 2.0 * 32 * wl.n_tensors * wl.n_tokens * wl.n_channels
         mfma = {nm: {"tflops": flops / (ms * 1e-3) / 1e12, "peak_fp32_mfma": 157.3, "frac": flops / (ms * 1e-3) / 1e12 / 157.3}
                 for nm, ms in r["kernel_ms"].items() if nm in ("k_lr_project", "k_lr_backproject", "k_lr_apply")}
-    cpu = None if (args.no_cpu_baseline or wl.scale == "lowrank") else cpu_baseline(wl, args.ef)
+    cpu = None if (args.no_cpu_baseline or wl.scale == "lowrank" or args.err_dtype != "f32") else cpu_baseline(wl, args.ef)
     if events is not None:
         events.destroy()
 
