@@ -101,6 +101,7 @@ class HipEvents:
 # ------------------------------------------------------------------ workload accounting
 
 ERR_BYTES = 4       # bytes of one error-buffer element (set from --err-dtype)
+LOWRANK_INT4 = False    # --flags has CF_FLAG_LOWRANK_INT4: 20 bytes per factor row instead of 32 values
 
 
 def bytes_per_element(wl, bits: int, ef: int) -> float:
@@ -117,7 +118,8 @@ def code_bytes_per_element(wl, bits: int) -> float:
     if wl.scale == "nm":                                # a mask bit per channel and `bits` values per block of `group`
         return 1 / 8.0 + bits * (4 if wl.dtype == "f32" else 2) / float(wl.group)
     if wl.scale == "lowrank":                           # U [N, 32] and V [C, 32] in the storage dtype
-        return (wl.n_tokens + wl.n_channels) * 32 * (4 if wl.dtype == "f32" else 2) / (wl.n_tokens * wl.n_channels)
+        row_bytes = 20 if LOWRANK_INT4 else 32 * (4 if wl.dtype == "f32" else 2)
+        return (wl.n_tokens + wl.n_channels) * row_bytes / (wl.n_tokens * wl.n_channels)
     return bits / 8.0
 
 
@@ -352,9 +354,10 @@ def read_traffic(kernel: str, workload: str):
 
 
 def main():
-    global ERR_BYTES
+    global ERR_BYTES, LOWRANK_INT4
     args = parse_args()
     ERR_BYTES = 2 if args.err_dtype == "bf16" else 4
+    LOWRANK_INT4 = bool(args.flags & 0x4)
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU only (the packed-code buffer in HBM stands in for the wire; "
               "there is no multi-GPU path): run with --gpus 1", file=sys.stderr)

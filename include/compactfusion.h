@@ -154,6 +154,12 @@ typedef struct {
  * CF_FLAG_SINGLE_PASS takes it whenever it applies, CF_FLAG_TWO_KERNEL never. */
 #define CF_FLAG_SINGLE_PASS 0x1u
 #define CF_FLAG_TWO_KERNEL 0x2u
+/* CF_LOWRANK tensors of the context send their factors as 4-bit integers (Sec. 3.4 and App. D name INT4
+ * factors without a format; this one is the library's): every factor row of 32 entries has one fp32 scale
+ * s = absmax / 7 and travels as nibbles q = clamp(round-half-even(f / s), -7, 7), two's complement, entry k
+ * in byte k / 2 with even k in the low nibble; D is formed from q * s.  The codes buffer then holds
+ * U nibbles [N, 16 bytes], V nibbles [C, 16 bytes], U scales [N] fp32, V scales [C] fp32: (N + C) * 20 bytes. */
+#define CF_FLAG_LOWRANK_INT4 0x4u
 
 /* Byte sizes of one tensor's buffers.  Any output pointer may be NULL.
  * CF_ERR_SHAPE / CF_ERR_UNSUPPORTED as for cf_init. */

@@ -17,6 +17,10 @@ Readings (the paper is silent or garbled on these):
     un-normalised, so that U V^T = A Q Q^T is the orthogonal projection of A onto span(Q).
   * The factors travel in the storage dtype of the tensor (bf16: round to nearest even) and D is formed from the
     travelled values, so that sender and receiver add the same D and the rounding loss stays in e.
+  * INT4 factors (Sec. 3.4 and App. D name them, no format is given): factor_bits = 4 sends every factor row of
+    r entries as one fp32 scale s = absmax / 7 and nibbles q = clamp(rint(f / s), -7, 7) (round half to even,
+    two's complement, entry k in byte k // 2, even k in the low nibble); D is formed from q * s.  The integer
+    decision is taken in fp32, the precision of the device path, on the fp64 factor rounded to fp32.
 """
 from __future__ import annotations
 
@@ -36,6 +40,7 @@ class LowRankConfig:
     dtype: int = BF16
     rank: int = 32
     iters: int = 1
+    factor_bits: int = 0        # 0: factors in the storage dtype; 4: INT4 nibbles + one fp32 scale per factor row
 
     @property
     def np_dtype(self):
@@ -59,6 +64,38 @@ def widen(a: np.ndarray, dtype: int) -> np.ndarray:
 
 def narrow(a: np.ndarray, dtype: int) -> np.ndarray:
     return rne_bf16(a) if dtype == BF16 else a.astype(np.float32)
+
+
+def quantise_rows(F: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """INT4 factor rows: -> (nibble bytes uint8 [rows, r // 2], scales fp32 [rows])."""
+    f = np.asarray(F, dtype=np.float64).astype(np.float32)
+    s = (np.abs(f).max(axis=1) / np.float32(7.0)).astype(np.float32)
+    safe = np.where(s == 0, np.float32(1.0), s).astype(np.float32)
+    q = np.clip(np.rint((f / safe[:, None]).astype(np.float32)), -7, 7).astype(np.int32)
+    q[s == 0] = 0
+    u = (q & 0xF).astype(np.uint8)
+    return (u[:, 0::2] | (u[:, 1::2] << 4)).astype(np.uint8), s
+
+
+def dequantise_rows(nibbles: np.ndarray, scales: np.ndarray) -> np.ndarray:
+    """-> fp64 [rows, r]: q * s, the product rounded to fp32 as the device forms it."""
+    b = np.asarray(nibbles, dtype=np.uint8)
+    u = np.empty((b.shape[0], 2 * b.shape[1]), dtype=np.int32)
+    u[:, 0::2] = b & 0xF
+    u[:, 1::2] = b >> 4
+    q = np.where(u >= 8, u - 16, u).astype(np.float32)
+    return (q * np.asarray(scales, dtype=np.float32)[:, None]).astype(np.float32).astype(np.float64)
+
+
+def factors_to_wire(cfg: LowRankConfig, F: np.ndarray):
+    """A factor as it travels: storage-dtype array, or (nibbles, scales) for INT4."""
+    return quantise_rows(F) if cfg.factor_bits == 4 else narrow(F, cfg.dtype)
+
+
+def factors_from_wire(cfg: LowRankConfig, W, rows: int) -> np.ndarray:
+    if cfg.factor_bits == 4:
+        return dequantise_rows(W[0].reshape(rows, cfg.rank // 2), W[1].reshape(rows))
+    return widen(W, cfg.dtype).reshape(rows, cfg.rank)
 
 
 def orthogonalize(Z: np.ndarray) -> np.ndarray:
@@ -91,13 +128,13 @@ def compress(cfg: LowRankConfig, x: np.ndarray, recon: np.ndarray, q0: np.ndarra
     """Sender half.  Returns (U_wire, V_wire, err fp32); recon is not touched."""
     A = widen(x, cfg.dtype).reshape(cfg.n_tokens, cfg.n_channels) - widen(recon, cfg.dtype).reshape(cfg.n_tokens, cfg.n_channels)
     U, V = subspace_iteration(A, np.asarray(q0, dtype=np.float64).reshape(cfg.n_channels, cfg.rank), cfg.iters)
-    Uw, Vw = narrow(U, cfg.dtype), narrow(V, cfg.dtype)
-    D = widen(Uw, cfg.dtype) @ widen(Vw, cfg.dtype).T
+    Uw, Vw = factors_to_wire(cfg, U), factors_to_wire(cfg, V)
+    D = factors_from_wire(cfg, Uw, cfg.n_tokens) @ factors_from_wire(cfg, Vw, cfg.n_channels).T
     return Uw, Vw, (A - D).astype(np.float32)
 
 
 def decode(cfg: LowRankConfig, Uw: np.ndarray, Vw: np.ndarray) -> np.ndarray:
-    return widen(Uw, cfg.dtype).reshape(cfg.n_tokens, cfg.rank) @ widen(Vw, cfg.dtype).reshape(cfg.n_channels, cfg.rank).T
+    return factors_from_wire(cfg, Uw, cfg.n_tokens) @ factors_from_wire(cfg, Vw, cfg.n_channels).T
 
 
 def decompress(cfg: LowRankConfig, Uw: np.ndarray, Vw: np.ndarray, recon: np.ndarray) -> np.ndarray:

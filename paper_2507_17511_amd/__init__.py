@@ -27,6 +27,7 @@ CF_SCALE_CHANNEL, CF_SCALE_GROUP, CF_SCALE_RANK1, CF_SPARSE_NM, CF_LOWRANK = 0, 
 CF_EF_RECON, CF_EF_LITERAL, CF_EF_OFF, CF_EF_NAIVE = 0, 1, 2, 3
 CF_FLAG_SINGLE_PASS = 0x1
 CF_FLAG_TWO_KERNEL = 0x2
+CF_FLAG_LOWRANK_INT4 = 0x4
 
 EXPORTS = ["cf_sizes", "cf_workspace_bytes", "cf_init", "cf_warmup", "cf_set_warm", "cf_compress",
            "cf_decompress", "cf_step_fused", "cf_destroy", "cf_status_string", "cf_last_hip_error",

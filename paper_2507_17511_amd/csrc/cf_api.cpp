@@ -42,7 +42,7 @@ cf_status check_opts(const cf_options *o, cf_options &out)
     if (!o) return CF_OK;
     if (o->ef != CF_EF_RECON && o->ef != CF_EF_LITERAL && o->ef != CF_EF_OFF && o->ef != CF_EF_NAIVE) return CF_ERR_UNSUPPORTED;
     if (o->err_dtype != CF_F32 && o->err_dtype != CF_BF16) return CF_ERR_UNSUPPORTED;
-    if (o->flags & ~(CF_FLAG_SINGLE_PASS | CF_FLAG_TWO_KERNEL)) return CF_ERR_UNSUPPORTED;
+    if (o->flags & ~(CF_FLAG_SINGLE_PASS | CF_FLAG_TWO_KERNEL | CF_FLAG_LOWRANK_INT4)) return CF_ERR_UNSUPPORTED;
     if (o->tile_rows != 0 && o->tile_rows != 8 && o->tile_rows != 16 && o->tile_rows != 32 && o->tile_rows != 64)
         return CF_ERR_UNSUPPORTED;
     if (o->encode_rows < 0 || o->encode_rows > 64) return CF_ERR_UNSUPPORTED;
@@ -131,7 +131,7 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
         v.dtype = d.dtype;
         v.bits = d.bits;
         v.scale = d.scale;
-        v.nm_block = d.scale == CF_SPARSE_NM ? (uint32_t)d.group : 0u;
+        v.nm_block = d.scale == CF_SPARSE_NM ? (uint32_t)d.group : (d.scale == CF_LOWRANK && (o.flags & CF_FLAG_LOWRANK_INT4)) ? 4u : 0u;
         v.rb_rows = rb;
         v.n_rowblocks = (int32_t)((d.n_tokens + rb - 1) / rb);
         v.n_colblocks = (v.n_chunks + kTileThreads - 1) / kTileThreads;
@@ -478,6 +478,10 @@ cf_status run_lowrank_sender(cf_ctx *ctx, int32_t first, int32_t count, const Ba
     }
     e = launch(ctx, s, "k_lr_project", [&] { return launch_lr_project(v, r, true, 0, s); });
     if (e != hipSuccess) return device_fail(ctx, e);
+    if (ctx->opts.flags & CF_FLAG_LOWRANK_INT4) {
+        e = launch(ctx, s, "k_lr_quant_u", [&] { return launch_lr_quant_u(v, r, s); });
+        if (e != hipSuccess) return device_fail(ctx, e);
+    }
     e = launch(ctx, s, "k_lr_apply", [&] { return launch_lr_encode(v, r, ctx->opts.err_dtype, fused, s); });
     if (e != hipSuccess) return device_fail(ctx, e);
     return CF_OK;
@@ -588,7 +592,8 @@ cf_status cf_sizes(const cf_tensor_desc *desc, const cf_options *opts, size_t *c
     if ((st = check_desc(*desc)) != CF_OK) return st;
     const size_t n = (size_t)desc->n_tokens, c = (size_t)desc->n_channels;
     if (desc->scale == CF_LOWRANK) {        // U [N, 32] then V [C, 32] in the storage dtype; the scales entry is the input Q0 [C, 32] fp32
-        if (codes_bytes) *codes_bytes = (n + c) * kLowRankRank * dtype_size(desc->dtype);
+        if (codes_bytes)                    // 4-bit factors: 16 nibble bytes and one fp32 scale per factor row
+            *codes_bytes = (o.flags & CF_FLAG_LOWRANK_INT4) ? (n + c) * 20 : (n + c) * kLowRankRank * dtype_size(desc->dtype);
         if (scales_bytes) *scales_bytes = c * kLowRankRank * sizeof(float);
     } else if (desc->scale == CF_SPARSE_NM) {      // one mask byte per block of 8, then (16-byte aligned) bits values per block
         if (codes_bytes)

@@ -75,6 +75,7 @@ struct alignas(16) TensorDev {
     uint32_t dec_pad_;
     // rank-1 scales: per-row sums of |z| over each 1024-channel tile, rowpart[N][n_colblocks]
     uint32_t nm_block;      // N:M sparsifier: M, channels per block (8 or 16)
+                            // low-rank compressor: 4 when the factors travel as 4-bit integers, else 0
     uint64_t rowpart_off;
     // low-rank compressor: P = A Q [N][32], Z = A^T P [C][32], Q in the order k_lr_project reads it (all fp32)
     uint64_t lr_p_off, lr_z_off, lr_q_off;
@@ -142,6 +143,8 @@ constexpr int kLowRankMaxChannels = 3072;
 hipError_t launch_lr_orth(const BatchView &v, const LaunchRange &r, bool from_q0, int min_iters, hipStream_t s);
 hipError_t launch_lr_project(const BatchView &v, const LaunchRange &r, bool wire, int min_iters, hipStream_t s);
 hipError_t launch_lr_backproject(const BatchView &v, const LaunchRange &r, int min_iters, hipStream_t s);
+// 4-bit factors: U from P (fp32, in the workspace) onto the wire, after the last projection
+hipError_t launch_lr_quant_u(const BatchView &v, const LaunchRange &r, hipStream_t s);
 hipError_t launch_lr_encode(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, hipStream_t s);
 hipError_t launch_lr_decode(const BatchView &v, const LaunchRange &r, hipStream_t s);
 

@@ -68,6 +68,40 @@ __device__ __forceinline__ uint8_t *wire_v(const TensorDev &d, const TensorPtrs 
     return p.codes + d.n_tokens * kRank * (d.dtype == BF16 ? 2 : 4);
 }
 
+// Factors as 4-bit integers (Sec. 3.4 and App. D name INT4 factors; the format is this library's): every
+// factor row of 32 entries has one fp32 scale s = absmax / 7 and travels as 32 nibbles q = clamp(rint(f / s),
+// -7, 7), two's complement, entry k in byte k / 2, even k in the low nibble -- the 4-bit group quantiser of
+// the activations with the rank index in place of the channel.  On the wire: U nibbles [N, 16 bytes],
+// V nibbles [C, 16 bytes], U scales [N] fp32, V scales [C] fp32.
+__device__ __forceinline__ bool factors_int4(const TensorDev &d) { return d.nm_block == 4u; }
+__device__ __forceinline__ uint8_t *wire4_u(const TensorPtrs &p) { return p.codes; }
+__device__ __forceinline__ uint8_t *wire4_v(const TensorDev &d, const TensorPtrs &p) { return p.codes + d.n_tokens * 16; }
+__device__ __forceinline__ float *wire4_u_scales(const TensorDev &d, const TensorPtrs &p)
+{
+    return reinterpret_cast<float *>(p.codes + (d.n_tokens + (int64_t)d.n_channels) * 16);
+}
+__device__ __forceinline__ float *wire4_v_scales(const TensorDev &d, const TensorPtrs &p) { return wire4_u_scales(d, p) + d.n_tokens; }
+
+// One factor row (32 fp32 values) onto the wire.
+__device__ __forceinline__ void quantise_factor_row(const float (&f)[kRank], uint8_t *nibbles16, float *scale)
+{
+    float amax = 0.0f;
+#pragma unroll
+    for (int k = 0; k < kRank; ++k) amax = fmaxf(amax, fabsf(f[k]));
+    const float s = amax / 7.0f;
+    u32x4 w;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        F8 z, sv, dq;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { z.v[k] = f[8 * g + k]; sv.v[k] = s; }
+        const uint32_t packed = quant8<4>(z, sv, dq);
+        if (g == 0) w.x = packed; else if (g == 1) w.y = packed; else if (g == 2) w.z = packed; else w.w = packed;
+    }
+    *gmut<u32x4>(nibbles16) = w;
+    *gmut<float>(scale) = s;
+}
+
 // ---------------------------------------------------------------- P = A Q  (and U on the wire)
 
 // A wave owns 64 tokens (two accumulator tiles that share the Q operand), a workgroup of two waves 128, and walks
@@ -168,7 +202,7 @@ __device__ __forceinline__ void lr_project_body(const BatchView &v, const Tensor
             const float val = half ? acc1[i] : acc0[i];
             if (rr < d.n_tokens) {
                 P[rr * kRank + m] = val;
-                if (wire) {
+                if (wire && !factors_int4(d)) {     // 4-bit factors are quantised from P by k_lr_quant_u
                     if (DT == BF16) gmut<uint16_t>(U)[rr * kRank + m] = (uint16_t)bf16_rne(val);
                     else gmut<float>(U)[rr * kRank + m] = val;
                 }
@@ -392,18 +426,54 @@ __global__ __launch_bounds__(kOrthThreads) void k_lr_orth(BatchView v, LaunchRan
 #pragma unroll
         for (int n = 0; n < kRank; ++n) {
             qs[((int64_t)s * 64 + hh * 32 + n) * 16 + j] = a[rr][n];
+            if (factors_int4(d)) continue;
             if (d.dtype == BF16) gmut<uint16_t>(V)[(int64_t)ch * kRank + n] = (uint16_t)bf16_rne(a[rr][n]);
             else gmut<float>(V)[(int64_t)ch * kRank + n] = a[rr][n];
         }
+        if (factors_int4(d)) quantise_factor_row(a[rr], wire4_v(d, p) + (int64_t)ch * 16, wire4_v_scales(d, p) + ch);
     }
+}
+
+// 4-bit factors: U = P (fp32, in the workspace) onto the wire, one lane per token.
+__global__ __launch_bounds__(256) void k_lr_quant_u(BatchView v, LaunchRange r)
+{
+    const int t = r.first + (int)blockIdx.y;
+    const TensorDev d = v.descs[t];
+    if (d.scale != LOWRANK || !factors_int4(d)) return;
+    const TensorPtrs p = v.ptrs[t];
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (row >= d.n_tokens) return;
+    const CF_GLOBAL f32x4 *src = gconst<f32x4>(v.workspace + d.lr_p_off) + row * (kRank / 4);
+    float f[kRank];
+#pragma unroll
+    for (int k = 0; k < kRank / 4; ++k) {
+        const f32x4 w = src[k];
+        f[4 * k] = w.x; f[4 * k + 1] = w.y; f[4 * k + 2] = w.z; f[4 * k + 3] = w.w;
+    }
+    quantise_factor_row(f, wire4_u(p) + row * 16, wire4_u_scales(d, p) + row);
 }
 
 // ---------------------------------------------------------------- D = U V^T, error and reconstruction
 
 // 16 consecutive rank entries (16 * h ...) of one row of a factor on the wire, widened.
-template <int DT> __device__ __forceinline__ void factor16(const uint8_t *base, int64_t row, int h, bool valid, float (&out)[16])
+// int4: `base` holds rows of 16 nibble bytes and `scales` one fp32 per row.
+template <int DT> __device__ __forceinline__ void factor16(const uint8_t *base, const float *scales, bool int4, int64_t row, int h,
+                                                           bool valid, float (&out)[16])
 {
-    load16<DT>(base, (valid ? row : 0) * kRank + 16 * h, out);      // row 0 always exists; its values are discarded
+    const int64_t r0 = valid ? row : 0;                             // row 0 always exists; its values are discarded
+    if (int4) {                                                     // uniform over the launch's tensor
+        const u32x2 w = *gconst<u32x2>(base + r0 * 16 + 8 * h);
+        const float s = *gconst<float>(scales + r0);
+        F8 sv, lo, hi;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) sv.v[k] = s;
+        dequant8<4>(w.x, sv, lo);
+        dequant8<4>(w.y, sv, hi);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { out[k] = lo.v[k]; out[8 + k] = hi.v[k]; }
+    } else {
+        load16<DT>(base, r0 * kRank + 16 * h, out);
+    }
 #pragma unroll
     for (int k = 0; k < 16; ++k) out[k] = valid ? out[k] : 0.0f;
 }
@@ -432,8 +502,10 @@ __device__ __forceinline__ void lr_apply_body(const TensorDev &d, const TensorPt
     if (tok_base >= d.n_tokens) return;                     // uniform over the wave
     const int64_t C = d.n_channels;
     float u[16];
-    factor16<DT>(wire_u(p), tok_base + n, h, tok_base + n < d.n_tokens, u);
-    const uint8_t *V = wire_v(d, p);
+    const bool int4 = factors_int4(d);
+    factor16<DT>(int4 ? wire4_u(p) : wire_u(p), wire4_u_scales(d, p), int4, tok_base + n, h, tok_base + n < d.n_tokens, u);
+    const uint8_t *V = int4 ? wire4_v(d, p) : wire_v(d, p);
+    const float *Vs = wire4_v_scales(d, p);
     const int sub_lo = span * (kApplySpan / 32);
     const int n_sub = d.n_channels / 32 < sub_lo + kApplySpan / 32 ? d.n_channels / 32 : sub_lo + kApplySpan / 32;
     const int chunk = lane & 7, trow = lane >> 3;           // row-major side: 8 chunks of 8 channels, 8 tokens per sweep
@@ -443,7 +515,7 @@ __device__ __forceinline__ void lr_apply_body(const TensorDev &d, const TensorPt
         // tile's x and recon, which are only needed once D has come back through the patch.
         float vv[2][16];
 #pragma unroll
-        for (int c = 0; c < 2; ++c) factor16<DT>(V, (int64_t)(sub0 + (c < cnt ? c : 0)) * 32 + n, h, true, vv[c]);
+        for (int c = 0; c < 2; ++c) factor16<DT>(V, Vs, int4, (int64_t)(sub0 + (c < cnt ? c : 0)) * 32 + n, h, true, vv[c]);
         Raw8<DT> xr[4], br[4];
         bool live[4];
 #pragma unroll
@@ -551,6 +623,14 @@ hipError_t launch_lr_backproject(const BatchView &v, const LaunchRange &r, int m
 static unsigned apply_blocks(const LaunchRange &r)
 {
     return (unsigned)((r.lr_max_tokens + 127) / 128) * (unsigned)((r.lr_max_channels + kApplySpan - 1) / kApplySpan);
+}
+
+hipError_t launch_lr_quant_u(const BatchView &v, const LaunchRange &r, hipStream_t s)
+{
+    if (r.count == 0 || r.lr_max_tokens == 0) return hipSuccess;
+    dim3 grid((unsigned)((r.lr_max_tokens + 255) / 256), (unsigned)r.count);
+    hipLaunchKernelGGL(k_lr_quant_u, grid, dim3(256), 0, s, v, r);
+    return hipGetLastError();
 }
 
 hipError_t launch_lr_encode(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, hipStream_t s)

@@ -26,7 +26,7 @@ import torch
 import paper_2507_17511_amd as cf
 from paper_2507_17511_amd.session import CodecSession
 
-CODECS: List[Tuple[str, int, int, int]] = [        # name, bits, scale kind, group
+CODECS: List[Tuple[str, int, int, int]] = [        # name, bits, scale kind, group (a name ending in "INT4 factors" sets that flag)
     ("4-bit, group-128 scales", 4, cf.CF_SCALE_GROUP, 128),
     ("4-bit, channel scales", 4, cf.CF_SCALE_CHANNEL, 128),
     ("2-bit, channel scales", 2, cf.CF_SCALE_CHANNEL, 128),
@@ -38,6 +38,7 @@ CODECS: List[Tuple[str, int, int, int]] = [        # name, bits, scale kind, gro
     ("1 of 8 kept", 1, cf.CF_SPARSE_NM, 8),
     ("rank 32, T = 1", 1, cf.CF_LOWRANK, 32),
     ("rank 32, T = 2", 2, cf.CF_LOWRANK, 32),
+    ("rank 32, T = 2, INT4 factors", 2, cf.CF_LOWRANK, 32),
 ]
 
 
@@ -62,9 +63,10 @@ def run(n_tokens: int = 1024, n_channels: int = 1024, steps: int = 28, rho: floa
     out = {}
     for name, bits, scale, group in CODECS:
         d = cf.desc(n_tokens, n_channels, cf.CF_BF16, bits, scale, group)
-        codes_bytes, scales_bytes, recon_bytes, _ = cf.cf_sizes(d)
+        opts = cf.options(flags=cf.CF_FLAG_LOWRANK_INT4 if name.endswith("INT4 factors") else 0)
+        codes_bytes, scales_bytes, recon_bytes, _ = cf.cf_sizes(d, opts)
         wire = codes_bytes + (0 if scale == cf.CF_LOWRANK else scales_bytes)      # the low-rank start matrix does not travel
-        sess = CodecSession([d], cf.options(), device=device)
+        sess = CodecSession([d], opts, device=device)
         errs = []
         try:
             sess.warmup([xs[0]])
@@ -90,9 +92,9 @@ def main() -> None:
     a = ap.parse_args()
     res = run(a.tokens, a.channels, a.steps, a.rho)
     print(f"[{a.tokens}, {a.channels}] bf16, {a.steps} steps, rho = {a.rho}; error relative to the stream's step-to-step change")
-    print(f"{'compressor':<28} {'ratio':>8} {'total error':>12}")
+    print(f"{'compressor':<30} {'ratio':>8} {'total error':>12}")
     for name, r in res.items():
-        print(f"{name:<28} {r['ratio']:>7.1f}x {r['total_error']:>12.4f}")
+        print(f"{name:<30} {r['ratio']:>7.1f}x {r['total_error']:>12.4f}")
 
 
 if __name__ == "__main__":

@@ -122,6 +122,16 @@ def test_calls_on_null_context_fail_cleanly():
     assert cf.cf_last_hip_error(None) == 0
 
 
+def test_lowrank_int4_factor_sizes():
+    o = cf.options(flags=cf.CF_FLAG_LOWRANK_INT4)
+    d = cf.desc(4096, 3072, cf.CF_BF16, 1, cf.CF_LOWRANK, 32)
+    assert cf.cf_sizes(d, o)[0] == (4096 + 3072) * 20              # 16 nibble bytes and one fp32 scale per factor row
+    assert cf.cf_sizes(d)[0] == (4096 + 3072) * 64
+    with pytest.raises(cf.CFError) as ei:
+        cf.cf_sizes(d, cf.options(flags=0x8))
+    assert ei.value.status == cf.CF_ERR_UNSUPPORTED
+
+
 def test_nm_sizes_and_block_lengths():
     for group in (4, 32):
         with pytest.raises(cf.CFError) as ei:

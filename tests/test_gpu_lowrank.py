@@ -74,7 +74,13 @@ def check_step(tag, cfg, sess, t, x, recon_before, q0, wire_tol=1e-3):
     # the subspace itself (independent of the basis)
     proj_gap = np.linalg.norm(V64 @ V64.T - Vo64 @ Vo64.T)
     assert proj_gap < (0.05 if dt == lr.BF16 else 1e-3), f"{tag}: projector differs by {proj_gap:.2e}"
-    # from the GPU's own factors on: D, e, recon
+    check_from_own_factors(tag, cfg, sess, t, x, recon_before, U64, V64, erro)
+    return float(np.abs(U64 - Uo64).max() / np.abs(Uo64).max()), float(np.abs(V64 - Vo64).max())
+
+
+def check_from_own_factors(tag, cfg, sess, t, x, recon_before, U64, V64, erro, loose_scale=1.0):
+    """D, e and recon against an fp64 evaluation of the factors the GPU itself put on the wire."""
+    n, c, dt = cfg.n_tokens, cfg.n_channels, cfg.dtype
     A = lr.widen(x, dt).reshape(n, c) - lr.widen(recon_before, dt).reshape(n, c)
     D = U64 @ V64.T
     terms = np.abs(U64) @ np.abs(V64).T
@@ -85,9 +91,12 @@ def check_step(tag, cfg, sess, t, x, recon_before, q0, wire_tol=1e-3):
     half_ulp = (2.0 ** -8 if dt == lr.BF16 else 2.0 ** -23) * np.abs(target) * 1.01
     assert np.all(np.abs(recon - target) <= half_ulp + 1e-5 * terms + 1e-30), f"{tag}: recon != recon + U V^T"
     # and the oracle's end result, loosely (it went through the oracle's own factors)
-    loose = (2e-2 if dt == lr.BF16 else 1e-3) * np.abs(A).max()
+    if loose_scale is None:      # INT4 factors: one nibble decided the other way moves a whole row or column of D by a step
+        gap = np.linalg.norm(err - erro) / max(np.linalg.norm(A), 1e-30)
+        assert gap <= 0.05, f"{tag}: error buffer {gap:.2e} (Frobenius, relative to the residual) from the oracle's"
+        return
+    loose = (2e-2 if dt == lr.BF16 else 1e-3) * np.abs(A).max() * loose_scale
     assert np.abs(err - erro).max() <= loose, f"{tag}: error buffer {np.abs(err - erro).max():.2e} from the oracle's"
-    return float(np.abs(U64 - Uo64).max() / np.abs(Uo64).max()), float(np.abs(V64 - Vo64).max())
 
 
 @pytest.mark.parametrize("dtype", [cf.CF_F32, cf.CF_BF16])
@@ -116,6 +125,67 @@ def test_lowrank_parity(dtype, iters, mode):
             say(f"   factors within {du:.1e} (U, relative) and {dv:.1e} (V, absolute) of the oracle")
         finally:
             sess.close()
+
+
+def split_wire_int4(codes: np.ndarray, n, c):
+    """U nibbles [N, 16], V nibbles [C, 16], U scales [N] fp32, V scales [C] fp32."""
+    flat = codes.reshape(-1)
+    assert flat.size == (n + c) * 20
+    un, vn = flat[:n * 16].reshape(n, 16), flat[n * 16:(n + c) * 16].reshape(c, 16)
+    sc = flat[(n + c) * 16:].view(np.float32)
+    return (un.copy(), sc[:n].copy()), (vn.copy(), sc[n:].copy())
+
+
+@pytest.mark.parametrize("dtype", [cf.CF_F32, cf.CF_BF16])
+@pytest.mark.parametrize("mode", ["fused", "split"])
+def test_lowrank_int4_factors(dtype, mode):
+    """CF_FLAG_LOWRANK_INT4: the factors travel as nibbles with one fp32 scale per factor row.  The scales must
+    agree with the oracle's to fp32 rounding and the nibbles must be the oracle's except where the fp32 factor
+    sits next to a rounding boundary (at most a few per thousand, off by one step); D, e and recon are then
+    checked against the GPU's own travelled factors as for the other wire formats."""
+    for k, (n, c) in enumerate([(96, 128), (203, 1024), (300, 3072), (1, 64), (517, 96)]):
+        say(f"lowrank int4 factors dtype={dtype} mode={mode} N={n} C={c}")
+        d = cf.desc(n, c, dtype, 1 + k % 2, cf.CF_LOWRANK, R)
+        cfg = lr.LowRankConfig(n, c, dtype=dtype, rank=R, iters=1 + k % 2, factor_bits=4)
+        xs = stream(n, c, dtype, 4, 1300 + k)
+        q0s = start_matrices(c, 4, 1350 + k)
+        sess = CodecSession([d], cf.options(flags=cf.CF_FLAG_LOWRANK_INT4), device=DEV)
+        try:
+            assert sess.codes[0].numel() * sess.codes[0].element_size() == (n + c) * 20
+            sess.warmup([xs[0]])
+            for s in range(1, 4):
+                before = as_numpy(sess.recon[0]).copy()
+                sess.scales[0].copy_(q0s[s].reshape(-1))
+                if mode == "fused":
+                    sess.step_fused([xs[s]])
+                else:
+                    sess.compress([xs[s]])
+                    sess.decompress()
+                cf.cf_check_device(sess.ctx, sess.stream_handle)
+                x = as_numpy(xs[s])
+                Ug, Vg = split_wire_int4(as_numpy(sess.codes[0]).view(np.uint8), n, c)
+                Uo, Vo, erro, _ = lr.step(cfg, x, before, as_numpy(q0s[s]))
+                flips = 0
+                for name, (gn, gs), (on, os_) in (("U", Ug, Uo), ("V", Vg, Vo)):
+                    big = np.abs(os_).max()
+                    assert np.all(np.abs(gs - os_) <= 1e-3 * big), f"{name} scales off by {np.abs(gs - os_).max() / big:.2e}"
+                    got, want = lr.dequantise_rows(gn, gs), lr.dequantise_rows(on, os_)
+                    step = np.maximum(gs, os_).astype(np.float64)[:, None]
+                    off = np.abs(got - want)
+                    assert np.all(off <= step * 1.001 + 1e-3 * big), f"{name}: a nibble is off by more than one step"
+                    flips += int(np.count_nonzero(off > 0.5 * step + 1e-3 * big))
+                assert flips <= 2 + 0.005 * (n + c) * R, f"{flips} nibbles differ from the oracle's"
+                U64, V64 = lr.dequantise_rows(*Ug), lr.dequantise_rows(*Vg)
+                check_from_own_factors(f"int4 N{n}C{c} step {s}", cfg, sess, 0, x, before, U64, V64, erro, loose_scale=None)
+            say(f"   {flips} of {(n + c) * R} nibbles differ from the oracle's at the last step")
+        finally:
+            sess.close()
+
+
+def test_lowrank_int4_sizes():
+    o = cf.options(flags=cf.CF_FLAG_LOWRANK_INT4)
+    assert cf.cf_sizes(cf.desc(4096, 3072, cf.CF_BF16, 1, cf.CF_LOWRANK, R), o)[0] == (4096 + 3072) * 20
+    assert cf.cf_sizes(cf.desc(4096, 3072, cf.CF_BF16, 1, cf.CF_LOWRANK, R))[0] == (4096 + 3072) * 64
 
 
 def test_lowrank_exact_for_residuals_of_small_rank():

@@ -632,3 +632,6 @@ def test_ratio_study_trends():
     assert abs(r["2-bit, channel scales"] - n * c * 2 / (n * c / 4 + 4 * c)) < 1e-9
     assert abs(r["2 of 8 kept"] - 16 / 5) < 0.01 and abs(r["1 of 8 kept"] - 16 / 3) < 0.01
     assert abs(r["rank 32, T = 1"] - 512 * 1024 / (32 * (512 + 1024))) < 0.01
+    # INT4 factors: 20 bytes per factor row instead of 64, for a few percent more error
+    assert abs(r["rank 32, T = 2, INT4 factors"] - 512 * 1024 * 2 / (20 * (512 + 1024))) < 0.01
+    assert e["rank 32, T = 2"] <= e["rank 32, T = 2, INT4 factors"] <= e["rank 32, T = 2"] * 1.25

@@ -119,3 +119,62 @@ def test_step_wiring_and_invariant(dtype):
         assert np.linalg.matrix_rank(lr.decode(cfg, Uw, Vw)) <= 32
         assert np.linalg.norm(err) < np.linalg.norm(A)
         recon = new
+
+
+# ---------------------------------------------------------------- INT4 factors (Sec. 3.4 / App. D name them; format: the oracle's header)
+
+def test_int4_factor_rows_round_trip_exactly_when_representable():
+    """Rows whose entries are k * 2^m, |k| <= 7, with absmax 7 * 2^m: the scale is 2^m and nothing is lost."""
+    rng = np.random.default_rng(20)
+    k = rng.integers(-7, 8, size=(50, 32))
+    k[:, 0] = 7 * rng.choice([-1, 1], size=50)
+    m = rng.integers(-6, 7, size=(50, 1))
+    f = k * 2.0 ** m
+    nib, s = lr.quantise_rows(f)
+    assert np.array_equal(s, (2.0 ** m[:, 0]).astype(np.float32))
+    assert np.array_equal(lr.dequantise_rows(nib, s), f)
+
+
+def test_int4_factor_bytes_by_hand():
+    """Entry k sits in byte k // 2, even k in the low nibble, two's complement."""
+    f = np.zeros((1, 32))
+    f[0, :6] = [7, -7, 1, -1, 3, -8]          # -8 clamps to -7
+    f[0, 31] = 2
+    f[0, 0] = 7                                # absmax would be 8: put it back to 7 for a scale of 1
+    f[0, 5] = -7
+    nib, s = lr.quantise_rows(f)
+    assert s[0] == np.float32(1.0)
+    assert list(nib[0, :3]) == [0x97, 0xF1, 0x93] and nib[0, 15] == 0x20 and not nib[0, 3:15].any()
+
+
+def test_int4_zero_row_and_error_bound_and_textbook_expression():
+    rng = np.random.default_rng(21)
+    f = rng.standard_normal((300, 32)) * np.exp(rng.standard_normal((300, 1)) * 3)
+    f[7] = 0.0
+    nib, s = lr.quantise_rows(f)
+    assert s[7] == 0 and not nib[7].any()
+    back = lr.dequantise_rows(nib, s)
+    f32 = f.astype(np.float32).astype(np.float64)
+    assert np.all(np.abs(back - f32) <= 0.5 * s[:, None].astype(np.float64) * (1 + 1e-6))
+    # the symmetric absmax quantiser as a library expression (torch.round rounds half to even)
+    t = torch.from_numpy(f.astype(np.float32))
+    st = t.abs().amax(dim=1, keepdim=True) / 7
+    want = torch.where(st > 0, torch.clamp(torch.round(t / torch.where(st > 0, st, torch.ones_like(st))), -7, 7) * st, torch.zeros_like(t))
+    assert np.array_equal(back.astype(np.float32), want.numpy())
+
+
+def test_int4_factors_keep_the_recursion_invariant_and_cost_accuracy_gracefully():
+    """recon_t + e_t = x_t holds with quantised factors (D is whatever travelled), and the extra error is of the
+    size of the quantisation step: a few percent of the factors' share, not a different regime."""
+    rng = np.random.default_rng(22)
+    n, c = 160, 128
+    x0 = rng.standard_normal((n, c)).astype(np.float32)
+    x1 = (x0 + 0.05 * rand_lowrank(rng, n, c, 40, noise=0.01, decay=0.9)).astype(np.float32)
+    q0 = rng.standard_normal((c, 32))
+    errs = {}
+    for fb in (0, 4):
+        cfg = lr.LowRankConfig(n, c, dtype=lr.F32, rank=32, iters=2, factor_bits=fb)
+        Uw, Vw, err, recon = lr.step(cfg, x1, x0.copy(), q0)
+        assert np.allclose(recon.astype(np.float64) + err, x1, atol=1e-5)
+        errs[fb] = np.linalg.norm(err)
+    assert errs[0] < errs[4] < 0.5 * np.linalg.norm(x1 - x0)
