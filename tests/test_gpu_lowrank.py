@@ -284,6 +284,53 @@ def test_lowrank_in_a_mixed_batch_and_receiver():
         recv.close()
 
 
+def test_lowrank_int4_in_a_mixed_batch_and_receiver():
+    """The INT4-factor context next to quantised and sparsified tensors: those are untouched by the flag (bit-exact
+    against the oracle), and a receiver fed the wire reaches the sender's reconstruction bit for bit."""
+    from helpers import OracleState, compare_tensor
+    opts = cf.options(flags=cf.CF_FLAG_LOWRANK_INT4)
+    descs = [cf.desc(203, 1024, cf.CF_BF16, 1, cf.CF_LOWRANK, R), cf.desc(130, 264, cf.CF_BF16, 2, cf.CF_SCALE_CHANNEL),
+             cf.desc(96, 128, cf.CF_F32, 2, cf.CF_LOWRANK, R), cf.desc(67, 3072, cf.CF_BF16, 2, cf.CF_SPARSE_NM, 16)]
+    xs = [stream(int(d.n_tokens), int(d.n_channels), int(d.dtype), 3, 170 + t) for t, d in enumerate(descs)]
+    q0 = {0: start_matrices(1024, 3, 15), 2: start_matrices(128, 3, 16)}
+    send, recv = CodecSession(descs, opts, device=DEV), CodecSession(descs, opts, device=DEV)
+    orc = OracleState(descs, opts, [1, 3])
+    try:
+        first = [x[0] for x in xs]
+        send.warmup(first)
+        recv.warmup(first)
+        for t in (1, 3):
+            orc.warmup(t, as_numpy(first[t]))
+        for s in (1, 2):
+            now = [x[s] for x in xs]
+            before = {t: as_numpy(send.recon[t]).copy() for t in (0, 2)}
+            for t in (0, 2):
+                send.scales[t].copy_(q0[t][s].reshape(-1))
+            send.step_fused(now)
+            cf.cf_check_device(send.ctx, send.stream_handle)
+            for t in (0, 2):
+                n, c = int(descs[t].n_tokens), int(descs[t].n_channels)
+                cfg = lr.LowRankConfig(n, c, dtype=int(descs[t].dtype), rank=R, iters=int(descs[t].bits), factor_bits=4)
+                Ug, Vg = split_wire_int4(as_numpy(send.codes[t]).view(np.uint8), n, c)
+                _, _, erro, _ = lr.step(cfg, as_numpy(now[t]), before[t], as_numpy(q0[t][s]))
+                check_from_own_factors(f"int4 mixed t{t} step {s}", cfg, send, t, as_numpy(now[t]), before[t],
+                                       lr.dequantise_rows(*Ug), lr.dequantise_rows(*Vg), erro, loose_scale=None)
+            for t in (1, 3):
+                orc.step(t, as_numpy(now[t]))
+                compare_tensor(f"int4 mixed step {s}", send, orc, t)
+            for t in range(len(descs)):
+                recv.codes[t].copy_(send.codes[t])
+                if recv.scales[t].numel():
+                    recv.scales[t].copy_(send.scales[t])
+            recv.decompress()
+            cf.cf_check_device(recv.ctx, recv.stream_handle)
+            for t in range(len(descs)):
+                assert torch.equal(recv.recon[t], send.recon[t]), f"receiver differs on tensor {t} at step {s}"
+    finally:
+        send.close()
+        recv.close()
+
+
 def test_lowrank_rejections():
     for d, status in ((cf.desc(64, 100, cf.CF_BF16, 1, cf.CF_LOWRANK, R), cf.CF_ERR_SHAPE),       # C not a multiple of 32
                       (cf.desc(64, 4096, cf.CF_BF16, 1, cf.CF_LOWRANK, R), cf.CF_ERR_SHAPE),      # C above 3072
