@@ -309,7 +309,10 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
             if (i < row1 && cvalid) {
                 int64_t e = i * C + (int64_t)chunk * kChunk;
                 xr[u].load(p.x, e);
-                if (EF != EF_NAIVE) br[u].load(p.recon, e); else br[u].zero();
+                // fused: the line is written back by this workgroup, and the streaming hint on its load pays (cfg4 4.09 -> 3.98 ms)
+                if (EF == EF_NAIVE) br[u].zero();
+                else if (FUSED) br[u].load_stream(p.recon, e);
+                else br[u].load(p.recon, e);
                 if (EF == EF_LITERAL || EF == EF_OFF) er[u].load(p.err, e); else er[u].zero();
             } else {
                 xr[u].zero();
@@ -391,7 +394,10 @@ __device__ __forceinline__ void nm_encode_tile(const TileCtx &c)
             if (i < row1) {
                 const int64_t e = i * C + (int64_t)chunk * kChunk;
                 xr[u].load(p.x, e);
-                if (EF != EF_NAIVE) br[u].load(p.recon, e); else br[u].zero();
+                // fused: the line is written back by this workgroup, and the streaming hint on its load pays (cfg4 4.09 -> 3.98 ms)
+                if (EF == EF_NAIVE) br[u].zero();
+                else if (FUSED) br[u].load_stream(p.recon, e);
+                else br[u].load(p.recon, e);
                 if (EF == EF_LITERAL || EF == EF_OFF) er[u].load(p.err, e); else er[u].zero();
             } else {
                 xr[u].zero();
@@ -531,7 +537,8 @@ __device__ __forceinline__ void decode_tile(const TileCtx &c, bool replace)
         for (int u = 0; u < U; ++u) {
             int64_t i = i0 + u;
             if (i < row1) {
-                if (!replace) br[u].load(p.recon, i * C + (int64_t)chunk * kChunk); else br[u].zero();
+                // streaming hint: the line is written back by this workgroup (measured 5 % faster than a plain load)
+                if (!replace) br[u].load_stream(p.recon, i * C + (int64_t)chunk * kChunk); else br[u].zero();
                 pk[u] = load_codes<BITS>(p.codes + i * row_bytes, chunk);
                 sg[u] = (MODE == 1) ? gconst<float>(p.scales)[i * n_groups + (chunk >> 4)]
                                     : (MODE == 2) ? gconst<float>(p.scales)[C + i] : 0.0f;
@@ -585,7 +592,8 @@ __device__ __forceinline__ void nm_decode_tile(const TileCtx &c, bool replace)
         for (int u = 0; u < U; ++u) {
             const int64_t i = i0 + u;
             if (i < row1) {
-                if (!replace) br[u].load(p.recon, i * C + (int64_t)chunk * kChunk); else br[u].zero();
+                // streaming hint: the line is written back by this workgroup (measured 5 % faster than a plain load)
+                if (!replace) br[u].load_stream(p.recon, i * C + (int64_t)chunk * kChunk); else br[u].zero();
                 mask[u] = load_codes<1>(p.codes + i * d.n_chunks, chunk);
                 if (PAIR) nm_load_values<DT, KEEP>(values + (i * (d.n_chunks >> 1) + (chunk >> 1)) * kValueBytes, vals[u]);
                 else nm_load_values<DT, KEEP>(values + (i * d.n_chunks + chunk) * kValueBytes, vals[u]);
