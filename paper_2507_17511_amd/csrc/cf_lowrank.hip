@@ -524,7 +524,8 @@ __device__ __forceinline__ void lr_apply_body(const TensorDev &d, const TensorPt
             live[it] = tok < d.n_tokens && chunk * 8 < cnt * 32;
             const int64_t e0 = tok * C + (int64_t)sub0 * 32 + chunk * 8;
             if (live[it]) {
-                br[it].load(p.recon, e0);
+                if (UPDATE) br[it].load_stream(p.recon, e0);        // written back below: the streaming hint pays
+                else br[it].load(p.recon, e0);
                 if (SENDER) xr[it].load(p.x, e0); else xr[it].zero();
             } else {
                 br[it].zero();
