@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void k_row_local(const u32x4 *x, u32x4 *r, u32
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n_vecs) return;
     const u32x4 a = __builtin_nontemporal_load((const GLOBAL u32x4 *)(x + i));
-    const u32x4 b = *(const GLOBAL u32x4 *)(r + i);
+    const u32x4 b = __builtin_nontemporal_load((const GLOBAL u32x4 *)(r + i));     // written back below: the hint pays
     *(GLOBAL u32x4 *)(e + 2 * i) = a - b;
     *(GLOBAL u32x4 *)(e + 2 * i + 1) = a ^ b;
     *(GLOBAL u32x4 *)(r + i) = a + b;
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void k_row_local_decode(u32x4 *r, const unsign
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n_vecs) return;
-    const u32x4 b = *(const GLOBAL u32x4 *)(r + i);
+    const u32x4 b = __builtin_nontemporal_load((const GLOBAL u32x4 *)(r + i));
     const unsigned c = *(const GLOBAL unsigned char *)(codes + i);
     *(GLOBAL u32x4 *)(r + i) = b + c;
 }
