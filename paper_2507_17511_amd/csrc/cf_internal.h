@@ -33,14 +33,16 @@ constexpr int kMaxUploadTensors = 64;                       // pointer sets per 
 // bf16 and a row's 1-bit codes of one item are 16 bytes.  Measured on 114 x
 // [4096, 3072] bf16: 64- / 128- / 256-channel stripes (8 / 16 / 32 items per
 // reduction group) 2.94 / 2.86 / 2.92 ms; 32-channel ones (64-byte segments)
-// were 50 % slower.
+// were 50 % slower.  Short tensors do better with the wide stripe (items half
+// as tall, twice as many per group): 57 x [1024, 3072] 0.417 -> 0.389 ms; a
+// context whose tallest channel-scale tensor makes at most 4 items per group
+// with the narrow stripe takes the wide one.
 constexpr int kPersistThreads = 256;
 #ifndef CF_STRIPE_CHANNELS
 #define CF_STRIPE_CHANNELS 128
 #endif
 constexpr int kStripeChannels = CF_STRIPE_CHANNELS;
-constexpr int kStripeChunks = kStripeChannels / kChunk;     // 16
-constexpr int kRowLanes = kPersistThreads / kStripeChunks;  // 16
+constexpr int kStripeChannelsWide = 2 * kStripeChannels;    // 256
 constexpr uint32_t kSpinLimit = 1u << 20;                   // bounded wait (about seconds), then the error flag
 
 // Static description of one tensor; built at cf_init, lives in the workspace.
@@ -149,9 +151,10 @@ hipError_t launch_lr_encode(const BatchView &v, const LaunchRange &r, int err_dt
 hipError_t launch_lr_decode(const BatchView &v, const LaunchRange &r, hipStream_t s);
 
 // Single-pass kernel (channel scales, CF_EF_RECON).  `grid` workgroups must be co-resident.
-int persistent_max_blocks_per_cu(int err_dtype, bool fused);
-hipError_t launch_single_pass(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, int grid, bool one_shot,
-                             hipStream_t s);
+int persistent_max_blocks_per_cu(int err_dtype, bool fused, bool wide);
+// wide: items of kStripeChannelsWide channels (the layout's choice, fixed at cf_init)
+hipError_t launch_single_pass(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, bool wide, int grid,
+                             bool one_shot, hipStream_t s);
 hipError_t launch_reset_partials(const BatchView &v, const LaunchRange &r, hipStream_t s);
 
 }  // namespace cf

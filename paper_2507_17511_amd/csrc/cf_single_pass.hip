@@ -6,8 +6,9 @@
 // keeps its share of x and recon in registers across the reduction instead:
 //   item  = p_rows x 128 channels of one tensor (256 rows of bf16, 128 of fp32:
 //           128 VGPRs of raw data per lane), owned by one workgroup of 256 lanes
-//           (16 chunks of 8 channels x 16 row-lanes);
-//   group = the items of one 128-channel stripe of one tensor; only they have
+//           (16 chunks of 8 channels x 16 row-lanes); for contexts of short
+//           tensors half as tall and 256 channels wide (32 chunks x 8 row-lanes);
+//   group = the items of one such stripe of one tensor; only they have
 //           to agree on that stripe's scales, so there is no grid-wide barrier,
 //           and different groups drift apart, which keeps HBM busy while some
 //           workgroups wait.
@@ -89,16 +90,19 @@ __device__ __forceinline__ float tree_over_published(int n, const float *mine, i
     return tree_top<LV, IS_MAX>(stack);
 }
 
-struct alignas(16) Shared {
-    float red[kRowLanes][kStripeChannels];
-    float scale[kStripeChannels];
+// SCH: channels per stripe (kStripeChannels or kStripeChannelsWide); the 256 lanes are SCH / 8 chunks across
+// by 2048 / SCH row-lanes down.
+template <int SCH> struct alignas(16) Shared {
+    float red[kPersistThreads / (SCH / kChunk)][SCH];
+    float scale[SCH];
     uint32_t ok;
 };
 
-template <int DT, int BITS, int ET, bool FUSED>
+template <int DT, int BITS, int ET, bool FUSED, int SCH>
 __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev &d, const TensorPtrs &p, int stripe,
-                                             int rb, Shared &sh)
+                                             int rb, Shared<SCH> &sh)
 {
+    constexpr int kStripeChannels = SCH, kStripeChunks = SCH / kChunk, kRowLanes = kPersistThreads / kStripeChunks;
     constexpr int RPT = (DT == BF16) ? CF_SP_RPT : CF_SP_RPT / 2;      // rows per lane
     constexpr bool IS_MAX = BITS == 4;
     const int tid = (int)threadIdx.x, cl = tid & (kStripeChunks - 1), rl = tid / kStripeChunks;
@@ -240,10 +244,10 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
     return true;
 }
 
-template <int ET, bool FUSED>
+template <int ET, bool FUSED, int SCH>
 __global__ __launch_bounds__(kPersistThreads, CF_SP_WAVES) void k_single_pass(BatchView v, LaunchRange r)
 {
-    __shared__ Shared sh;
+    __shared__ Shared<SCH> sh;
     // Workgroups are handed to the 8 XCDs in turn (blockIdx.x % 8).  Taking item b in workgroup b runs the
     // consecutive items of a reduction group on different XCDs at the same time, and a tensor whose row
     // blocks number a multiple of 8 keeps each of them on one XCD, whose L2 then sees all stripes of a code row.  Short tensors
@@ -262,13 +266,13 @@ __global__ __launch_bounds__(kPersistThreads, CF_SP_WAVES) void k_single_pass(Ba
         const int rb = (int)(local % (uint32_t)d.p_n_rb);
         bool ok;
         if (d.dtype == BF16) {
-            if (d.bits == 1) ok = persist_item<BF16, 1, ET, FUSED>(v, d, p, stripe, rb, sh);
-            else if (d.bits == 2) ok = persist_item<BF16, 2, ET, FUSED>(v, d, p, stripe, rb, sh);
-            else ok = persist_item<BF16, 4, ET, FUSED>(v, d, p, stripe, rb, sh);
+            if (d.bits == 1) ok = persist_item<BF16, 1, ET, FUSED, SCH>(v, d, p, stripe, rb, sh);
+            else if (d.bits == 2) ok = persist_item<BF16, 2, ET, FUSED, SCH>(v, d, p, stripe, rb, sh);
+            else ok = persist_item<BF16, 4, ET, FUSED, SCH>(v, d, p, stripe, rb, sh);
         } else {
-            if (d.bits == 1) ok = persist_item<F32, 1, ET, FUSED>(v, d, p, stripe, rb, sh);
-            else if (d.bits == 2) ok = persist_item<F32, 2, ET, FUSED>(v, d, p, stripe, rb, sh);
-            else ok = persist_item<F32, 4, ET, FUSED>(v, d, p, stripe, rb, sh);
+            if (d.bits == 1) ok = persist_item<F32, 1, ET, FUSED, SCH>(v, d, p, stripe, rb, sh);
+            else if (d.bits == 2) ok = persist_item<F32, 2, ET, FUSED, SCH>(v, d, p, stripe, rb, sh);
+            else ok = persist_item<F32, 4, ET, FUSED, SCH>(v, d, p, stripe, rb, sh);
         }
         if (!ok) return;                                            // uniform over the workgroup
     }
@@ -282,20 +286,25 @@ __global__ void k_reset_partials(u32x4 *words, uint64_t n_vec)
         *gmut<u32x4>(words + i) = fill;
 }
 
-template <int ET, bool FUSED> const void *persistent_fn() { return reinterpret_cast<const void *>(&k_single_pass<ET, FUSED>); }
+template <int ET, bool FUSED, int SCH> const void *persistent_fn() { return reinterpret_cast<const void *>(&k_single_pass<ET, FUSED, SCH>); }
 
-const void *pick(int err_dtype, bool fused)
+template <int SCH> const void *pick_width(int err_dtype, bool fused)
 {
-    if (err_dtype == BF16) return fused ? persistent_fn<BF16, true>() : persistent_fn<BF16, false>();
-    return fused ? persistent_fn<F32, true>() : persistent_fn<F32, false>();
+    if (err_dtype == BF16) return fused ? persistent_fn<BF16, true, SCH>() : persistent_fn<BF16, false, SCH>();
+    return fused ? persistent_fn<F32, true, SCH>() : persistent_fn<F32, false, SCH>();
+}
+
+const void *pick(int err_dtype, bool fused, bool wide)
+{
+    return wide ? pick_width<kStripeChannelsWide>(err_dtype, fused) : pick_width<kStripeChannels>(err_dtype, fused);
 }
 
 }  // namespace
 
-int persistent_max_blocks_per_cu(int err_dtype, bool fused)
+int persistent_max_blocks_per_cu(int err_dtype, bool fused, bool wide)
 {
     int n = 0;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, pick(err_dtype, fused), kPersistThreads, 0);
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, pick(err_dtype, fused, wide), kPersistThreads, 0);
     if (e != hipSuccess) { (void)hipGetLastError(); return 0; }
     return n;
 }
@@ -320,8 +329,8 @@ hipError_t launch_reset_partials(const BatchView &v, const LaunchRange &r, hipSt
 // items belongs to this group too, and as long as the XCD's share of `grid` (the co-resident capacity)
 // exceeds the group a slot is free and the item starts.  The caller passes one_shot only when an XCD's
 // share of `grid` holds a whole group.  Should the assumption ever fail, the bounded wait raises the error flag.
-hipError_t launch_single_pass(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, int grid, bool one_shot,
-                             hipStream_t s)
+hipError_t launch_single_pass(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, bool wide, int grid,
+                             bool one_shot, hipStream_t s)
 {
     if (r.item_hi == r.item_lo) return hipSuccess;
     uint32_t items = r.item_hi - r.item_lo;
@@ -329,8 +338,8 @@ hipError_t launch_single_pass(const BatchView &v, const LaunchRange &r, int err_
     BatchView vv = v;
     LaunchRange rr = r;
     void *args[] = {&vv, &rr};
-    if (one_shot) return hipLaunchKernel(pick(err_dtype, fused), dim3(items), dim3(kPersistThreads), args, 0, s);
-    return hipLaunchCooperativeKernel(pick(err_dtype, fused), dim3(grid), dim3(kPersistThreads), args, 0, s);
+    if (one_shot) return hipLaunchKernel(pick(err_dtype, fused, wide), dim3(items), dim3(kPersistThreads), args, 0, s);
+    return hipLaunchCooperativeKernel(pick(err_dtype, fused, wide), dim3(grid), dim3(kPersistThreads), args, 0, s);
 }
 
 }  // namespace cf
