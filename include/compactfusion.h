@@ -149,7 +149,7 @@ typedef struct {
  * again, writes the codes.  Results are bit-identical either way.  By default
  * a call takes the single pass where it applies, every channel-scale tensor
  * of the context has at least 256 tokens and the call covers at least 64 work
- * items of 256 rows x 128 channels (it is about 25 % faster on MI355X at the
+ * items of 256 rows x 128 channels (128 x 256 for contexts of short tensors; it is about 25 % faster on MI355X at the
  * sizes of the paper's models and slower on tiny batches);
  * CF_FLAG_SINGLE_PASS takes it whenever it applies, CF_FLAG_TWO_KERNEL never. */
 #define CF_FLAG_SINGLE_PASS 0x1u
