@@ -61,9 +61,9 @@ struct alignas(16) TensorDev {
     uint64_t partial_off;   // byte offset in the workspace of partial[n_rowblocks][C] (channel scales)
     // single-pass path (channel scales, CF_EF_RECON): items of p_rows x kStripeChannels
     uint64_t p_partial_off; // byte offset of partial[p_n_rb][C]
-    int32_t p_rows;         // rows per item (256 for bf16, 128 for fp32); 0 = tensor not on this path
+    int32_t p_rows;         // rows per item (256 for bf16, 128 for fp32; half of that with the wide stripe); 0 = tensor not on this path
     int32_t p_n_rb;         // ceil(N / p_rows): items per reduction group
-    int32_t p_n_stripes;    // ceil(C / kStripeChannels): reduction groups of this tensor
+    int32_t p_n_stripes;    // ceil(C / stripe width of the context): reduction groups of this tensor
     uint32_t p_item_begin;  // id of this tensor's first item
     uint32_t p_pad_;
     // element-wise kernels (warm-up, encode, decode): short tiles of ew_rows x 1024 channels
