@@ -123,8 +123,10 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     for (int32_t t = 0; t < n; ++t)
         if (descs[t].scale == CF_SCALE_RANK1) L.single_pass = false;   // the single-pass kernel knows channel scales only
     // Single-pass item shape: 256 lanes x 16 (bf16) or 8 (fp32) rows per lane cover kStripeChannels channels by
-    // default; when even the tallest channel-scale tensor would make at most 4 items per group that way, items half
-    // as tall and twice as wide measure faster (57 x [1024, 3072] bf16: 0.417 -> 0.389 ms).
+    // default; when even the tallest channel-scale tensor would make at most 12 items per group that way (bf16:
+    // N <= 3072), items half as tall and twice as wide measure faster (57 x [1024, 3072] bf16: 0.417 -> 0.382 ms;
+    // sweep over [N, 3072]: equal or up to 12 % faster through N = 3072, 2 % slower at N = 4096 with 1-bit codes,
+    // clearly slower from N = 8192 on, where groups get long).
     auto narrow_item_rows = [](int32_t dtype) { return (kPersistThreads / (kStripeChannels / kChunk)) * (dtype == CF_BF16 ? CF_SP_RPT : CF_SP_RPT / 2); };
     int64_t narrow_max_group = 0;
     for (int32_t t = 0; t < n; ++t)
@@ -133,7 +135,7 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
             const int64_t g = (descs[t].n_tokens + rows - 1) / rows;
             if (g > narrow_max_group) narrow_max_group = g;
         }
-    L.sp_wide = L.single_pass && narrow_max_group > 0 && narrow_max_group <= 4;
+    L.sp_wide = L.single_pass && narrow_max_group > 0 && narrow_max_group <= 12;
     const int stripe_channels = L.sp_wide ? kStripeChannelsWide : kStripeChannels;
     for (int32_t t = 0; t < n; ++t) {
         const cf_tensor_desc &d = descs[t];

@@ -34,9 +34,9 @@ constexpr int kMaxUploadTensors = 64;                       // pointer sets per 
 // [4096, 3072] bf16: 64- / 128- / 256-channel stripes (8 / 16 / 32 items per
 // reduction group) 2.94 / 2.86 / 2.92 ms; 32-channel ones (64-byte segments)
 // were 50 % slower.  Short tensors do better with the wide stripe (items half
-// as tall, twice as many per group): 57 x [1024, 3072] 0.417 -> 0.389 ms; a
-// context whose tallest channel-scale tensor makes at most 4 items per group
-// with the narrow stripe takes the wide one.
+// as tall, twice as many per group): 57 x [1024, 3072] 0.417 -> 0.382 ms; a
+// context whose tallest channel-scale tensor makes at most 12 items per group
+// with the narrow stripe (bf16: N <= 3072) takes the wide one.
 constexpr int kPersistThreads = 256;
 #ifndef CF_STRIPE_CHANNELS
 #define CF_STRIPE_CHANNELS 128
