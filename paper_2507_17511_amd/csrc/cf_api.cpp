@@ -128,14 +128,18 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     // sweep over [N, 3072]: equal or up to 12 % faster through N = 3072, 2 % slower at N = 4096 with 1-bit codes,
     // clearly slower from N = 8192 on, where groups get long).
     auto narrow_item_rows = [](int32_t dtype) { return (kPersistThreads / (kStripeChannels / kChunk)) * (dtype == CF_BF16 ? CF_SP_RPT : CF_SP_RPT / 2); };
+    // Up to 16 items per group (N = 4096) the wide stripe still pays for 2- and 4-bit codes, whose code rows
+    // then are whole 64- and 128-byte pieces (4-bit: 7 % faster), but not for 1-bit codes (2 % slower).
     int64_t narrow_max_group = 0;
+    bool one_bit = false;
     for (int32_t t = 0; t < n; ++t)
         if (descs[t].scale == CF_SCALE_CHANNEL) {
             const int64_t rows = narrow_item_rows(descs[t].dtype);
             const int64_t g = (descs[t].n_tokens + rows - 1) / rows;
             if (g > narrow_max_group) narrow_max_group = g;
+            if (descs[t].bits == 1) one_bit = true;
         }
-    L.sp_wide = L.single_pass && narrow_max_group > 0 && narrow_max_group <= 12;
+    L.sp_wide = L.single_pass && narrow_max_group > 0 && (narrow_max_group <= 12 || (narrow_max_group <= 16 && !one_bit));
     const int stripe_channels = L.sp_wide ? kStripeChannelsWide : kStripeChannels;
     for (int32_t t = 0; t < n; ++t) {
         const cf_tensor_desc &d = descs[t];
