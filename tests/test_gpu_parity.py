@@ -119,6 +119,23 @@ def test_single_pass_many_row_blocks_and_stripes():
     run_parity(descs, cf.options(), xs, mode="fused")
 
 
+def test_single_pass_stripe_width_rule_boundaries():
+    """The single-pass kernel takes 256-channel stripes for contexts of short tensors and for 4096-token contexts
+    without 1-bit tensors, 128-channel ones otherwise: contexts on both sides of each boundary (N = 3072 / 3328;
+    N = 4096 with and without a 1-bit tensor), ragged in both directions, against the oracle."""
+    cases = [[(3072, 264, 1), (1000, 1096, 2)],                 # wide, groups of 24 and 8 items
+             [(3328, 264, 1), (1000, 1096, 2)],                 # narrow, groups of 13 and 4
+             [(4096, 264, 4), (4000, 136, 2)],                  # wide (no 1-bit tensor), groups of 32
+             [(4096, 264, 4), (4000, 136, 1)]]                  # narrow, groups of 16
+    for k, shapes in enumerate(cases):
+        say(f"stripe width boundary case {k}: {shapes}")
+        descs = [cf.desc(n, c, cf.CF_BF16, bits, CH) for n, c, bits in shapes]
+        streams = [drift_stream((d.n_tokens, d.n_channels), d.dtype, steps=3, seed=270 + 10 * k + t, device=DEV) for t, d in enumerate(descs)]
+        xs = [[streams[t][s] for t in range(len(descs))] for s in range(3)]
+        for mode in ("fused", "split"):
+            run_parity(descs, cf.options(flags=cf.CF_FLAG_SINGLE_PASS), xs, mode=mode)
+
+
 def test_single_pass_looping_grid():
     """Groups of 157 items (N = 40000) are too large for one workgroup per item to be safe, so the
     single-pass kernel runs as a co-resident grid that loops over the items (cooperative launch)."""
