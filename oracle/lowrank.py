@@ -19,8 +19,10 @@ Readings (the paper is silent or garbled on these):
     travelled values, so that sender and receiver add the same D and the rounding loss stays in e.
   * INT4 factors (Sec. 3.4 and App. D name them, no format is given): factor_bits = 4 sends every factor row of
     r entries as one fp32 scale s = absmax / 7 and nibbles q = clamp(rint(f / s), -7, 7) (round half to even,
-    two's complement, entry k in byte k // 2, even k in the low nibble); D is formed from q * s.  The integer
-    decision is taken in fp32, the precision of the device path, on the fp64 factor rounded to fp32.
+    two's complement, entry k in byte k // 2, even k in the low nibble); D is formed from q * s.  Like everything
+    else here the decision is taken in fp64, on the fp64 factor and the scale as it travels (absmax / 7 rounded
+    once to fp32); an implementation that works in fp32 may decide a nibble the other way only where f / s lies
+    within its own factor error of a half-integer, which is what its parity test has to show.
 """
 from __future__ import annotations
 
@@ -68,23 +70,27 @@ def narrow(a: np.ndarray, dtype: int) -> np.ndarray:
 
 def quantise_rows(F: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     """INT4 factor rows: -> (nibble bytes uint8 [rows, r // 2], scales fp32 [rows])."""
-    f = np.asarray(F, dtype=np.float64).astype(np.float32)
-    s = (np.abs(f).max(axis=1) / np.float32(7.0)).astype(np.float32)
-    safe = np.where(s == 0, np.float32(1.0), s).astype(np.float32)
-    q = np.clip(np.rint((f / safe[:, None]).astype(np.float32)), -7, 7).astype(np.int32)
+    f = np.asarray(F, dtype=np.float64)
+    s = (np.abs(f).max(axis=1) / 7.0).astype(np.float32)            # the scale travels as fp32
+    safe = np.where(s == 0, 1.0, s.astype(np.float64))
+    q = np.clip(np.rint(f / safe[:, None]), -7, 7).astype(np.int32)
     q[s == 0] = 0
     u = (q & 0xF).astype(np.uint8)
     return (u[:, 0::2] | (u[:, 1::2] << 4)).astype(np.uint8), s
 
 
-def dequantise_rows(nibbles: np.ndarray, scales: np.ndarray) -> np.ndarray:
-    """-> fp64 [rows, r]: q * s, the product rounded to fp32 as the device forms it."""
+def unpack_nibbles(nibbles: np.ndarray) -> np.ndarray:
+    """-> int32 [rows, r]: the signed 4-bit integers."""
     b = np.asarray(nibbles, dtype=np.uint8)
     u = np.empty((b.shape[0], 2 * b.shape[1]), dtype=np.int32)
     u[:, 0::2] = b & 0xF
     u[:, 1::2] = b >> 4
-    q = np.where(u >= 8, u - 16, u).astype(np.float32)
-    return (q * np.asarray(scales, dtype=np.float32)[:, None]).astype(np.float32).astype(np.float64)
+    return np.where(u >= 8, u - 16, u)
+
+
+def dequantise_rows(nibbles: np.ndarray, scales: np.ndarray) -> np.ndarray:
+    """-> fp64 [rows, r]: q * s (exact in fp64: a 3-bit integer times an fp32 value)."""
+    return unpack_nibbles(nibbles).astype(np.float64) * np.asarray(scales, dtype=np.float32).astype(np.float64)[:, None]
 
 
 def factors_to_wire(cfg: LowRankConfig, F: np.ndarray):

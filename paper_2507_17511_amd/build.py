@@ -51,23 +51,5 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
-PROBE = os.path.join(HERE, "stream_ceiling")
-
-
-def build_probe(verbose: bool = False) -> str:
-    """The stand-alone copy-kernel program that measures what HBM rate the codec's byte mix can reach at all
-    (csrc/stream_ceiling.hip; a measurement aid, the library does not use it)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = PROBE + f".tmp{os.getpid()}"
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", os.path.join(CSRC, "stream_ceiling.hip"), "-o", tmp]
-    if verbose:
-        print(" ".join(cmd))
-    subprocess.check_call(cmd)
-    os.replace(tmp, PROBE)
-    return PROBE
-
-
 if __name__ == "__main__":
     print(build(force=True, verbose=True))
-    print(build_probe(verbose=True))

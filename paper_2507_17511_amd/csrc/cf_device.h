@@ -134,6 +134,47 @@ template <> struct Raw8<F32> {
     }
 };
 
+// ---------------------------------------------------------------- fp32 rows to memory as whole lines
+
+// A lane's 8 fp32 values are 32 bytes, so a plain pair of 128-bit stores half-fills every 64-byte
+// request, and a streaming store (which nothing merges on the way) would reach memory in pieces.
+// Instead the lanes of a wave pass their values through a wave-private LDS patch (2 KB: the image
+// of what the wave writes) and take them back so that store h of a run covers bytes
+// [h * 16 * RUN, (h + 1) * 16 * RUN) of it: whole 128-byte lines per instruction.  RUN = lanes
+// whose outputs are contiguous in memory (a divisor of 64).  Lane j of a run then holds pieces
+// j and RUN + j (16 bytes each) of the run's 2 * RUN pieces; piece q belongs to channel chunk q / 2.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int RUN>
+__device__ __forceinline__ void lines_exchange(float *patch, int lane, const F8 &v, f32x4 (&out)[2])
+{
+    f32x4 *img = reinterpret_cast<f32x4 *>(patch);
+    f32x4 lo, hi;
+    lo.x = v.v[0]; lo.y = v.v[1]; lo.z = v.v[2]; lo.w = v.v[3];
+    hi.x = v.v[4]; hi.y = v.v[5]; hi.z = v.v[6]; hi.w = v.v[7];
+    img[2 * lane] = lo;
+    img[2 * lane + 1] = hi;
+    wave_lds_fence();
+    const int first = (lane / RUN) * 2 * RUN, j = lane % RUN;
+    out[0] = img[first + j];
+    out[1] = img[first + RUN + j];
+    wave_lds_fence();                   // the next exchange overwrites the patch
+}
+
+// `run` points at the first byte of the run in memory; n_valid = channel chunks of the run that exist.
+template <int RUN>
+__device__ __forceinline__ void lines_store_stream(void *run, int j, int n_valid, const f32x4 (&pieces)[2])
+{
+    CF_GLOBAL f32x4 *dst = gmut<f32x4>(run);
+    if ((j >> 1) < n_valid) __builtin_nontemporal_store(pieces[0], dst + j);
+    if (((RUN + j) >> 1) < n_valid) __builtin_nontemporal_store(pieces[1], dst + RUN + j);
+}
+
 // ---------------------------------------------------------------- a1 + a2
 
 // z from the raw operands; the order of the two fp32 operations is fixed.

@@ -280,14 +280,18 @@ __global__ __launch_bounds__(kRank1Threads) void k_finalize_rank1(BatchView v, L
 
 // MODE: 0 = channel scales read from memory, 1 = group scales computed in the wave,
 // 2 = rank-1 scales u_i * v_j (v read once per lane, u once per row).
+// Every lane stays alive (lanes past the last chunk of the row are masked): the group maximum and the
+// whole-line store of an fp32 error row are wave-wide exchanges.  `patch`: the wave's 2 KB of LDS.
 template <int DT, int BITS, int MODE, int EF, int ET, bool FUSED>
-__device__ __forceinline__ void encode_tile(const TileCtx &c)
+__device__ __forceinline__ void encode_tile(const TileCtx &c, float *patch)
 {
     const TensorDev &d = c.d;
     const TensorPtrs &p = c.p;
     int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
     const bool cvalid = chunk < d.n_chunks;
-    if (MODE != 1 && !cvalid) return;           // group mode keeps every lane alive for the DPP reduction
+    const int lane = (int)threadIdx.x & 63;
+    const int run_chunk0 = chunk - lane;                                // first chunk of the wave's 64
+    const int run_valid = d.n_chunks - run_chunk0;                      // chunks of the wave that exist (may exceed 64 or be <= 0)
     int64_t row0 = (int64_t)c.rowblock * c.rows;
     int64_t row1 = row0 + c.rows < d.n_tokens ? row0 + c.rows : d.n_tokens;
     const int64_t C = d.n_channels;
@@ -295,9 +299,9 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
     const int n_groups = d.n_channels >> 7;
     const bool wide = (d.n_channels & 31) == 0;
 
-    F8 s, vj;
-    if (MODE == 0) s = load_scales8(p.scales, (int64_t)chunk * kChunk);
-    if (MODE == 2) vj = load_scales8(p.scales, (int64_t)chunk * kChunk);
+    F8 s = {}, vj = {};
+    if (MODE == 0 && cvalid) s = load_scales8(p.scales, (int64_t)chunk * kChunk);
+    if (MODE == 2 && cvalid) vj = load_scales8(p.scales, (int64_t)chunk * kChunk);
 
     constexpr int U = 4;
     for (int64_t i0 = row0; i0 < row1; i0 += U) {
@@ -342,10 +346,9 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
 #pragma unroll
                 for (int k = 0; k < 8; ++k) s.v[k] = ui * vj.v[k];
             }
-            if (!cvalid) continue;
             F8 dq;
             uint32_t packed = quant8<BITS>(z, s, dq);
-            store_codes_wide<BITS>(p.codes + i * row_bytes, chunk, packed, wide);
+            if (cvalid) store_codes_wide<BITS>(p.codes + i * row_bytes, chunk, packed, wide);
             int64_t e = i * C + (int64_t)chunk * kChunk;
             F8 enew;
 #pragma unroll
@@ -354,16 +357,22 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c)
                 if (EF == EF_OFF) lost = eold.v[k] + lost;
                 enew.v[k] = lost;
             }
-            Raw8<ET> eo;
-            eo.narrow(enew);
-            eo.store(p.err, e);
-            if (FUSED) {
+            if (ET == F32) {                    // whole 128-byte lines per store, streaming
+                f32x4 pieces[2];
+                lines_exchange<64>(patch, lane, enew, pieces);
+                lines_store_stream<64>(static_cast<float *>(p.err) + i * C + (int64_t)run_chunk0 * kChunk, lane, run_valid, pieces);
+            } else if (cvalid) {
+                Raw8<ET> eo;
+                eo.narrow(enew);
+                eo.store_stream(p.err, e);
+            }
+            if (FUSED && cvalid) {
                 F8 nb;
 #pragma unroll
                 for (int k = 0; k < 8; ++k) nb.v[k] = (EF == EF_NAIVE) ? dq.v[k] : b.v[k] + dq.v[k];
                 Raw8<DT> out;
                 out.narrow(nb);
-                out.store(p.recon, e);
+                if (DT == BF16) out.store_stream(p.recon, e); else out.store(p.recon, e);
             }
         }
     }
@@ -474,28 +483,30 @@ __device__ __forceinline__ void nm_encode_dispatch(const TileCtx &c)
 }
 
 template <int DT, int EF, int ET, bool FUSED>
-__device__ __forceinline__ void encode_dispatch(const TileCtx &c)
+__device__ __forceinline__ void encode_dispatch(const TileCtx &c, float *patch)
 {
     const TensorDev &d = c.d;
-    if (d.scale == SCALE_GROUP) { encode_tile<DT, 4, 1, EF, ET, FUSED>(c); return; }
+    if (d.scale == SCALE_GROUP) { encode_tile<DT, 4, 1, EF, ET, FUSED>(c, patch); return; }
     if (d.scale == SCALE_RANK1) {
-        if (d.bits == 1) encode_tile<DT, 1, 2, EF, ET, FUSED>(c);
-        else encode_tile<DT, 2, 2, EF, ET, FUSED>(c);
+        if (d.bits == 1) encode_tile<DT, 1, 2, EF, ET, FUSED>(c, patch);
+        else encode_tile<DT, 2, 2, EF, ET, FUSED>(c, patch);
         return;
     }
-    if (d.bits == 1) encode_tile<DT, 1, 0, EF, ET, FUSED>(c);
-    else if (d.bits == 2) encode_tile<DT, 2, 0, EF, ET, FUSED>(c);
-    else encode_tile<DT, 4, 0, EF, ET, FUSED>(c);
+    if (d.bits == 1) encode_tile<DT, 1, 0, EF, ET, FUSED>(c, patch);
+    else if (d.bits == 2) encode_tile<DT, 2, 0, EF, ET, FUSED>(c, patch);
+    else encode_tile<DT, 4, 0, EF, ET, FUSED>(c, patch);
 }
 
 template <int EF, int ET, bool FUSED, int DTS>
 __global__ __launch_bounds__(kTileThreads) void k_encode(BatchView v, LaunchRange r)
 {
+    __shared__ __attribute__((aligned(16))) float patches[kTileThreads / 64][512];      // 2 KB per wave: an fp32 error row's way to whole lines
     TileCtx c = locate_tile<true>(v, r);
     if (r.only_group_scale && c.d.scale == SCALE_CHANNEL) return;   // covered by the single-pass kernel
     if (c.d.scale == LOWRANK || c.d.scale == SPARSE_NM) return;     // have kernels of their own
-    if (is_bf16<DTS>(c.d)) encode_dispatch<BF16, EF, ET, FUSED>(c);
-    else encode_dispatch<F32, EF, ET, FUSED>(c);
+    float *patch = patches[(int)threadIdx.x >> 6];
+    if (is_bf16<DTS>(c.d)) encode_dispatch<BF16, EF, ET, FUSED>(c, patch);
+    else encode_dispatch<F32, EF, ET, FUSED>(c, patch);
 }
 
 // The sparsifier's tensors, over the same tiles; PAIR: those with 16-channel blocks, else those with 8-channel

@@ -203,7 +203,7 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
         xr[k].opaque();
         br[k].opaque();
     }
-    if (cvalid) {
+    {
         F8 s;
         {
             const f32x4 *src = reinterpret_cast<const f32x4 *>(&sh.scale[cl * kChunk]);
@@ -213,31 +213,42 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
         }
         const int64_t row_bytes = C * BITS / 8;
         const bool wide = (d.n_channels & 31) == 0;
+        // fp32 error rows go out as whole lines (see lines_exchange): a run is the kStripeChunks lanes of one row
+        // segment; the wave's patch is its 2 KB of `red`, which nobody reads any more
+        float *patch = &sh.red[0][0] + (tid >> 6) * 512;
+        const int run_valid = d.n_chunks - stripe * kStripeChunks;
 #pragma unroll
         for (int k = 0; k < RPT; ++k) {
             const int64_t row = row0 + k;
+            const bool rvalid = row < d.n_tokens;
             __builtin_amdgcn_sched_barrier(0);      // one row at a time: keeps the live set inside the register budget
-            if (row < d.n_tokens) {
-                const int64_t e = row * C + (int64_t)chunk * kChunk;
-                F8 b = br[k].widen();
-                F8 z = residual8<EF_RECON>(xr[k].widen(), b, none);
-                F8 dq;
-                uint32_t packed = quant8<BITS>(z, s, dq);
-                store_codes_wide<BITS>(p.codes + row * row_bytes, chunk, packed, wide);
-                F8 enew;
+            const int64_t e = row * C + (int64_t)chunk * kChunk;
+            F8 b = br[k].widen();
+            F8 z = residual8<EF_RECON>(xr[k].widen(), b, none);     // masked lanes and rows hold zeros
+            F8 dq;
+            uint32_t packed = quant8<BITS>(z, s, dq);
+            if (rvalid && cvalid) store_codes_wide<BITS>(p.codes + row * row_bytes, chunk, packed, wide);
+            F8 enew;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) enew.v[j] = z.v[j] - dq.v[j];
+            for (int j = 0; j < 8; ++j) enew.v[j] = z.v[j] - dq.v[j];
+            if (ET == F32) {
+                f32x4 pieces[2];
+                lines_exchange<kStripeChunks>(patch, tid & 63, enew, pieces);
+                if (rvalid)
+                    lines_store_stream<kStripeChunks>(static_cast<float *>(p.err) + row * C + (int64_t)stripe * kStripeChannels, cl,
+                                                      run_valid, pieces);
+            } else if (rvalid && cvalid) {
                 Raw8<ET> eo;
                 eo.narrow(enew);
-                eo.store(p.err, e);
-                if (FUSED) {
-                    F8 nb;
+                eo.store_stream(p.err, e);
+            }
+            if (FUSED && rvalid && cvalid) {
+                F8 nb;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) nb.v[j] = b.v[j] + dq.v[j];
-                    Raw8<DT> out;
-                    out.narrow(nb);
-                    out.store(p.recon, e);
-                }
+                for (int j = 0; j < 8; ++j) nb.v[j] = b.v[j] + dq.v[j];
+                Raw8<DT> out;
+                out.narrow(nb);
+                if (DT == BF16) out.store_stream(p.recon, e); else out.store(p.recon, e);
             }
         }
     }

@@ -154,13 +154,13 @@ def test_int4_zero_row_and_error_bound_and_textbook_expression():
     nib, s = lr.quantise_rows(f)
     assert s[7] == 0 and not nib[7].any()
     back = lr.dequantise_rows(nib, s)
-    f32 = f.astype(np.float32).astype(np.float64)
-    assert np.all(np.abs(back - f32) <= 0.5 * s[:, None].astype(np.float64) * (1 + 1e-6))
-    # the symmetric absmax quantiser as a library expression (torch.round rounds half to even)
-    t = torch.from_numpy(f.astype(np.float32))
-    st = t.abs().amax(dim=1, keepdim=True) / 7
+    assert np.all(np.abs(back - f) <= 0.5 * s[:, None].astype(np.float64) * (1 + 1e-6))
+    # the symmetric absmax quantiser as a library expression (torch.round rounds half to even), in fp64 on the
+    # scale as it travels (absmax / 7 rounded once to fp32)
+    t = torch.from_numpy(f)
+    st = (t.abs().amax(dim=1, keepdim=True) / 7).float().double()
     want = torch.where(st > 0, torch.clamp(torch.round(t / torch.where(st > 0, st, torch.ones_like(st))), -7, 7) * st, torch.zeros_like(t))
-    assert np.array_equal(back.astype(np.float32), want.numpy())
+    assert np.array_equal(back, want.numpy())
 
 
 def test_int4_factors_keep_the_recursion_invariant_and_cost_accuracy_gracefully():
