@@ -50,8 +50,23 @@
  * do not depend on the launch shape.  NaN or Inf inputs give undefined values
  * (never a fault).
  *
- * Errors.  Every entry point returns a cf_status; nothing is thrown.  On any
- * error no work is enqueued and no state changes.
+ * x, recon, err, codes and scales of one tensor must not overlap one another
+ * (checked on byte ranges; buffers of different tensors are the caller's business).
+ *
+ * Errors.  Every entry point returns a cf_status; nothing is thrown.  Arguments,
+ * shapes, state and workspace are validated before anything is enqueued: on
+ * every status but CF_ERR_DEVICE no work was enqueued and no state changed.
+ * CF_ERR_DEVICE means a HIP call failed part of the way through a call's launch
+ * sequence: kernels enqueued before it still run, so the tensors of that call
+ * hold undefined values and must be warmed up again.
+ *
+ * Streams and graphs.  The device pointers of a call reach the kernels through a
+ * table in the workspace that a small kernel of the same call fills; the library
+ * skips that upload when the pointers are the ones it uploaded last on the same
+ * stream.  A call on another stream than the last one, or on a stream that is
+ * being captured into a HIP graph, uploads the whole table again, and after a
+ * captured call the next call does too: a captured call is self-contained and may
+ * be replayed at any time, as long as no other use of the context is in flight.
  */
 #ifndef COMPACTFUSION_H
 #define COMPACTFUSION_H

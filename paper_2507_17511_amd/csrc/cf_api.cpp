@@ -21,7 +21,8 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Layout {
     size_t off_descs = 0, off_ptrs = 0, off_tile_prefix = 0, off_fin_prefix = 0, off_partials = 0;
     size_t off_item_prefix = 0, off_item_tensor = 0, off_error = 0, off_p_partials = 0;
-    std::vector<uint32_t> item_prefix, item_tensor;
+    std::vector<uint32_t> item_prefix;
+    size_t n_items = 0;
     int32_t max_group_items = 0;   // largest reduction group of the single-pass path
     bool sp_wide = false;          // single-pass items are kStripeChannelsWide channels wide (short tensors)
     bool single_pass = false;      // every channel-scale tensor has single-pass geometry
@@ -83,6 +84,38 @@ cf_status check_desc(const cf_tensor_desc &d)
 }
 
 size_t dtype_size(int32_t dt) { return dt == CF_BF16 ? 2 : 4; }
+
+struct BufferBytes {
+    size_t codes, scales, recon, err;      // recon is also the size of x
+};
+
+// Byte sizes of one (valid) tensor's buffers.
+BufferBytes buffer_bytes(const cf_tensor_desc &d, const cf_options &o)
+{
+    BufferBytes b;
+    const size_t n = (size_t)d.n_tokens, c = (size_t)d.n_channels;
+    if (d.scale == CF_LOWRANK) {        // U [N, 32] then V [C, 32] in the storage dtype; the scales entry is the input Q0 [C, 32] fp32
+        // 4-bit factors: 16 nibble bytes and one fp32 scale per factor row
+        b.codes = (o.flags & CF_FLAG_LOWRANK_INT4) ? (n + c) * 20 : (n + c) * kLowRankRank * dtype_size(d.dtype);
+        b.scales = c * kLowRankRank * sizeof(float);
+    } else if (d.scale == CF_SPARSE_NM) {      // one mask byte per block of 8, then (16-byte aligned) bits values per block
+        b.codes = (n * (c / 8) + 15) / 16 * 16 + n * (c / (size_t)d.group) * (size_t)d.bits * dtype_size(d.dtype);
+        b.scales = 0;
+    } else {
+        b.codes = n * (c * (size_t)d.bits / 8);
+        b.scales = sizeof(float) * (d.scale == CF_SCALE_GROUP ? n * (c / 128) : d.scale == CF_SCALE_RANK1 ? c + n : c);
+    }
+    b.recon = n * c * dtype_size(d.dtype);
+    b.err = n * c * dtype_size(o.err_dtype);
+    return b;
+}
+
+inline bool overlap(const void *a, size_t na, const void *b, size_t nb)
+{
+    if (!a || !b || na == 0 || nb == 0) return false;
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+    return pa < pb + nb && pb < pa + na;
+}
 
 // Rows per tile: as large as still leaves the batched grid a few thousand
 // workgroups (256 CUs, several resident workgroups each).
@@ -227,9 +260,7 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     L.off_partials = off;     off = align_up(off + partial_bytes);
     L.off_item_prefix = off;  off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
     L.off_item_tensor = off;  off = align_up(off + sizeof(uint32_t) * (size_t)items);
-    L.item_tensor.resize((size_t)items);
-    for (int32_t t = 0; t < n; ++t)
-        for (uint32_t i = L.item_prefix[t]; i < L.item_prefix[t + 1]; ++i) L.item_tensor[i] = (uint32_t)t;
+    L.n_items = (size_t)items;
     L.off_error = off;        off = align_up(off + sizeof(uint32_t));
     L.off_p_partials = off;   off = align_up(off + p_partial_bytes);
     L.total = off;
@@ -258,7 +289,9 @@ struct cf_ctx {
     cf_options opts;
     uint8_t *ws = nullptr;
     size_t ws_bytes = 0;
-    std::vector<TensorPtrs> ptrs;      // what the workspace table currently holds
+    std::vector<TensorPtrs> ptrs;      // what the workspace table currently holds (once the uploads on ptrs_stream have run)
+    hipStream_t ptrs_stream = nullptr; // stream the pointer uploads were enqueued on
+    bool ptrs_synced = false;          // the table matches `ptrs` for work enqueued on ptrs_stream from now on
     std::vector<uint8_t> warm;
     int32_t last_hip = 0;
     int device = 0;
@@ -420,6 +453,58 @@ cf_status device_fail(cf_ctx *ctx, hipError_t e)
     return CF_ERR_DEVICE;
 }
 
+// Builds a context over `workspace` and brings its tables there.  Everything travels inside kernel arguments
+// (no host-to-device copy, no memset), so this works wherever a kernel launch does.
+cf_status make_ctx(cf_ctx **out, const cf_tensor_desc *descs, int32_t n_tensors, const cf_options &o, void *workspace,
+                   size_t workspace_bytes, hipStream_t s)
+{
+    cf_ctx *ctx = new (std::nothrow) cf_ctx;
+    if (!ctx) return CF_ERR_INVALID_ARG;
+    cf_status st = make_layout(descs, n_tensors, o, ctx->L);
+    if (st != CF_OK) { delete ctx; return st; }
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < ctx->L.total) {
+        delete ctx;
+        return CF_ERR_WORKSPACE;
+    }
+    ctx->descs.assign(descs, descs + n_tensors);
+    ctx->opts = o;
+    ctx->ws = static_cast<uint8_t *>(workspace);
+    ctx->ws_bytes = workspace_bytes;
+    ctx->ptrs.resize(n_tensors);
+    std::memset(ctx->ptrs.data(), 0, sizeof(TensorPtrs) * (size_t)n_tensors);
+    ctx->warm.assign(n_tensors, 0);
+
+    const Layout &L = ctx->L;
+    const size_t prefix_bytes = sizeof(uint32_t) * (size_t)(n_tensors + 1);
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e == hipSuccess) e = launch_upload_bytes(L.dev.data(), ctx->ws + L.off_descs, sizeof(TensorDev) * (size_t)n_tensors, s);
+    if (e == hipSuccess) e = launch_upload_bytes(L.tile_prefix.data(), ctx->ws + L.off_tile_prefix, prefix_bytes, s);
+    if (e == hipSuccess) e = launch_upload_bytes(L.fin_prefix.data(), ctx->ws + L.off_fin_prefix, prefix_bytes, s);
+    if (e == hipSuccess) e = launch_upload_bytes(L.ew_prefix.data(), ctx->ws + L.off_ew_prefix, prefix_bytes, s);
+    if (e == hipSuccess) e = launch_upload_bytes(L.dec_prefix.data(), ctx->ws + L.off_dec_prefix, prefix_bytes, s);
+    if (e == hipSuccess) e = launch_upload_bytes(L.item_prefix.data(), ctx->ws + L.off_item_prefix, prefix_bytes, s);
+    if (e == hipSuccess && L.n_items > 0)
+        e = launch_fill_item_tensor(reinterpret_cast<const uint32_t *>(ctx->ws + L.off_item_prefix),
+                                    reinterpret_cast<uint32_t *>(ctx->ws + L.off_item_tensor), n_tensors, s);
+    if (e == hipSuccess) e = launch_fill_words(ctx->ws + L.off_ptrs, 0u, sizeof(TensorPtrs) * (size_t)n_tensors / 4, s);
+    if (e == hipSuccess) e = launch_fill_words(ctx->ws + L.off_error, 0u, 1, s);
+    if (e == hipSuccess && L.single_pass && L.max_group_items > 0) {
+        int n_cu = 0;
+        e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, ctx->device);
+        if (e == hipSuccess)
+            for (int et = 0; et < 2; ++et)
+                for (int fu = 0; fu < 2; ++fu)
+                    ctx->persist_grid[et][fu] = persistent_max_blocks_per_cu(et, fu != 0, L.sp_wide) * n_cu;
+    }
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        delete ctx;
+        return CF_ERR_DEVICE;
+    }
+    *out = ctx;
+    return CF_OK;
+}
+
 // Runs one launch; when the call is being profiled, brackets it with the caller's events.
 template <class F>
 hipError_t launch(cf_ctx *ctx, hipStream_t s, const char *name, F &&f)
@@ -461,20 +546,31 @@ cf_status sync_ptrs(cf_ctx *ctx, int32_t first, int32_t count, const void *const
             changed = true;
         }
     }
-    if (!changed) return CF_OK;
+    // The mirror describes the table as work enqueued on ptrs_stream after the last upload sees it.  On another
+    // stream nothing orders that upload before this call, and while a stream is being captured into a graph the
+    // upload is recorded, not run (nobody knows whether or when the graph will): in both cases the whole table
+    // is uploaded, and after a captured call it counts as unknown again.
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cap) != hipSuccess) {
+        (void)hipGetLastError();
+        cap = hipStreamCaptureStatusNone;
+    }
+    const bool capturing = cap != hipStreamCaptureStatusNone;
+    const bool whole = capturing || !ctx->ptrs_synced || ctx->ptrs_stream != s;
+    if (!changed && !whole) return CF_OK;
+    const int32_t lo = whole ? 0 : first, n = whole ? (int32_t)ctx->ptrs.size() : count;
     TensorPtrs *table = reinterpret_cast<TensorPtrs *>(ctx->ws + ctx->L.off_ptrs);
-    for (int32_t k0 = 0; k0 < count; k0 += kMaxUploadTensors) {
-        int n = count - k0 < kMaxUploadTensors ? count - k0 : kMaxUploadTensors;
+    ctx->ptrs_synced = false;
+    for (int32_t k0 = 0; k0 < n; k0 += kMaxUploadTensors) {
+        int m = n - k0 < kMaxUploadTensors ? n - k0 : kMaxUploadTensors;
         PtrChunk chunk;
         std::memset(&chunk, 0, sizeof chunk);
-        for (int k = 0; k < n; ++k) chunk.p[k] = ctx->ptrs[first + k0 + k];
-        hipError_t e = launch(ctx, s, "k_upload_ptrs", [&] { return launch_upload_ptrs(chunk, table + first + k0, n, s); });
-        if (e != hipSuccess) {
-            // the mirror no longer matches the device table: force a re-upload next time
-            for (int32_t k = 0; k < count; ++k) std::memset(&ctx->ptrs[first + k], 0xff, sizeof(TensorPtrs));
-            return device_fail(ctx, e);
-        }
+        for (int k = 0; k < m; ++k) chunk.p[k] = ctx->ptrs[lo + k0 + k];
+        hipError_t e = launch(ctx, s, "k_upload_ptrs", [&] { return launch_upload_ptrs(chunk, table + lo + k0, m, s); });
+        if (e != hipSuccess) return device_fail(ctx, e);       // the table counts as unknown: the next call uploads all of it
     }
+    ctx->ptrs_synced = !capturing;
+    ctx->ptrs_stream = s;
     return CF_OK;
 }
 
@@ -536,11 +632,14 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
     if ((st = check_ptrs(err, count)) != CF_OK) return st;
     if ((st = check_ptrs(codes, count)) != CF_OK) return st;
     if ((st = check_scale_ptrs(ctx, first, count, reinterpret_cast<const void *const *>(scales))) != CF_OK) return st;
-    for (int32_t k = 0; k < count; ++k) {
+    for (int32_t k = 0; k < count; ++k) {       // the buffers of one tensor must not overlap one another
+        const BufferBytes b = buffer_bytes(ctx->descs[first + k], ctx->opts);
         const void *px = x[k], *pr = recon[k], *pe = err[k], *pc = codes[k], *ps = scales[k];
-        if (px == pr || px == pe || pr == pe) return CF_ERR_INVALID_ARG;
-        if (pc == px || pc == pr || pc == pe) return CF_ERR_INVALID_ARG;
-        if (ps && (ps == px || ps == pr || ps == pe || ps == pc)) return CF_ERR_INVALID_ARG;
+        if (overlap(px, b.recon, pr, b.recon) || overlap(px, b.recon, pe, b.err) || overlap(pr, b.recon, pe, b.err)) return CF_ERR_INVALID_ARG;
+        if (overlap(pc, b.codes, px, b.recon) || overlap(pc, b.codes, pr, b.recon) || overlap(pc, b.codes, pe, b.err)) return CF_ERR_INVALID_ARG;
+        if (overlap(ps, b.scales, px, b.recon) || overlap(ps, b.scales, pr, b.recon) || overlap(ps, b.scales, pe, b.err) ||
+            overlap(ps, b.scales, pc, b.codes))
+            return CF_ERR_INVALID_ARG;
     }
     if ((st = check_warm(ctx, first, count)) != CF_OK) return st;
 
@@ -610,22 +709,11 @@ cf_status cf_sizes(const cf_tensor_desc *desc, const cf_options *opts, size_t *c
     cf_status st = check_opts(opts, o);
     if (st != CF_OK) return st;
     if ((st = check_desc(*desc)) != CF_OK) return st;
-    const size_t n = (size_t)desc->n_tokens, c = (size_t)desc->n_channels;
-    if (desc->scale == CF_LOWRANK) {        // U [N, 32] then V [C, 32] in the storage dtype; the scales entry is the input Q0 [C, 32] fp32
-        if (codes_bytes)                    // 4-bit factors: 16 nibble bytes and one fp32 scale per factor row
-            *codes_bytes = (o.flags & CF_FLAG_LOWRANK_INT4) ? (n + c) * 20 : (n + c) * kLowRankRank * dtype_size(desc->dtype);
-        if (scales_bytes) *scales_bytes = c * kLowRankRank * sizeof(float);
-    } else if (desc->scale == CF_SPARSE_NM) {      // one mask byte per block of 8, then (16-byte aligned) bits values per block
-        if (codes_bytes)
-            *codes_bytes = (n * (c / 8) + 15) / 16 * 16 + n * (c / (size_t)desc->group) * (size_t)desc->bits * dtype_size(desc->dtype);
-        if (scales_bytes) *scales_bytes = 0;
-    } else {
-        if (codes_bytes) *codes_bytes = n * (c * (size_t)desc->bits / 8);
-        if (scales_bytes)
-            *scales_bytes = sizeof(float) * (desc->scale == CF_SCALE_GROUP ? n * (c / 128) : desc->scale == CF_SCALE_RANK1 ? c + n : c);
-    }
-    if (recon_bytes) *recon_bytes = n * c * dtype_size(desc->dtype);
-    if (err_bytes) *err_bytes = n * c * dtype_size(o.err_dtype);
+    BufferBytes b = buffer_bytes(*desc, o);
+    if (codes_bytes) *codes_bytes = b.codes;
+    if (scales_bytes) *scales_bytes = b.scales;
+    if (recon_bytes) *recon_bytes = b.recon;
+    if (err_bytes) *err_bytes = b.err;
     return CF_OK;
 }
 
@@ -646,65 +734,7 @@ cf_status cf_init(cf_ctx **out, const cf_tensor_desc *descs, int32_t n_tensors, 
     cf_options o;
     cf_status st = check_opts(opts, o);
     if (st != CF_OK) return st;
-    cf_ctx *ctx = new (std::nothrow) cf_ctx;
-    if (!ctx) return CF_ERR_INVALID_ARG;
-    st = make_layout(descs, n_tensors, o, ctx->L);
-    if (st != CF_OK) { delete ctx; return st; }
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < ctx->L.total) {
-        delete ctx;
-        return CF_ERR_WORKSPACE;
-    }
-    ctx->descs.assign(descs, descs + n_tensors);
-    ctx->opts = o;
-    ctx->ws = static_cast<uint8_t *>(workspace);
-    ctx->ws_bytes = workspace_bytes;
-    ctx->ptrs.resize(n_tensors);
-    std::memset(ctx->ptrs.data(), 0, sizeof(TensorPtrs) * (size_t)n_tensors);
-    ctx->warm.assign(n_tensors, 0);
-
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = hipGetDevice(&ctx->device);
-    // The tables stay alive in the context (never modified), so the copies may complete late.
-    if (e == hipSuccess)
-        e = hipMemcpyAsync(ctx->ws + ctx->L.off_descs, ctx->L.dev.data(), sizeof(TensorDev) * (size_t)n_tensors,
-                           hipMemcpyHostToDevice, s);
-    if (e == hipSuccess)
-        e = hipMemcpyAsync(ctx->ws + ctx->L.off_tile_prefix, ctx->L.tile_prefix.data(),
-                           sizeof(uint32_t) * (size_t)(n_tensors + 1), hipMemcpyHostToDevice, s);
-    if (e == hipSuccess)
-        e = hipMemcpyAsync(ctx->ws + ctx->L.off_fin_prefix, ctx->L.fin_prefix.data(),
-                           sizeof(uint32_t) * (size_t)(n_tensors + 1), hipMemcpyHostToDevice, s);
-    if (e == hipSuccess)
-        e = hipMemcpyAsync(ctx->ws + ctx->L.off_ew_prefix, ctx->L.ew_prefix.data(),
-                           sizeof(uint32_t) * (size_t)(n_tensors + 1), hipMemcpyHostToDevice, s);
-    if (e == hipSuccess)
-        e = hipMemcpyAsync(ctx->ws + ctx->L.off_dec_prefix, ctx->L.dec_prefix.data(),
-                           sizeof(uint32_t) * (size_t)(n_tensors + 1), hipMemcpyHostToDevice, s);
-    if (e == hipSuccess)
-        e = hipMemcpyAsync(ctx->ws + ctx->L.off_item_prefix, ctx->L.item_prefix.data(),
-                           sizeof(uint32_t) * (size_t)(n_tensors + 1), hipMemcpyHostToDevice, s);
-    if (e == hipSuccess && !ctx->L.item_tensor.empty())
-        e = hipMemcpyAsync(ctx->ws + ctx->L.off_item_tensor, ctx->L.item_tensor.data(),
-                           sizeof(uint32_t) * ctx->L.item_tensor.size(), hipMemcpyHostToDevice, s);
-    if (e == hipSuccess)
-        e = hipMemsetAsync(ctx->ws + ctx->L.off_ptrs, 0, sizeof(TensorPtrs) * (size_t)n_tensors, s);
-    if (e == hipSuccess)
-        e = hipMemsetAsync(ctx->ws + ctx->L.off_error, 0, sizeof(uint32_t), s);
-    if (e == hipSuccess && ctx->L.single_pass && ctx->L.max_group_items > 0) {
-        hipDeviceProp_t prop;
-        e = hipGetDeviceProperties(&prop, ctx->device);
-        if (e == hipSuccess)
-            for (int et = 0; et < 2; ++et)
-                for (int fu = 0; fu < 2; ++fu)
-                    ctx->persist_grid[et][fu] = persistent_max_blocks_per_cu(et, fu != 0, ctx->L.sp_wide) * prop.multiProcessorCount;
-    }
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        delete ctx;
-        return CF_ERR_DEVICE;
-    }
-    *out = ctx;
-    return CF_OK;
+    return make_ctx(out, descs, n_tensors, o, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 void cf_destroy(cf_ctx *ctx) { delete ctx; }
@@ -764,8 +794,11 @@ cf_status cf_warmup(cf_ctx *ctx, int32_t first, int32_t count, const void *const
     if ((st = check_ptrs(x0, count)) != CF_OK) return st;
     if ((st = check_ptrs(recon, count)) != CF_OK) return st;
     if ((st = check_ptrs(err, count)) != CF_OK) return st;
-    for (int32_t k = 0; k < count; ++k)
-        if (x0[k] == recon[k] || x0[k] == err[k] || recon[k] == err[k]) return CF_ERR_INVALID_ARG;
+    for (int32_t k = 0; k < count; ++k) {
+        const BufferBytes b = buffer_bytes(ctx->descs[first + k], ctx->opts);
+        if (overlap(x0[k], b.recon, recon[k], b.recon) || overlap(x0[k], b.recon, err[k], b.err) || overlap(recon[k], b.recon, err[k], b.err))
+            return CF_ERR_INVALID_ARG;
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     if ((st = sync_ptrs(ctx, first, count, x0, recon, err, nullptr, nullptr, s)) != CF_OK) return st;
     hipError_t e = launch_warmup(ctx->view(), ctx->range(first, count), ctx->opts.err_dtype, s);
@@ -797,8 +830,9 @@ cf_status cf_decompress(cf_ctx *ctx, int32_t first, int32_t count, const void *c
     if ((st = check_scale_ptrs(ctx, first, count, scales)) != CF_OK) return st;
     if ((st = check_ptrs(recon, count)) != CF_OK) return st;
     for (int32_t k = 0; k < count; ++k) {
-        if (codes[k] == recon[k]) return CF_ERR_INVALID_ARG;
-        if (scales[k] && (codes[k] == scales[k] || scales[k] == recon[k])) return CF_ERR_INVALID_ARG;
+        const BufferBytes b = buffer_bytes(ctx->descs[first + k], ctx->opts);
+        if (overlap(codes[k], b.codes, recon[k], b.recon)) return CF_ERR_INVALID_ARG;
+        if (overlap(scales[k], b.scales, codes[k], b.codes) || overlap(scales[k], b.scales, recon[k], b.recon)) return CF_ERR_INVALID_ARG;
     }
     if ((st = check_warm(ctx, first, count)) != CF_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);

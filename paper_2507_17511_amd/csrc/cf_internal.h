@@ -83,6 +83,8 @@ struct alignas(16) TensorDev {
     uint64_t lr_p_off, lr_z_off, lr_q_off;
 };
 
+static_assert(sizeof(TensorDev) % 4 == 0, "tables travel as 4-byte words");
+
 // Per-call device pointers of one tensor; uploaded into the workspace.
 struct TensorPtrs {
     const void *x;
@@ -94,6 +96,12 @@ struct TensorPtrs {
 
 struct PtrChunk {
     TensorPtrs p[kMaxUploadTensors];
+};
+
+// A piece of one of the context's tables on its way to the workspace inside a kernel's arguments.
+constexpr int kUploadWords = 896;
+struct WordChunk {
+    uint32_t w[kUploadWords];
 };
 
 // Device view of a context's workspace.
@@ -130,6 +138,11 @@ struct LaunchRange {
 enum class Op { Compress, StepFused };
 
 hipError_t launch_upload_ptrs(const PtrChunk &chunk, TensorPtrs *dst, int n, hipStream_t s);
+// Host tables (multiples of 4 bytes) to the workspace through kernel arguments; fills; the item -> tensor table
+hipError_t launch_upload_bytes(const void *src, void *dst, size_t bytes, hipStream_t s);
+hipError_t launch_fill_words(void *dst, uint32_t value, size_t n_words, hipStream_t s);
+hipError_t launch_fill_item_tensor(const uint32_t *item_prefix, uint32_t *item_tensor, int n_tensors, hipStream_t s);
+
 hipError_t launch_warmup(const BatchView &v, const LaunchRange &r, int err_dtype, hipStream_t s);
 hipError_t launch_colreduce(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, hipStream_t s);
 hipError_t launch_finalize(const BatchView &v, const LaunchRange &r, hipStream_t s);

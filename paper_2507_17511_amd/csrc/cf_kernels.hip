@@ -66,7 +66,9 @@ __device__ __forceinline__ void warmup_tile(const TileCtx &c)
 {
     const TensorDev &d = c.d;
     int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
-    if (chunk >= d.n_chunks) return;
+    const bool cvalid = chunk < d.n_chunks;
+    const int lane = (int)threadIdx.x & 63;
+    const int run_chunk0 = chunk - lane, run_valid = d.n_chunks - run_chunk0;    // the wave's 64 chunks: first, and how many exist
     int64_t row0 = (int64_t)c.rowblock * c.rows;
     int64_t row1 = row0 + c.rows < d.n_tokens ? row0 + c.rows : d.n_tokens;
     constexpr int U = 4;
@@ -74,15 +76,22 @@ __device__ __forceinline__ void warmup_tile(const TileCtx &c)
         Raw8<DT> x[U];
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (i0 + u < row1) x[u].load_stream(c.p.x, (i0 + u) * d.n_channels + (int64_t)chunk * kChunk);
+            if (i0 + u < row1 && cvalid) x[u].load_stream(c.p.x, (i0 + u) * d.n_channels + (int64_t)chunk * kChunk);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (i0 + u >= row1) break;
             int64_t e = (i0 + u) * d.n_channels + (int64_t)chunk * kChunk;
-            x[u].store(c.p.recon, e);
-            Raw8<ET> zero;
-            zero.zero();
-            zero.store(c.p.err, e);
+            if (cvalid) {
+                if (DT == BF16) x[u].store_stream(c.p.recon, e); else x[u].store(c.p.recon, e);
+            }
+            if (ET == F32) {        // zeros need no exchange: every lane fills the pieces a whole-line store gives it
+                const f32x4 zero[2] = {(f32x4)(0.0f), (f32x4)(0.0f)};
+                lines_store_stream<64>(static_cast<float *>(c.p.err) + (i0 + u) * d.n_channels + (int64_t)run_chunk0 * kChunk, lane, run_valid, zero);
+            } else if (cvalid) {
+                Raw8<ET> zero;
+                zero.zero();
+                zero.store_stream(c.p.err, e);
+            }
         }
     }
 }
@@ -381,12 +390,14 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c, float *patch)
 // N:M block sparsifier (Sec. 3.4), blocks of 8 channels: one lane selects, packs and decodes its own
 // block; the row's mask bytes go where 1-bit codes would, the kept values behind all masks.
 template <int DT, int KEEP, bool PAIR, int EF, int ET, bool FUSED>
-__device__ __forceinline__ void nm_encode_tile(const TileCtx &c)
+__device__ __forceinline__ void nm_encode_tile(const TileCtx &c, float *patch)
 {
     const TensorDev &d = c.d;
     const TensorPtrs &p = c.p;
     const int chunk = c.colblock * kTileThreads + (int)threadIdx.x;
-    if (chunk >= d.n_chunks) return;
+    const bool cvalid = chunk < d.n_chunks;         // every lane stays alive for the whole-line store of the error row
+    const int lane = (int)threadIdx.x & 63;
+    const int run_chunk0 = chunk - lane, run_valid = d.n_chunks - run_chunk0;
     const int64_t row0 = (int64_t)c.rowblock * c.rows;
     const int64_t row1 = row0 + c.rows < d.n_tokens ? row0 + c.rows : d.n_tokens;
     const int64_t C = d.n_channels;
@@ -400,7 +411,7 @@ __device__ __forceinline__ void nm_encode_tile(const TileCtx &c)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t i = i0 + u;
-            if (i < row1) {
+            if (i < row1 && cvalid) {
                 const int64_t e = i * C + (int64_t)chunk * kChunk;
                 xr[u].load(p.x, e);
                 // fused: the line is written back by this workgroup, and the streaming hint on its load pays (cfg4 4.09 -> 3.98 ms)
@@ -425,7 +436,7 @@ __device__ __forceinline__ void nm_encode_tile(const TileCtx &c)
             uint32_t vals[KEEP];
             F8 dq;
             nm_values8<DT, KEEP>(z, mask, vals, dq);
-            store_codes_wide<1>(p.codes + i * d.n_chunks, chunk, mask, wide);
+            if (cvalid) store_codes_wide<1>(p.codes + i * d.n_chunks, chunk, mask, wide);
             if (PAIR) {
                 // the even lane writes the block: its own kept values, then the odd lane's
                 const int mine = __builtin_popcount(mask);
@@ -443,11 +454,11 @@ __device__ __forceinline__ void nm_encode_tile(const TileCtx &c)
                 if (DT == BF16 && KEEP == 1 && wide) {
                     // two blocks of a lane quad share one dword (whole quads are active: 32 | C)
                     const uint32_t next = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)block[0], 0xAA, 0xF, 0xF, false);   // quad_perm [2,2,2,2]
-                    if ((chunk & 3) == 0) *gmut<uint32_t>(dst) = (block[0] & 0xFFFFu) | (next << 16);
-                } else if ((chunk & 1) == 0) {
+                    if (cvalid && (chunk & 3) == 0) *gmut<uint32_t>(dst) = (block[0] & 0xFFFFu) | (next << 16);
+                } else if (cvalid && (chunk & 1) == 0) {
                     nm_store_values<DT, KEEP>(dst, chunk >> 1, block, false);
                 }
-            } else {
+            } else if (cvalid) {
                 nm_store_values<DT, KEEP>(values + (i * d.n_chunks + chunk) * kValueBytes, chunk, vals, wide);
             }
             const int64_t e = i * C + (int64_t)chunk * kChunk;
@@ -458,28 +469,34 @@ __device__ __forceinline__ void nm_encode_tile(const TileCtx &c)
                 if (EF == EF_OFF) lost = eold.v[k] + lost;
                 enew.v[k] = lost;
             }
-            Raw8<ET> eo;
-            eo.narrow(enew);
-            eo.store(p.err, e);
-            if (FUSED) {
+            if (ET == F32) {                    // whole 128-byte lines per store, streaming
+                f32x4 pieces[2];
+                lines_exchange<64>(patch, lane, enew, pieces);
+                lines_store_stream<64>(static_cast<float *>(p.err) + i * C + (int64_t)run_chunk0 * kChunk, lane, run_valid, pieces);
+            } else if (cvalid) {
+                Raw8<ET> eo;
+                eo.narrow(enew);
+                eo.store_stream(p.err, e);
+            }
+            if (FUSED && cvalid) {
                 F8 nb;
 #pragma unroll
                 for (int k = 0; k < 8; ++k) nb.v[k] = (EF == EF_NAIVE) ? dq.v[k] : b.v[k] + dq.v[k];
                 Raw8<DT> out;
                 out.narrow(nb);
-                out.store(p.recon, e);
+                if (DT == BF16) out.store_stream(p.recon, e); else out.store(p.recon, e);
             }
         }
     }
 }
 
 template <int DT, bool PAIR, int EF, int ET, bool FUSED>
-__device__ __forceinline__ void nm_encode_dispatch(const TileCtx &c)
+__device__ __forceinline__ void nm_encode_dispatch(const TileCtx &c, float *patch)
 {
     const TensorDev &d = c.d;
-    if (d.bits == 1) nm_encode_tile<DT, 1, PAIR, EF, ET, FUSED>(c);
-    else if (d.bits == 2) nm_encode_tile<DT, 2, PAIR, EF, ET, FUSED>(c);
-    else nm_encode_tile<DT, 4, PAIR, EF, ET, FUSED>(c);
+    if (d.bits == 1) nm_encode_tile<DT, 1, PAIR, EF, ET, FUSED>(c, patch);
+    else if (d.bits == 2) nm_encode_tile<DT, 2, PAIR, EF, ET, FUSED>(c, patch);
+    else nm_encode_tile<DT, 4, PAIR, EF, ET, FUSED>(c, patch);
 }
 
 template <int DT, int EF, int ET, bool FUSED>
@@ -515,10 +532,12 @@ __global__ __launch_bounds__(kTileThreads) void k_encode(BatchView v, LaunchRang
 template <int EF, int ET, bool FUSED, bool PAIR, int DTS>
 __global__ __launch_bounds__(kTileThreads) void k_encode_nm(BatchView v, LaunchRange r)
 {
+    __shared__ __attribute__((aligned(16))) float patches[kTileThreads / 64][512];
     TileCtx c = locate_tile<true>(v, r);
     if (c.d.scale != SPARSE_NM || (c.d.nm_block == 16) != PAIR) return;
-    if (is_bf16<DTS>(c.d)) nm_encode_dispatch<BF16, PAIR, EF, ET, FUSED>(c);
-    else nm_encode_dispatch<F32, PAIR, EF, ET, FUSED>(c);
+    float *patch = patches[(int)threadIdx.x >> 6];
+    if (is_bf16<DTS>(c.d)) nm_encode_dispatch<BF16, PAIR, EF, ET, FUSED>(c, patch);
+    else nm_encode_dispatch<F32, PAIR, EF, ET, FUSED>(c, patch);
 }
 
 // ---------------------------------------------------------------- a6 + a8: receiver decode
@@ -577,7 +596,8 @@ __device__ __forceinline__ void decode_tile(const TileCtx &c, bool replace)
             for (int k = 0; k < 8; ++k) nb.v[k] = replace ? dq.v[k] : b.v[k] + dq.v[k];
             Raw8<DT> out;
             out.narrow(nb);
-            out.store(p.recon, i * C + (int64_t)chunk * kChunk);
+            if (DT == BF16) out.store_stream(p.recon, i * C + (int64_t)chunk * kChunk);     // a whole line per 8 lanes, written once
+            else out.store(p.recon, i * C + (int64_t)chunk * kChunk);
         }
     }
 }
@@ -631,7 +651,8 @@ __device__ __forceinline__ void nm_decode_tile(const TileCtx &c, bool replace)
             for (int k = 0; k < 8; ++k) nb.v[k] = replace ? dq.v[k] : b.v[k] + dq.v[k];
             Raw8<DT> out;
             out.narrow(nb);
-            out.store(p.recon, i * C + (int64_t)chunk * kChunk);
+            if (DT == BF16) out.store_stream(p.recon, i * C + (int64_t)chunk * kChunk);
+            else out.store(p.recon, i * C + (int64_t)chunk * kChunk);
         }
     }
 }
@@ -669,7 +690,7 @@ __global__ __launch_bounds__(kTileThreads) void k_decode(BatchView v, LaunchRang
     if (is_bf16<DTS>(c.d)) decode_dispatch<BF16>(c, r.naive != 0); else decode_dispatch<F32>(c, r.naive != 0);
 }
 
-// ---------------------------------------------------------------- pointer table upload
+// ---------------------------------------------------------------- table uploads and fills
 
 // The per-call device pointers travel in the kernel arguments (captured at
 // launch, so the host arrays may be reused at once) and are written to the
@@ -680,6 +701,25 @@ __global__ void k_upload_ptrs(PtrChunk chunk, TensorPtrs *dst, int n)
     if (i < n) dst[i] = chunk.p[i];
 }
 
+// The same way for the context's own tables (descriptors, prefix arrays): no host-to-device copy, so a
+// context can be set up where copies from pageable memory are not allowed.
+__global__ void k_upload_words(WordChunk chunk, uint32_t *dst, int n)
+{
+    for (int i = (int)threadIdx.x; i < n; i += (int)blockDim.x) dst[i] = chunk.w[i];
+}
+
+__global__ void k_fill_words(uint32_t *dst, uint32_t value, uint32_t n)
+{
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) dst[i] = value;
+}
+
+// item_tensor[i] = t for the items [item_prefix[t], item_prefix[t + 1]) of tensor t = blockIdx.x
+__global__ void k_fill_item_tensor(const uint32_t *item_prefix, uint32_t *item_tensor)
+{
+    const uint32_t t = blockIdx.x, lo = item_prefix[t], hi = item_prefix[t + 1];
+    for (uint32_t i = lo + threadIdx.x; i < hi; i += blockDim.x) item_tensor[i] = t;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------- host-side launchers
@@ -687,6 +727,41 @@ __global__ void k_upload_ptrs(PtrChunk chunk, TensorPtrs *dst, int n)
 hipError_t launch_upload_ptrs(const PtrChunk &chunk, TensorPtrs *dst, int n, hipStream_t s)
 {
     hipLaunchKernelGGL(k_upload_ptrs, dim3(1), dim3(kMaxUploadTensors), 0, s, chunk, dst, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_upload_bytes(const void *src, void *dst, size_t bytes, hipStream_t s)
+{
+    const uint32_t *from = static_cast<const uint32_t *>(src);      // tables are arrays of 4-byte words
+    uint32_t *to = static_cast<uint32_t *>(dst);
+    size_t words = bytes / 4;
+    while (words > 0) {
+        WordChunk chunk;
+        const int n = words < (size_t)kUploadWords ? (int)words : kUploadWords;
+        for (int i = 0; i < n; ++i) chunk.w[i] = from[i];
+        hipLaunchKernelGGL(k_upload_words, dim3(1), dim3(256), 0, s, chunk, to, n);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        from += n;
+        to += n;
+        words -= (size_t)n;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_fill_words(void *dst, uint32_t value, size_t n_words, hipStream_t s)
+{
+    if (n_words == 0) return hipSuccess;
+    const size_t want = (n_words + 255) / 256;
+    hipLaunchKernelGGL(k_fill_words, dim3((unsigned)(want < 1024 ? want : 1024)), dim3(256), 0, s, static_cast<uint32_t *>(dst), value,
+                       (uint32_t)n_words);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_item_tensor(const uint32_t *item_prefix, uint32_t *item_tensor, int n_tensors, hipStream_t s)
+{
+    if (n_tensors <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill_item_tensor, dim3((unsigned)n_tensors), dim3(256), 0, s, item_prefix, item_tensor);
     return hipGetLastError();
 }
 

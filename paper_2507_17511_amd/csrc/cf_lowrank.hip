@@ -492,7 +492,7 @@ constexpr int kApplySpan = CF_APPLY_SPAN;                   // channels per work
 constexpr int kApplyPitch = kApplyChannels + 4;             // floats per token row of the patch
 
 template <int DT, int ET, bool SENDER, bool UPDATE>
-__device__ __forceinline__ void lr_apply_body(const TensorDev &d, const TensorPtrs &p, float *patch)
+__device__ __forceinline__ void lr_apply_body(const TensorDev &d, const TensorPtrs &p, float *patch, float *epatch)
 {
     const int lane = (int)threadIdx.x & 63, wave = (int)threadIdx.x >> 6;
     const int n = lane & 31, h = lane >> 5;
@@ -547,34 +547,40 @@ __device__ __forceinline__ void lr_apply_body(const TensorDev &d, const TensorPt
         for (int it = 0; it < 4; ++it) {
             const int tl = trow + 8 * it;
             const int64_t tok = tok_base + tl;
-            if (live[it]) {
-                const f32x4 *src = reinterpret_cast<const f32x4 *>(patch + tl * kApplyPitch + chunk * 8);
-                const f32x4 d0 = src[0], d1 = src[1];
-                F8 D;
-                D.v[0] = d0.x; D.v[1] = d0.y; D.v[2] = d0.z; D.v[3] = d0.w;
-                D.v[4] = d1.x; D.v[5] = d1.y; D.v[6] = d1.z; D.v[7] = d1.w;
-                const int64_t e0 = tok * C + (int64_t)sub0 * 32 + chunk * 8;
-                const F8 b = br[it].widen();
-                if (SENDER) {
-                    const F8 x = xr[it].widen();
-                    F8 lost;
+            // every lane goes through the exchange of the error row (dead lanes carry values nobody stores)
+            const f32x4 *src = reinterpret_cast<const f32x4 *>(patch + tl * kApplyPitch + chunk * 8);
+            const f32x4 d0 = src[0], d1 = src[1];
+            F8 D;
+            D.v[0] = d0.x; D.v[1] = d0.y; D.v[2] = d0.z; D.v[3] = d0.w;
+            D.v[4] = d1.x; D.v[5] = d1.y; D.v[6] = d1.z; D.v[7] = d1.w;
+            const int64_t e0 = tok * C + (int64_t)sub0 * 32 + chunk * 8;
+            const F8 b = br[it].widen();
+            if (SENDER) {
+                const F8 x = xr[it].widen();
+                F8 lost;
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        const float z = x.v[k] - b.v[k];
-                        lost.v[k] = z - D.v[k];
-                    }
+                for (int k = 0; k < 8; ++k) {
+                    const float z = x.v[k] - b.v[k];
+                    lost.v[k] = z - D.v[k];
+                }
+                if (ET == F32) {        // the 8 lanes of a token row send its 256 bytes as two whole lines
+                    f32x4 pieces[2];
+                    lines_exchange<8>(epatch, lane, lost, pieces);
+                    if (tok < d.n_tokens)
+                        lines_store_stream<8>(static_cast<float *>(p.err) + tok * C + (int64_t)sub0 * 32, chunk, cnt * 4, pieces);
+                } else if (live[it]) {
                     Raw8<ET> eo;
                     eo.narrow(lost);
-                    eo.store(p.err, e0);
+                    eo.store_stream(p.err, e0);
                 }
-                if (UPDATE) {
-                    F8 nb;
+            }
+            if (UPDATE && live[it]) {
+                F8 nb;
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) nb.v[k] = b.v[k] + D.v[k];
-                    Raw8<DT> out;
-                    out.narrow(nb);
-                    out.store(p.recon, e0);
-                }
+                for (int k = 0; k < 8; ++k) nb.v[k] = b.v[k] + D.v[k];
+                Raw8<DT> out;
+                out.narrow(nb);
+                if (DT == BF16) out.store_stream(p.recon, e0); else out.store(p.recon, e0);
             }
         }
         __builtin_amdgcn_wave_barrier();
@@ -589,9 +595,11 @@ __global__ __launch_bounds__(256) void k_lr_apply(BatchView v, LaunchRange r)
     const TensorDev d = v.descs[t];
     if (d.scale != LOWRANK) return;
     const TensorPtrs p = v.ptrs[t];
+    __shared__ __attribute__((aligned(16))) float epatches[4][512];       // the error rows' way to whole lines (2 KB per wave)
     float *patch = patches[(int)threadIdx.x >> 6];
-    if (d.dtype == BF16) lr_apply_body<BF16, ET, SENDER, UPDATE>(d, p, patch);
-    else lr_apply_body<F32, ET, SENDER, UPDATE>(d, p, patch);
+    float *epatch = epatches[(int)threadIdx.x >> 6];
+    if (d.dtype == BF16) lr_apply_body<BF16, ET, SENDER, UPDATE>(d, p, patch, epatch);
+    else lr_apply_body<F32, ET, SENDER, UPDATE>(d, p, patch, epatch);
 }
 
 }  // namespace

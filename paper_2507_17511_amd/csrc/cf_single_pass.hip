@@ -73,6 +73,9 @@ __device__ __forceinline__ float tree_over_published(int n, const float *mine, i
 #pragma unroll
             for (int u = 0; u < NB; ++u) pending |= (__float_as_uint(vals[u]) == kUnpublished ? 1u : 0u) << u;
             if (pending == 0) break;
+#ifdef CF_EXP_NOWAIT
+            break;      // timing experiment only: wrong scales
+#endif
             if (spins >= kSpinLimit) { ok = false; break; }
             __builtin_amdgcn_s_sleep(1);
 #pragma unroll
@@ -92,11 +95,38 @@ __device__ __forceinline__ float tree_over_published(int n, const float *mine, i
 
 // SCH: channels per stripe (kStripeChannels or kStripeChannelsWide); the 256 lanes are SCH / 8 chunks across
 // by 2048 / SCH row-lanes down.
+#ifndef CF_SP_LDS_ROWS
+#define CF_SP_LDS_ROWS 0
+#endif
 template <int SCH> struct alignas(16) Shared {
     float red[kPersistThreads / (SCH / kChunk)][SCH];
     float scale[SCH];
     uint32_t ok;
+    u32x4 stage[CF_SP_LDS_ROWS > 0 ? CF_SP_LDS_ROWS : 1][kPersistThreads];     // recon rows that wait in LDS instead of registers
 };
+
+// A lane's own slot of a staged row (only the lane itself ever touches it: no barrier).
+template <int DT> __device__ __forceinline__ void stage_put(u32x4 (*stage)[kPersistThreads], int k, int tid, const Raw8<DT> &r);
+template <> __device__ __forceinline__ void stage_put<BF16>(u32x4 (*stage)[kPersistThreads], int k, int tid, const Raw8<BF16> &r) { stage[k][tid] = r.w; }
+template <> __device__ __forceinline__ void stage_put<F32>(u32x4 (*stage)[kPersistThreads], int k, int tid, const Raw8<F32> &r)
+{
+    stage[2 * k][tid] = __builtin_bit_cast(u32x4, r.a);
+    stage[2 * k + 1][tid] = __builtin_bit_cast(u32x4, r.b);
+}
+template <int DT> __device__ __forceinline__ Raw8<DT> stage_get(u32x4 (*stage)[kPersistThreads], int k, int tid);
+template <> __device__ __forceinline__ Raw8<BF16> stage_get<BF16>(u32x4 (*stage)[kPersistThreads], int k, int tid)
+{
+    Raw8<BF16> r;
+    r.w = stage[k][tid];
+    return r;
+}
+template <> __device__ __forceinline__ Raw8<F32> stage_get<F32>(u32x4 (*stage)[kPersistThreads], int k, int tid)
+{
+    Raw8<F32> r;
+    r.a = __builtin_bit_cast(f32x4, stage[2 * k][tid]);
+    r.b = __builtin_bit_cast(f32x4, stage[2 * k + 1][tid]);
+    return r;
+}
 
 template <int DT, int BITS, int ET, bool FUSED, int SCH>
 __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev &d, const TensorPtrs &p, int stripe,
@@ -111,20 +141,38 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
     const int64_t row0 = (int64_t)rb * d.p_rows + rl * RPT;
     const int64_t C = d.n_channels;
 
-    // ---- load the lane's rows (raw), all in flight at once
-    Raw8<DT> xr[RPT], br[RPT];
+    // ---- load the lane's rows (raw), all in flight at once.  The first LR rows of recon wait in LDS,
+    // not in registers (loaded first, so that they have arrived and gone to LDS while the rest is on its way).
+    constexpr int LR = (DT == BF16) ? CF_SP_LDS_ROWS : CF_SP_LDS_ROWS / 2;
+    Raw8<DT> xr[RPT], br[RPT - LR > 0 ? RPT - LR : 1];
+    {
+        Raw8<DT> tmp[LR > 0 ? LR : 1];
 #pragma unroll
-    for (int k = 0; k < RPT; ++k) {
-        const int64_t row = row0 + k;
-        if (cvalid && row < d.n_tokens) {
-            const int64_t e = row * C + (int64_t)chunk * kChunk;
-            xr[k].load_stream(p.x, e);       // read once: keep the caches for the partials and the outputs
-            br[k].load_stream(p.recon, e);
-        } else {                                    // zero padding of the tree / masked lanes
-            xr[k].zero();
-            br[k].zero();
+        for (int k = 0; k < LR; ++k) {
+            const int64_t row = row0 + k;
+            if (cvalid && row < d.n_tokens) tmp[k].load_stream(p.recon, row * C + (int64_t)chunk * kChunk);
+            else tmp[k].zero();
         }
+#pragma unroll
+        for (int k = 0; k < RPT; ++k) {
+            const int64_t row = row0 + k;
+            if (cvalid && row < d.n_tokens) {
+                const int64_t e = row * C + (int64_t)chunk * kChunk;
+#ifdef CF_EXP_X_PLAIN
+                xr[k].load(p.x, e);
+#else
+                xr[k].load_stream(p.x, e);       // read once: keep the caches for the partials and the outputs
+#endif
+                if (k >= LR) br[k >= LR ? k - LR : 0].load_stream(p.recon, e);
+            } else {                                    // zero padding of the tree / masked lanes
+                xr[k].zero();
+                if (k >= LR) br[k >= LR ? k - LR : 0].zero();
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < LR; ++k) stage_put<DT>(sh.stage, k, tid, tmp[k]);
     }
+    auto recon_row = [&](int k) -> Raw8<DT> { return k < LR ? stage_get<DT>(sh.stage, k < LR ? k : 0, tid) : br[k >= LR ? k - LR : 0]; };
 
     // ---- a3, level 1: balanced tree over the lane's RPT consecutive rows
     // (a binary-counter stack: after row k the slots hold the partial trees of the rows seen so far;
@@ -134,7 +182,7 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
     const F8 none = {};
 #pragma unroll
     for (int k = 0; k < RPT; ++k) {
-        F8 z = residual8<EF_RECON>(xr[k].widen(), br[k].widen(), none);
+        F8 z = residual8<EF_RECON>(xr[k].widen(), recon_row(k).widen(), none);
         F8 a;
 #pragma unroll
         for (int j = 0; j < 8; ++j) a.v[j] = fabsf(z.v[j]);
@@ -201,7 +249,7 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
 #pragma unroll
     for (int k = 0; k < RPT; ++k) {
         xr[k].opaque();
-        br[k].opaque();
+        if (k >= LR) br[k >= LR ? k - LR : 0].opaque();
     }
     {
         F8 s;
@@ -223,7 +271,7 @@ __device__ __forceinline__ bool persist_item(const BatchView &v, const TensorDev
             const bool rvalid = row < d.n_tokens;
             __builtin_amdgcn_sched_barrier(0);      // one row at a time: keeps the live set inside the register budget
             const int64_t e = row * C + (int64_t)chunk * kChunk;
-            F8 b = br[k].widen();
+            F8 b = recon_row(k).widen();
             F8 z = residual8<EF_RECON>(xr[k].widen(), b, none);     // masked lanes and rows hold zeros
             F8 dq;
             uint32_t packed = quant8<BITS>(z, s, dq);
