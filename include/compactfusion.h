@@ -219,6 +219,28 @@ cf_status cf_step_fused(cf_ctx *ctx, int32_t first, int32_t count, const void *c
                         void *const *recon, void *const *err, void *const *codes,
                         void *const *scales, void *stream);
 
+/* For callers that cannot allocate device memory (code that runs under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): one whole codec
+ * step, as cf_step_fused over all `n_tensors` tensors, with NO context and NO
+ * workspace argument.  Its scratch is a device array inside the library
+ * (CF_STATIC_SCRATCH_BYTES per GPU, held until the process ends); the call
+ * allocates nothing, on the device or through any library.  The tensors must need
+ * no more workspace than that (compare cf_workspace_bytes): otherwise
+ * CF_ERR_WORKSPACE, nothing enqueued.  There is no warm-up call for it: the caller
+ * vouches that recon and err hold valid state (recon = x_0, err = 0 after the
+ * uncompressed step).  Outputs are bit-identical to cf_step_fused on the same
+ * buffers.  All calls on one GPU share that GPU's array: calls that overlap in
+ * time on one GPU race, whatever their streams; calls in stream order are fine,
+ * with any mix of shapes (the tables are laid out again when the tensors or the
+ * options change).  Uses the device that is current at the call; not thread-safe.
+ * The bounded waits of the single-pass kernel apply as for cf_step_fused, but
+ * there is no context to ask about them: pass CF_FLAG_TWO_KERNEL for a launch
+ * sequence without any wait between workgroups. */
+#define CF_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+cf_status cf_step_fused_static(const cf_tensor_desc *descs, int32_t n_tensors, const cf_options *opts,
+                               const void *const *x, void *const *recon, void *const *err,
+                               void *const *codes, void *const *scales, void *stream);
+
 /* Frees the host-side context (never device memory).  NULL is allowed. */
 void cf_destroy(cf_ctx *ctx);
 

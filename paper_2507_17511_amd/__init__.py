@@ -31,7 +31,8 @@ CF_FLAG_LOWRANK_INT4 = 0x4
 
 EXPORTS = ["cf_sizes", "cf_workspace_bytes", "cf_init", "cf_warmup", "cf_set_warm", "cf_compress",
            "cf_decompress", "cf_step_fused", "cf_destroy", "cf_status_string", "cf_last_hip_error",
-           "cf_profile_next_call", "cf_profile_launch_count", "cf_profile_kernel_name", "cf_check_device"]
+           "cf_profile_next_call", "cf_profile_launch_count", "cf_profile_kernel_name", "cf_check_device",
+           "cf_step_fused_static"]
 
 
 class cf_tensor_desc(ctypes.Structure):
@@ -97,6 +98,8 @@ def lib() -> ctypes.CDLL:
         L.cf_profile_launch_count.argtypes = [vp]
         L.cf_profile_kernel_name.restype = ctypes.c_char_p
         L.cf_profile_kernel_name.argtypes = [vp, i32]
+        L.cf_step_fused_static.restype = i32
+        L.cf_step_fused_static.argtypes = [dp, i32, op, pp, pp, pp, pp, pp, vp]
         _lib = L
     return _lib
 
@@ -205,6 +208,17 @@ def cf_decompress(ctx, first: int, count: int, codes, scales, recon, stream=None
 def cf_step_fused(ctx, first: int, count: int, x, recon, err, codes, scales, stream=None) -> None:
     _check(lib().cf_step_fused(ctx, first, count, _pa(x), _pa(recon), _pa(err), _pa(codes), _pa(scales),
                                _addr(stream)), "cf_step_fused", ctx)
+
+
+CF_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def cf_step_fused_static(descs, opts: Optional[cf_options], x, recon, err, codes, scales, stream=None) -> None:
+    """One whole codec step over all tensors with the library's own static scratch: no context, no workspace,
+    no allocation."""
+    arr = _descs(descs)
+    _check(lib().cf_step_fused_static(arr, len(arr), ctypes.byref(opts) if opts else None, _pa(x), _pa(recon), _pa(err),
+                                      _pa(codes), _pa(scales), _addr(stream)), "cf_step_fused_static")
 
 
 def cf_profile_next_call(ctx, events, n_pairs: int) -> None:

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcompactfusion.so")
-SOURCES = ["cf_api.cpp", "cf_kernels.hip", "cf_single_pass.hip", "cf_lowrank.hip"]
+SOURCES = ["cf_api.cpp", "cf_kernels.hip", "cf_single_pass.hip", "cf_lowrank.hip", "cf_static.hip"]
 HEADERS = [os.path.join(CSRC, "cf_internal.h"), os.path.join(CSRC, "cf_device.h"), os.path.join(ROOT, "include", "compactfusion.h")]
 
 # -ffp-contract=off: one rounding per fp32 operation (results must match a plain

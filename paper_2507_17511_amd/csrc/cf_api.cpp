@@ -852,4 +852,42 @@ cf_status cf_decompress(cf_ctx *ctx, int32_t first, int32_t count, const void *c
     return CF_OK;
 }
 
+namespace {
+constexpr int kMaxStaticDevices = 64;
+cf_ctx *g_static_ctx[kMaxStaticDevices];       // the context over each device's static scratch, kept while the tensors stay the same
+}  // namespace
+
+cf_status cf_step_fused_static(const cf_tensor_desc *descs, int32_t n_tensors, const cf_options *opts, const void *const *x,
+                               void *const *recon, void *const *err, void *const *codes, void *const *scales, void *stream)
+{
+    cf_options o;
+    cf_status st = check_opts(opts, o);
+    if (st != CF_OK) return st;
+    if (!descs || n_tensors < 1) return CF_ERR_INVALID_ARG;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxStaticDevices) {
+        (void)hipGetLastError();
+        return CF_ERR_DEVICE;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    cf_ctx *&ctx = g_static_ctx[dev];
+    const bool same = ctx && ctx->descs.size() == (size_t)n_tensors &&
+                      std::memcmp(ctx->descs.data(), descs, sizeof(cf_tensor_desc) * (size_t)n_tensors) == 0 &&
+                      std::memcmp(&ctx->opts, &o, sizeof o) == 0;
+    if (!same) {
+        delete ctx;
+        ctx = nullptr;
+        void *ws = nullptr;
+        if (static_scratch(&ws) != hipSuccess) {
+            (void)hipGetLastError();
+            return CF_ERR_DEVICE;
+        }
+        // lays the tables out in the scratch array afresh (CF_ERR_WORKSPACE if these tensors need more than it holds)
+        st = make_ctx(&ctx, descs, n_tensors, o, ws, kStaticScratchBytes, s);
+        if (st != CF_OK) return st;
+        for (auto &w : ctx->warm) w = 1;        // the caller vouches for recon and err
+    }
+    return run_sender(ctx, 0, n_tensors, x, recon, err, codes, scales, stream, true);
+}
+
 }  // extern "C"

@@ -143,6 +143,10 @@ hipError_t launch_upload_bytes(const void *src, void *dst, size_t bytes, hipStre
 hipError_t launch_fill_words(void *dst, uint32_t value, size_t n_words, hipStream_t s);
 hipError_t launch_fill_item_tensor(const uint32_t *item_prefix, uint32_t *item_tensor, int n_tensors, hipStream_t s);
 
+// The library's own scratch for callers that cannot allocate (cf_static.hip): one array per device, resolved on
+// first use with that device current.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+hipError_t static_scratch(void **ptr);
 hipError_t launch_warmup(const BatchView &v, const LaunchRange &r, int err_dtype, hipStream_t s);
 hipError_t launch_colreduce(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, hipStream_t s);
 hipError_t launch_finalize(const BatchView &v, const LaunchRange &r, hipStream_t s);
