@@ -148,10 +148,10 @@ typedef struct {
     int32_t ef;        /* cf_ef_mode */
     int32_t err_dtype; /* cf_dtype of every error buffer; CF_F32 by default */
     uint32_t flags;    /* CF_FLAG_* */
-    int32_t tile_rows; /* rows per workgroup tile of the scale reduction: 0 = chosen by the library,
-                          else 8, 16, 32 or 64 (a tuning knob: results do not depend on it) */
-    int32_t encode_rows; /* rows per workgroup of the element-wise kernels: 0 = chosen by the
-                            library, else 1..64 (a tuning knob as well) */
+    /* The two fields below are for TESTING ONLY (leave them 0): they force launch shapes the library
+       otherwise picks by itself, so that tests can show that no result depends on them. */
+    int32_t tile_rows;   /* rows per workgroup tile of the two-kernel path's scale reduction: 8, 16, 32 or 64 */
+    int32_t encode_rows; /* rows per workgroup of the receiver's kernel (cf_decompress): 1..64 */
 } cf_options;
 
 /* A channel scale needs every token of a channel before any code of that

@@ -195,7 +195,7 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
         tiles += (uint64_t)v.n_rowblocks * (uint64_t)v.n_colblocks;
         // element-wise kernels do best with short-lived workgroups: a lane never has to wait for
         // its own stores before it can use its next loads
-        v.ew_rows = o.encode_rows ? o.encode_rows : 1;
+        v.ew_rows = 1;
         v.ew_n_rowblocks = (int32_t)((d.n_tokens + v.ew_rows - 1) / v.ew_rows);
         v.ew_tile_begin = (uint32_t)ew_tiles;
         L.ew_prefix[t] = (uint32_t)ew_tiles;

@@ -69,30 +69,20 @@ __device__ __forceinline__ void warmup_tile(const TileCtx &c)
     const bool cvalid = chunk < d.n_chunks;
     const int lane = (int)threadIdx.x & 63;
     const int run_chunk0 = chunk - lane, run_valid = d.n_chunks - run_chunk0;    // the wave's 64 chunks: first, and how many exist
-    int64_t row0 = (int64_t)c.rowblock * c.rows;
-    int64_t row1 = row0 + c.rows < d.n_tokens ? row0 + c.rows : d.n_tokens;
-    constexpr int U = 4;
-    for (int64_t i0 = row0; i0 < row1; i0 += U) {
-        Raw8<DT> x[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (i0 + u < row1 && cvalid) x[u].load_stream(c.p.x, (i0 + u) * d.n_channels + (int64_t)chunk * kChunk);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (i0 + u >= row1) break;
-            int64_t e = (i0 + u) * d.n_channels + (int64_t)chunk * kChunk;
-            if (cvalid) {
-                if (DT == BF16) x[u].store_stream(c.p.recon, e); else x[u].store(c.p.recon, e);
-            }
-            if (ET == F32) {        // zeros need no exchange: every lane fills the pieces a whole-line store gives it
-                const f32x4 zero[2] = {(f32x4)(0.0f), (f32x4)(0.0f)};
-                lines_store_stream<64>(static_cast<float *>(c.p.err) + (i0 + u) * d.n_channels + (int64_t)run_chunk0 * kChunk, lane, run_valid, zero);
-            } else if (cvalid) {
-                Raw8<ET> zero;
-                zero.zero();
-                zero.store_stream(c.p.err, e);
-            }
-        }
+    const int64_t i = c.rowblock;                   // element-wise tiles are one row tall
+    const int64_t e = i * d.n_channels + (int64_t)chunk * kChunk;
+    if (cvalid) {
+        Raw8<DT> x;
+        x.load_stream(c.p.x, e);
+        if (DT == BF16) x.store_stream(c.p.recon, e); else x.store(c.p.recon, e);
+    }
+    if (ET == F32) {        // zeros need no exchange: every lane fills the pieces a whole-line store gives it
+        const f32x4 zero[2] = {(f32x4)(0.0f), (f32x4)(0.0f)};
+        lines_store_stream<64>(static_cast<float *>(c.p.err) + i * d.n_channels + (int64_t)run_chunk0 * kChunk, lane, run_valid, zero);
+    } else if (cvalid) {
+        Raw8<ET> zero;
+        zero.zero();
+        zero.store_stream(c.p.err, e);
     }
 }
 
@@ -301,8 +291,7 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c, float *patch)
     const int lane = (int)threadIdx.x & 63;
     const int run_chunk0 = chunk - lane;                                // first chunk of the wave's 64
     const int run_valid = d.n_chunks - run_chunk0;                      // chunks of the wave that exist (may exceed 64 or be <= 0)
-    int64_t row0 = (int64_t)c.rowblock * c.rows;
-    int64_t row1 = row0 + c.rows < d.n_tokens ? row0 + c.rows : d.n_tokens;
+    const int64_t row0 = c.rowblock;            // element-wise tiles are one row tall
     const int64_t C = d.n_channels;
     const int64_t row_bytes = C * BITS / 8;
     const int n_groups = d.n_channels >> 7;
@@ -312,78 +301,68 @@ __device__ __forceinline__ void encode_tile(const TileCtx &c, float *patch)
     if (MODE == 0 && cvalid) s = load_scales8(p.scales, (int64_t)chunk * kChunk);
     if (MODE == 2 && cvalid) vj = load_scales8(p.scales, (int64_t)chunk * kChunk);
 
-    constexpr int U = 4;
-    for (int64_t i0 = row0; i0 < row1; i0 += U) {
-        Raw8<DT> xr[U], br[U];
-        Raw8<ET> er[U];
+    // One row per workgroup (the element-wise tiling): a lane never has to wait for its own stores
+    // before it can use its next loads, and the register file holds one row's worth, not four.
+    const int64_t i = row0;
+    const int64_t e = i * C + (int64_t)chunk * kChunk;
+    Raw8<DT> xr, br;
+    Raw8<ET> er;
+    if (cvalid) {
+        xr.load(p.x, e);
+        // fused: the line is written back by this workgroup, and the streaming hint on its load pays (cfg4 4.09 -> 3.98 ms)
+        if (EF == EF_NAIVE) br.zero();
+        else if (FUSED) br.load_stream(p.recon, e);
+        else br.load(p.recon, e);
+        if (EF == EF_LITERAL || EF == EF_OFF) er.load(p.err, e); else er.zero();
+    } else {
+        xr.zero();
+        br.zero();
+        er.zero();
+    }
+    F8 b = br.widen();
+    F8 eold = er.widen();
+    F8 z = residual8<EF>(xr.widen(), b, eold);
+    if (MODE == 1) {
+        float m = 0.0f;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int64_t i = i0 + u;
-            if (i < row1 && cvalid) {
-                int64_t e = i * C + (int64_t)chunk * kChunk;
-                xr[u].load(p.x, e);
-                // fused: the line is written back by this workgroup, and the streaming hint on its load pays (cfg4 4.09 -> 3.98 ms)
-                if (EF == EF_NAIVE) br[u].zero();
-                else if (FUSED) br[u].load_stream(p.recon, e);
-                else br[u].load(p.recon, e);
-                if (EF == EF_LITERAL || EF == EF_OFF) er[u].load(p.err, e); else er[u].zero();
-            } else {
-                xr[u].zero();
-                br[u].zero();
-                er[u].zero();
-            }
-        }
+        for (int k = 0; k < 8; ++k) m = fmaxf(m, fabsf(z.v[k]));
+        m = row16_max(m);
+        float sg = m / 7.0f;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int64_t i = i0 + u;
-            if (i >= row1) break;               // uniform over the workgroup
-            F8 b = br[u].widen();
-            F8 eold = er[u].widen();
-            F8 z = residual8<EF>(xr[u].widen(), b, eold);
-            if (MODE == 1) {
-                float m = 0.0f;
+        for (int k = 0; k < 8; ++k) s.v[k] = sg;
+        if (cvalid && (threadIdx.x & 15) == 0) gmut<float>(p.scales)[i * n_groups + (chunk >> 4)] = sg;
+    }
+    if (MODE == 2) {
+        const float ui = gconst<float>(p.scales)[C + i];
 #pragma unroll
-                for (int k = 0; k < 8; ++k) m = fmaxf(m, fabsf(z.v[k]));
-                m = row16_max(m);
-                float sg = m / 7.0f;
+        for (int k = 0; k < 8; ++k) s.v[k] = ui * vj.v[k];
+    }
+    F8 dq;
+    uint32_t packed = quant8<BITS>(z, s, dq);
+    if (cvalid) store_codes_wide<BITS>(p.codes + i * row_bytes, chunk, packed, wide);
+    F8 enew;
 #pragma unroll
-                for (int k = 0; k < 8; ++k) s.v[k] = sg;
-                if (cvalid && (threadIdx.x & 15) == 0) gmut<float>(p.scales)[i * n_groups + (chunk >> 4)] = sg;
-            }
-            if (MODE == 2) {
-                const float ui = gconst<float>(p.scales)[C + i];
+    for (int k = 0; k < 8; ++k) {
+        float lost = z.v[k] - dq.v[k];
+        if (EF == EF_OFF) lost = eold.v[k] + lost;
+        enew.v[k] = lost;
+    }
+    if (ET == F32) {                    // whole 128-byte lines per store, streaming
+        f32x4 pieces[2];
+        lines_exchange<64>(patch, lane, enew, pieces);
+        lines_store_stream<64>(static_cast<float *>(p.err) + i * C + (int64_t)run_chunk0 * kChunk, lane, run_valid, pieces);
+    } else if (cvalid) {
+        Raw8<ET> eo;
+        eo.narrow(enew);
+        eo.store_stream(p.err, e);
+    }
+    if (FUSED && cvalid) {
+        F8 nb;
 #pragma unroll
-                for (int k = 0; k < 8; ++k) s.v[k] = ui * vj.v[k];
-            }
-            F8 dq;
-            uint32_t packed = quant8<BITS>(z, s, dq);
-            if (cvalid) store_codes_wide<BITS>(p.codes + i * row_bytes, chunk, packed, wide);
-            int64_t e = i * C + (int64_t)chunk * kChunk;
-            F8 enew;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                float lost = z.v[k] - dq.v[k];
-                if (EF == EF_OFF) lost = eold.v[k] + lost;
-                enew.v[k] = lost;
-            }
-            if (ET == F32) {                    // whole 128-byte lines per store, streaming
-                f32x4 pieces[2];
-                lines_exchange<64>(patch, lane, enew, pieces);
-                lines_store_stream<64>(static_cast<float *>(p.err) + i * C + (int64_t)run_chunk0 * kChunk, lane, run_valid, pieces);
-            } else if (cvalid) {
-                Raw8<ET> eo;
-                eo.narrow(enew);
-                eo.store_stream(p.err, e);
-            }
-            if (FUSED && cvalid) {
-                F8 nb;
-#pragma unroll
-                for (int k = 0; k < 8; ++k) nb.v[k] = (EF == EF_NAIVE) ? dq.v[k] : b.v[k] + dq.v[k];
-                Raw8<DT> out;
-                out.narrow(nb);
-                if (DT == BF16) out.store_stream(p.recon, e); else out.store(p.recon, e);
-            }
-        }
+        for (int k = 0; k < 8; ++k) nb.v[k] = (EF == EF_NAIVE) ? dq.v[k] : b.v[k] + dq.v[k];
+        Raw8<DT> out;
+        out.narrow(nb);
+        if (DT == BF16) out.store_stream(p.recon, e); else out.store(p.recon, e);
     }
 }
 
@@ -398,95 +377,81 @@ __device__ __forceinline__ void nm_encode_tile(const TileCtx &c, float *patch)
     const bool cvalid = chunk < d.n_chunks;         // every lane stays alive for the whole-line store of the error row
     const int lane = (int)threadIdx.x & 63;
     const int run_chunk0 = chunk - lane, run_valid = d.n_chunks - run_chunk0;
-    const int64_t row0 = (int64_t)c.rowblock * c.rows;
-    const int64_t row1 = row0 + c.rows < d.n_tokens ? row0 + c.rows : d.n_tokens;
+    const int64_t i = c.rowblock;                   // element-wise tiles are one row tall
     const int64_t C = d.n_channels;
     const bool wide = (d.n_channels & 31) == 0;
     constexpr int kValueBytes = KEEP * (DT == BF16 ? 2 : 4);
     uint8_t *values = p.codes + ((d.n_tokens * d.n_chunks + 15) / 16) * 16;
-    constexpr int U = 4;
-    for (int64_t i0 = row0; i0 < row1; i0 += U) {
-        Raw8<DT> xr[U], br[U];
-        Raw8<ET> er[U];
+    const int64_t e = i * C + (int64_t)chunk * kChunk;
+    Raw8<DT> xr, br;
+    Raw8<ET> er;
+    if (cvalid) {
+        xr.load(p.x, e);
+        // fused: the line is written back by this workgroup, and the streaming hint on its load pays
+        if (EF == EF_NAIVE) br.zero();
+        else if (FUSED) br.load_stream(p.recon, e);
+        else br.load(p.recon, e);
+        if (EF == EF_LITERAL || EF == EF_OFF) er.load(p.err, e); else er.zero();
+    } else {
+        xr.zero();
+        br.zero();
+        er.zero();
+    }
+    const F8 b = br.widen();
+    const F8 eold = er.widen();
+    const F8 z = residual8<EF>(xr.widen(), b, eold);
+    const uint32_t mask = nm_select8<KEEP, PAIR>(z);
+    uint32_t vals[KEEP];
+    F8 dq;
+    nm_values8<DT, KEEP>(z, mask, vals, dq);
+    if (cvalid) store_codes_wide<1>(p.codes + i * d.n_chunks, chunk, mask, wide);
+    if (PAIR) {
+        // the even lane writes the block: its own kept values, then the odd lane's
+        const int mine = __builtin_popcount(mask);
+        uint32_t theirs[KEEP], block[KEEP];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t i = i0 + u;
-            if (i < row1 && cvalid) {
-                const int64_t e = i * C + (int64_t)chunk * kChunk;
-                xr[u].load(p.x, e);
-                // fused: the line is written back by this workgroup, and the streaming hint on its load pays (cfg4 4.09 -> 3.98 ms)
-                if (EF == EF_NAIVE) br[u].zero();
-                else if (FUSED) br[u].load_stream(p.recon, e);
-                else br[u].load(p.recon, e);
-                if (EF == EF_LITERAL || EF == EF_OFF) er[u].load(p.err, e); else er[u].zero();
-            } else {
-                xr[u].zero();
-                br[u].zero();
-                er[u].zero();
-            }
+        for (int q = 0; q < KEEP; ++q) theirs[q] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)vals[q], 0xB1, 0xF, 0xF, false);
+#pragma unroll
+        for (int q = 0; q < KEEP; ++q) {
+            uint32_t from_theirs = 0u;
+#pragma unroll
+            for (int t = 0; t < KEEP; ++t) from_theirs = (q - mine == t) ? theirs[t] : from_theirs;
+            block[q] = q < mine ? vals[q] : from_theirs;
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t i = i0 + u;
-            if (i >= row1) break;               // uniform over the workgroup
-            const F8 b = br[u].widen();
-            const F8 eold = er[u].widen();
-            const F8 z = residual8<EF>(xr[u].widen(), b, eold);
-            const uint32_t mask = nm_select8<KEEP, PAIR>(z);
-            uint32_t vals[KEEP];
-            F8 dq;
-            nm_values8<DT, KEEP>(z, mask, vals, dq);
-            if (cvalid) store_codes_wide<1>(p.codes + i * d.n_chunks, chunk, mask, wide);
-            if (PAIR) {
-                // the even lane writes the block: its own kept values, then the odd lane's
-                const int mine = __builtin_popcount(mask);
-                uint32_t theirs[KEEP], block[KEEP];
-#pragma unroll
-                for (int q = 0; q < KEEP; ++q) theirs[q] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)vals[q], 0xB1, 0xF, 0xF, false);
-#pragma unroll
-                for (int q = 0; q < KEEP; ++q) {
-                    uint32_t from_theirs = 0u;
-#pragma unroll
-                    for (int t = 0; t < KEEP; ++t) from_theirs = (q - mine == t) ? theirs[t] : from_theirs;
-                    block[q] = q < mine ? vals[q] : from_theirs;
-                }
-                uint8_t *dst = values + (i * (d.n_chunks >> 1) + (chunk >> 1)) * kValueBytes;
-                if (DT == BF16 && KEEP == 1 && wide) {
-                    // two blocks of a lane quad share one dword (whole quads are active: 32 | C)
-                    const uint32_t next = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)block[0], 0xAA, 0xF, 0xF, false);   // quad_perm [2,2,2,2]
-                    if (cvalid && (chunk & 3) == 0) *gmut<uint32_t>(dst) = (block[0] & 0xFFFFu) | (next << 16);
-                } else if (cvalid && (chunk & 1) == 0) {
-                    nm_store_values<DT, KEEP>(dst, chunk >> 1, block, false);
-                }
-            } else if (cvalid) {
-                nm_store_values<DT, KEEP>(values + (i * d.n_chunks + chunk) * kValueBytes, chunk, vals, wide);
-            }
-            const int64_t e = i * C + (int64_t)chunk * kChunk;
-            F8 enew;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                float lost = z.v[k] - dq.v[k];
-                if (EF == EF_OFF) lost = eold.v[k] + lost;
-                enew.v[k] = lost;
-            }
-            if (ET == F32) {                    // whole 128-byte lines per store, streaming
-                f32x4 pieces[2];
-                lines_exchange<64>(patch, lane, enew, pieces);
-                lines_store_stream<64>(static_cast<float *>(p.err) + i * C + (int64_t)run_chunk0 * kChunk, lane, run_valid, pieces);
-            } else if (cvalid) {
-                Raw8<ET> eo;
-                eo.narrow(enew);
-                eo.store_stream(p.err, e);
-            }
-            if (FUSED && cvalid) {
-                F8 nb;
-#pragma unroll
-                for (int k = 0; k < 8; ++k) nb.v[k] = (EF == EF_NAIVE) ? dq.v[k] : b.v[k] + dq.v[k];
-                Raw8<DT> out;
-                out.narrow(nb);
-                if (DT == BF16) out.store_stream(p.recon, e); else out.store(p.recon, e);
-            }
+        uint8_t *dst = values + (i * (d.n_chunks >> 1) + (chunk >> 1)) * kValueBytes;
+        if (DT == BF16 && KEEP == 1 && wide) {
+            // two blocks of a lane quad share one dword (whole quads are active: 32 | C)
+            const uint32_t next = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)block[0], 0xAA, 0xF, 0xF, false);   // quad_perm [2,2,2,2]
+            if (cvalid && (chunk & 3) == 0) *gmut<uint32_t>(dst) = (block[0] & 0xFFFFu) | (next << 16);
+        } else if (cvalid && (chunk & 1) == 0) {
+            nm_store_values<DT, KEEP>(dst, chunk >> 1, block, false);
         }
+    } else if (cvalid) {
+        nm_store_values<DT, KEEP>(values + (i * d.n_chunks + chunk) * kValueBytes, chunk, vals, wide);
+    }
+    F8 enew;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        float lost = z.v[k] - dq.v[k];
+        if (EF == EF_OFF) lost = eold.v[k] + lost;
+        enew.v[k] = lost;
+    }
+    if (ET == F32) {                    // whole 128-byte lines per store, streaming
+        f32x4 pieces[2];
+        lines_exchange<64>(patch, lane, enew, pieces);
+        lines_store_stream<64>(static_cast<float *>(p.err) + i * C + (int64_t)run_chunk0 * kChunk, lane, run_valid, pieces);
+    } else if (cvalid) {
+        Raw8<ET> eo;
+        eo.narrow(enew);
+        eo.store_stream(p.err, e);
+    }
+    if (FUSED && cvalid) {
+        F8 nb;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) nb.v[k] = (EF == EF_NAIVE) ? dq.v[k] : b.v[k] + dq.v[k];
+        Raw8<DT> out;
+        out.narrow(nb);
+        if (DT == BF16) out.store_stream(p.recon, e); else out.store(p.recon, e);
     }
 }
 
@@ -765,12 +730,18 @@ hipError_t launch_fill_item_tensor(const uint32_t *item_prefix, uint32_t *item_t
     return hipGetLastError();
 }
 
-// Launches KERNEL<ARGS..., DTS> for the range's dtype selector.
+// Launches KERNEL<ARGS..., DTS> for the range's dtype selector, with `pad_lds` bytes of dynamic LDS (see kCapLdsBytes).
+// The row-local kernels need few registers, and left alone 16 of their workgroups would share a CU.  They run
+// faster with about 12 (measured on 42 x [16384, 3072] bf16, 4-bit group codes: 16 resident 3.71 ms, 12 3.53 ms,
+// 10 3.52 ms, 8 3.57 ms, 6 4.07 ms; the receiver's kernel 1.54 -> 1.49 ms): with more, too many streams of reads
+// and writes are open at once.  Dynamic LDS that nobody touches is what caps them: kCapLdsBytes per workgroup
+// in total, 12 of which fit the 160 KB of a CU.
+constexpr unsigned kCapLdsBytes = 13312;
 #define CF_LAUNCH_DTS(KERNEL, ...)                                                                      \
     do {                                                                                                \
-        if (r.dts == 0) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 0>), grid, block, 0, s, v, r);          \
-        else if (r.dts == 1) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 1>), grid, block, 0, s, v, r);     \
-        else hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 2>), grid, block, 0, s, v, r);                     \
+        if (r.dts == 0) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 0>), grid, block, pad_lds, s, v, r);            \
+        else if (r.dts == 1) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 1>), grid, block, pad_lds, s, v, r);       \
+        else hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 2>), grid, block, pad_lds, s, v, r);                       \
     } while (0)
 
 #define CF_LAUNCH_EF_ET(KERNEL, ...)                                                                    \
@@ -792,6 +763,7 @@ hipError_t launch_warmup(const BatchView &v, const LaunchRange &r, int err_dtype
 {
     dim3 grid(r.ew_hi - r.ew_lo), block(kTileThreads);
     if (grid.x == 0) return hipSuccess;
+    const unsigned pad_lds = 0;
     if (err_dtype == BF16) CF_LAUNCH_DTS(k_warmup, BF16);
     else CF_LAUNCH_DTS(k_warmup, F32);
     return hipGetLastError();
@@ -801,6 +773,7 @@ hipError_t launch_colreduce(const BatchView &v, const LaunchRange &r, int ef, in
 {
     dim3 grid(r.tile_hi - r.tile_lo), block(kTileThreads);
     if (grid.x == 0) return hipSuccess;
+    const unsigned pad_lds = 0;
     CF_LAUNCH_EF_ET(k_colreduce);
     return hipGetLastError();
 }
@@ -824,6 +797,7 @@ hipError_t launch_encode(const BatchView &v, const LaunchRange &r, int ef, int e
 {
     dim3 grid(r.ew_hi - r.ew_lo), block(kTileThreads);
     if (grid.x == 0) return hipSuccess;
+    const unsigned pad_lds = kCapLdsBytes - (unsigned)sizeof(float) * 512 * (kTileThreads / 64);       // the kernel's own patches count
     if (fused) CF_LAUNCH_EF_ET(k_encode, , true);
     else CF_LAUNCH_EF_ET(k_encode, , false);
     return hipGetLastError();
@@ -833,6 +807,7 @@ hipError_t launch_encode_nm(const BatchView &v, const LaunchRange &r, int ef, in
 {
     dim3 grid(r.ew_hi - r.ew_lo), block(kTileThreads);
     if (grid.x == 0) return hipSuccess;
+    const unsigned pad_lds = kCapLdsBytes - (unsigned)sizeof(float) * 512 * (kTileThreads / 64);
     if (pair) {
         if (fused) CF_LAUNCH_EF_ET(k_encode_nm, , true, true);
         else CF_LAUNCH_EF_ET(k_encode_nm, , false, true);
@@ -847,9 +822,9 @@ hipError_t launch_decode(const BatchView &v, const LaunchRange &r, hipStream_t s
 {
     dim3 grid(r.dec_hi - r.dec_lo), block(kTileThreads);
     if (grid.x == 0) return hipSuccess;
-    if (r.dts == 0) hipLaunchKernelGGL(k_decode<0>, grid, block, 0, s, v, r);
-    else if (r.dts == 1) hipLaunchKernelGGL(k_decode<1>, grid, block, 0, s, v, r);
-    else hipLaunchKernelGGL(k_decode<2>, grid, block, 0, s, v, r);
+    if (r.dts == 0) hipLaunchKernelGGL(k_decode<0>, grid, block, kCapLdsBytes, s, v, r);
+    else if (r.dts == 1) hipLaunchKernelGGL(k_decode<1>, grid, block, kCapLdsBytes, s, v, r);
+    else hipLaunchKernelGGL(k_decode<2>, grid, block, kCapLdsBytes, s, v, r);
     return hipGetLastError();
 }
 

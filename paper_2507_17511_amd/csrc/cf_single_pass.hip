@@ -321,8 +321,13 @@ __global__ __launch_bounds__(kPersistThreads, CF_SP_WAVES) void k_single_pass(Ba
         const TensorDev d = v.descs[t];                             // by value: scalar registers, never re-read
         const TensorPtrs p = v.ptrs[t];
         const uint32_t local = item - d.p_item_begin;               // group-major: stripe, then row block
+#ifdef CF_EXP_RBMAJOR
+        const int stripe = (int)(local % (uint32_t)d.p_n_stripes);
+        const int rb = (int)(local / (uint32_t)d.p_n_stripes);
+#else
         const int stripe = (int)(local / (uint32_t)d.p_n_rb);
         const int rb = (int)(local % (uint32_t)d.p_n_rb);
+#endif
         bool ok;
         if (d.dtype == BF16) {
             if (d.bits == 1) ok = persist_item<BF16, 1, ET, FUSED, SCH>(v, d, p, stripe, rb, sh);
