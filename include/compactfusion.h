@@ -155,20 +155,40 @@ typedef struct {
 } cf_options;
 
 /* A channel scale needs every token of a channel before any code of that
- * channel.  With CF_EF_RECON a single persistent kernel keeps x and recon in
- * registers across that reduction (each is read once; workgroups of one
- * 128-channel stripe wait for each other's partial sums, every wait bounded:
- * see cf_check_device).  It applies to CF_EF_RECON, CF_SCALE_CHANNEL tensors, no
- * CF_SCALE_RANK1 tensor in the context, N / 256 workgroups co-resident.
- * Otherwise one kernel reduces and a second one, which reads x and recon
- * again, writes the codes.  Results are bit-identical either way.  By default
- * a call takes the single pass where it applies, every channel-scale tensor
- * of the context has at least 256 tokens and the call covers at least 64 work
- * items of 256 rows x 128 channels (128 x 256 for contexts of short tensors; it is about 25 % faster on MI355X at the
- * sizes of the paper's models and slower on tiny batches);
- * CF_FLAG_SINGLE_PASS takes it whenever it applies, CF_FLAG_TWO_KERNEL never. */
+ * channel.  The single-pass kernel keeps the operands of a 256-row x 128-channel
+ * item in registers across that reduction, so that x, recon (and err, where it is
+ * an operand) are read once; the workgroups of one 128-channel stripe of a tensor
+ * publish their partial sums to each other through the workspace.  It covers every
+ * CF_SCALE_CHANNEL tensor of a context without CF_SCALE_RANK1 tensors, in every
+ * error-feedback mode.  Otherwise one kernel reduces and a second one, which
+ * reads the operands again, writes the codes.  Results are bit-identical either
+ * way.  By default a call takes the single pass where it applies, every
+ * channel-scale tensor of the context has at least 256 tokens and the call covers
+ * at least 64 items (it is about 30 % faster on MI355X at the sizes of the paper's
+ * models and slower on tiny batches); CF_FLAG_SINGLE_PASS takes it whenever it
+ * applies, CF_FLAG_TWO_KERNEL never.
+ *
+ * Waiting in the single pass.  A workgroup normally finds the partial sums of its
+ * stripe within microseconds, because the workgroups of a stripe are launched
+ * next to each other.  It does not depend on that: a workgroup that has waited
+ * for a partial sum for some milliseconds gives its item up (it has written
+ * nothing but its own partial sum by then), and a second launch of the same
+ * kernel, which is part of every call and normally finds nothing to do, does the
+ * given-up items once all partial sums are there.  So the call finishes, with the
+ * same bits, whatever else runs on the device and in whatever order workgroups
+ * are started; it needs no co-residency and no cooperative launch.
+ * cf_given_up_items tells how many items of the last call went that way.
+ * CF_FLAG_FIXED_GRID launches as many workgroups as fit the device at once and
+ * lets them loop over the items, for callers who want the codec to hold a fixed
+ * number of workgroup slots next to other kernels (about 4 % slower when it has
+ * the device to itself). */
 #define CF_FLAG_SINGLE_PASS 0x1u
 #define CF_FLAG_TWO_KERNEL 0x2u
+#define CF_FLAG_FIXED_GRID 0x8u
+/* TESTING ONLY: workgroups of the single pass do not wait at all: an item whose stripe's partial
+ * sums are not all there at the first look is given up and done by the second launch.  Slow;
+ * results unchanged. */
+#define CF_FLAG_TEST_NO_WAIT 0x100u
 /* CF_LOWRANK tensors of the context send their factors as 4-bit integers (Sec. 3.4 and App. D name INT4
  * factors without a format; this one is the library's): every factor row of 32 entries has one fp32 scale
  * s = absmax / 7 and travels as nibbles q = clamp(round-half-even(f / s), -7, 7), two's complement, entry k
@@ -249,12 +269,16 @@ const char *cf_status_string(cf_status s);
 /* The hipError_t value of the last failed HIP call in this context (0 if none). */
 int32_t cf_last_hip_error(const cf_ctx *ctx);
 
-/* Synchronises `stream` and reports whether any kernel of this context gave up
- * on a bounded wait (the single-pass kernel's workgroups wait for each other;
- * a wait that expires raises a flag in the workspace instead of hanging).
- * CF_OK, or CF_ERR_DEVICE with cf_last_hip_error() == 0 for that flag; after
- * it the outputs of that call are undefined and the context should be rebuilt. */
+/* Synchronises `stream`; CF_ERR_DEVICE with cf_last_hip_error() != 0 if that fails (a kernel
+ * enqueued before it faulted), CF_ERR_DEVICE with cf_last_hip_error() == 0 if the library's own
+ * consistency check on the device tripped (the second launch of a single pass found a partial sum
+ * missing, which the design rules out); the context is then unusable. */
 cf_status cf_check_device(cf_ctx *ctx, void *stream);
+
+/* Synchronises `stream` and reports in *count how many items of the LAST single pass were given
+ * up by their first workgroup and done by the second launch (see "Waiting in the single pass";
+ * 0 in ordinary operation). */
+cf_status cf_given_up_items(cf_ctx *ctx, void *stream, uint32_t *count);
 
 /* Instrumentation for benchmarks (no part of the method).  With `events` set
  * (a host array of 2*n_pairs hipEvent_t created by the caller), the NEXT

@@ -90,6 +90,8 @@ def lib() -> ctypes.CDLL:
         L.cfo_bf16_to_f32.argtypes = [ctypes.c_uint16]
         L.cfo_f32_to_bf16.restype = ctypes.c_uint16
         L.cfo_f32_to_bf16.argtypes = [ctypes.c_float]
+        L.cfo_f32_to_bf16_array.restype = None
+        L.cfo_f32_to_bf16_array.argtypes = [vp, vp, ctypes.c_int64]
         L.cfo_treesum.restype = ctypes.c_float
         L.cfo_treesum.argtypes = [vp, ctypes.c_int64, ctypes.c_int64]
         L.cfo_codes_bytes.restype = ctypes.c_int64
@@ -134,7 +136,9 @@ def f32_to_bf16(f: np.ndarray) -> np.ndarray:
     """Element-wise through the oracle's own round-to-nearest-even narrowing."""
     L = lib()
     flat = np.ascontiguousarray(f, dtype=np.float32).ravel()
-    return np.array([L.cfo_f32_to_bf16(float(v)) for v in flat], dtype=np.uint16).reshape(np.shape(f))
+    out = np.empty(flat.shape, dtype=np.uint16)
+    L.cfo_f32_to_bf16_array(_p(flat), _p(out), flat.size)
+    return out.reshape(np.shape(f))
 
 
 def treesum(v: np.ndarray) -> np.float32:

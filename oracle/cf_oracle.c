@@ -37,6 +37,12 @@ uint16_t cfo_f32_to_bf16(float f)
     return (uint16_t)(u >> 16);
 }
 
+/* The same narrowing over an array (one call instead of one per element from Python). */
+void cfo_f32_to_bf16_array(const float *src, uint16_t *dst, int64_t n)
+{
+    for (int64_t k = 0; k < n; ++k) dst[k] = cfo_f32_to_bf16(src[k]);
+}
+
 static float load_elem(const void *p, int dtype, int64_t k)
 {
     if (dtype == CFO_BF16)

@@ -47,6 +47,7 @@ typedef struct {
 /* Element conversions (bf16 <-> fp32), exported so tests can pin them. */
 float    cfo_bf16_to_f32(uint16_t h);
 uint16_t cfo_f32_to_bf16(float f);
+void     cfo_f32_to_bf16_array(const float *src, uint16_t *dst, int64_t n);
 
 /* Balanced binary-tree sum of v[0], v[stride], ..., v[(n-1)*stride]. */
 float cfo_treesum(const float *v, int64_t n, int64_t stride);

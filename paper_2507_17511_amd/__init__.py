@@ -28,11 +28,13 @@ CF_EF_RECON, CF_EF_LITERAL, CF_EF_OFF, CF_EF_NAIVE = 0, 1, 2, 3
 CF_FLAG_SINGLE_PASS = 0x1
 CF_FLAG_TWO_KERNEL = 0x2
 CF_FLAG_LOWRANK_INT4 = 0x4
+CF_FLAG_FIXED_GRID = 0x8
+CF_FLAG_TEST_NO_WAIT = 0x100
 
 EXPORTS = ["cf_sizes", "cf_workspace_bytes", "cf_init", "cf_warmup", "cf_set_warm", "cf_compress",
            "cf_decompress", "cf_step_fused", "cf_destroy", "cf_status_string", "cf_last_hip_error",
            "cf_profile_next_call", "cf_profile_launch_count", "cf_profile_kernel_name", "cf_check_device",
-           "cf_step_fused_static"]
+           "cf_step_fused_static", "cf_given_up_items"]
 
 
 class cf_tensor_desc(ctypes.Structure):
@@ -98,6 +100,8 @@ def lib() -> ctypes.CDLL:
         L.cf_profile_launch_count.argtypes = [vp]
         L.cf_profile_kernel_name.restype = ctypes.c_char_p
         L.cf_profile_kernel_name.argtypes = [vp, i32]
+        L.cf_given_up_items.restype = i32
+        L.cf_given_up_items.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint32)]
         L.cf_step_fused_static.restype = i32
         L.cf_step_fused_static.argtypes = [dp, i32, op, pp, pp, pp, pp, pp, vp]
         _lib = L
@@ -237,5 +241,12 @@ def cf_profile_kernel_name(ctx, k: int) -> Optional[str]:
 
 
 def cf_check_device(ctx, stream=None) -> None:
-    """Synchronises the stream; raises if a kernel of this context gave up on a bounded wait."""
+    """Synchronises the stream; raises if that fails or the device-side consistency check tripped."""
     _check(lib().cf_check_device(ctx, _addr(stream)), "cf_check_device", ctx)
+
+
+def cf_given_up_items(ctx, stream=None) -> int:
+    """Synchronises the stream; -> items of the last single pass that were given up and done by the second launch."""
+    n = ctypes.c_uint32()
+    _check(lib().cf_given_up_items(ctx, _addr(stream), ctypes.byref(n)), "cf_given_up_items", ctx)
+    return int(n.value)

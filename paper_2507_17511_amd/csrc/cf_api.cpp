@@ -20,7 +20,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
     size_t off_descs = 0, off_ptrs = 0, off_tile_prefix = 0, off_fin_prefix = 0, off_partials = 0;
-    size_t off_item_prefix = 0, off_item_tensor = 0, off_error = 0, off_p_partials = 0;
+    size_t off_item_prefix = 0, off_item_tensor = 0, off_gave_up = 0, off_error = 0, off_p_partials = 0;
     std::vector<uint32_t> item_prefix;
     size_t n_items = 0;
     int32_t max_group_items = 0;   // largest reduction group of the single-pass path
@@ -44,7 +44,8 @@ cf_status check_opts(const cf_options *o, cf_options &out)
     if (!o) return CF_OK;
     if (o->ef != CF_EF_RECON && o->ef != CF_EF_LITERAL && o->ef != CF_EF_OFF && o->ef != CF_EF_NAIVE) return CF_ERR_UNSUPPORTED;
     if (o->err_dtype != CF_F32 && o->err_dtype != CF_BF16) return CF_ERR_UNSUPPORTED;
-    if (o->flags & ~(CF_FLAG_SINGLE_PASS | CF_FLAG_TWO_KERNEL | CF_FLAG_LOWRANK_INT4)) return CF_ERR_UNSUPPORTED;
+    if (o->flags & ~(CF_FLAG_SINGLE_PASS | CF_FLAG_TWO_KERNEL | CF_FLAG_LOWRANK_INT4 | CF_FLAG_FIXED_GRID | CF_FLAG_TEST_NO_WAIT))
+        return CF_ERR_UNSUPPORTED;
     if (o->tile_rows != 0 && o->tile_rows != 8 && o->tile_rows != 16 && o->tile_rows != 32 && o->tile_rows != 64)
         return CF_ERR_UNSUPPORTED;
     if (o->encode_rows < 0 || o->encode_rows > 64) return CF_ERR_UNSUPPORTED;
@@ -152,15 +153,15 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     uint64_t tiles = 0, fins = 0, items = 0;
     size_t partial_bytes = 0, p_partial_bytes = 0;
     L.item_prefix.assign(n + 1, 0);
-    L.single_pass = o.ef == CF_EF_RECON && (o.flags & CF_FLAG_TWO_KERNEL) == 0;
+    L.single_pass = (o.flags & CF_FLAG_TWO_KERNEL) == 0;
     for (int32_t t = 0; t < n; ++t)
         if (descs[t].scale == CF_SCALE_RANK1) L.single_pass = false;   // the single-pass kernel knows channel scales only
-    // Single-pass item shape: 256 lanes x 16 (bf16) or 8 (fp32) rows per lane cover kStripeChannels channels by
+    // Single-pass item shape: 256 lanes, each with single_pass_rows_per_lane rows, cover kStripeChannels channels by
     // default; when even the tallest channel-scale tensor would make at most 12 items per group that way (bf16:
     // N <= 3072), items half as tall and twice as wide measure faster (57 x [1024, 3072] bf16: 0.417 -> 0.382 ms;
     // sweep over [N, 3072]: equal or up to 12 % faster through N = 3072, 2 % slower at N = 4096 with 1-bit codes,
     // clearly slower from N = 8192 on, where groups get long).
-    auto narrow_item_rows = [](int32_t dtype) { return (kPersistThreads / (kStripeChannels / kChunk)) * (dtype == CF_BF16 ? CF_SP_RPT : CF_SP_RPT / 2); };
+    auto narrow_item_rows = [&](int32_t dtype) { return (kPersistThreads / (kStripeChannels / kChunk)) * single_pass_rows_per_lane(dtype, o.ef); };
     // Up to 16 items per group (N = 4096) the wide stripe still pays for 2- and 4-bit codes, whose code rows
     // then are whole 64- and 128-byte pieces (4-bit: 7 % faster), but not for 1-bit codes (2 % slower).
     int64_t narrow_max_group = 0;
@@ -261,7 +262,8 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
     L.off_item_prefix = off;  off = align_up(off + sizeof(uint32_t) * (size_t)(n + 1));
     L.off_item_tensor = off;  off = align_up(off + sizeof(uint32_t) * (size_t)items);
     L.n_items = (size_t)items;
-    L.off_error = off;        off = align_up(off + sizeof(uint32_t));
+    L.off_gave_up = off;      off = align_up(off + sizeof(uint32_t) * (size_t)items);
+    L.off_error = off;        off = align_up(off + sizeof(uint32_t) * 64);      // error word, and the give-up counter 128 bytes on
     L.off_p_partials = off;   off = align_up(off + p_partial_bytes);
     L.total = off;
     for (int32_t t = 0; t < n; ++t) {
@@ -315,6 +317,7 @@ struct cf_ctx {
         v.item_prefix = reinterpret_cast<const uint32_t *>(ws + L.off_item_prefix);
         v.item_tensor = reinterpret_cast<const uint32_t *>(ws + L.off_item_tensor);
         v.error_flag = reinterpret_cast<uint32_t *>(ws + L.off_error);
+        v.gave_up_items = reinterpret_cast<uint32_t *>(ws + L.off_gave_up);
         v.workspace = ws;
         v.n_tensors = (int32_t)descs.size();
         return v;
@@ -334,6 +337,8 @@ struct cf_ctx {
         r.fin_lo = L.fin_prefix[first];
         r.fin_hi = L.fin_prefix[first + count];
         r.sp_xcd_major = 0;
+        r.sp_wait_polls = kWaitPolls;
+        r.sp_redo = 0;
         r.item_lo = L.item_prefix[first];
         r.item_hi = L.item_prefix[first + count];
         r.only_group_scale = 0;
@@ -487,14 +492,14 @@ cf_status make_ctx(cf_ctx **out, const cf_tensor_desc *descs, int32_t n_tensors,
         e = launch_fill_item_tensor(reinterpret_cast<const uint32_t *>(ctx->ws + L.off_item_prefix),
                                     reinterpret_cast<uint32_t *>(ctx->ws + L.off_item_tensor), n_tensors, s);
     if (e == hipSuccess) e = launch_fill_words(ctx->ws + L.off_ptrs, 0u, sizeof(TensorPtrs) * (size_t)n_tensors / 4, s);
-    if (e == hipSuccess) e = launch_fill_words(ctx->ws + L.off_error, 0u, 1, s);
+    if (e == hipSuccess) e = launch_fill_words(ctx->ws + L.off_error, 0u, 64, s);
     if (e == hipSuccess && L.single_pass && L.max_group_items > 0) {
         int n_cu = 0;
         e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, ctx->device);
         if (e == hipSuccess)
             for (int et = 0; et < 2; ++et)
                 for (int fu = 0; fu < 2; ++fu)
-                    ctx->persist_grid[et][fu] = persistent_max_blocks_per_cu(et, fu != 0, L.sp_wide) * n_cu;
+                    ctx->persist_grid[et][fu] = persistent_max_blocks_per_cu(o.ef, et, fu != 0, L.sp_wide) * n_cu;
     }
     if (e != hipSuccess) {
         (void)hipGetLastError();
@@ -655,15 +660,21 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
     // (an item is 128 or 256 rows tall: most of its lanes would idle)
     const bool forced = (ctx->opts.flags & CF_FLAG_SINGLE_PASS) != 0;
     const bool worth_it = forced || (r.item_hi - r.item_lo >= 64u && ctx->L.min_channel_scale_tokens >= 256);
-    if (ctx->L.single_pass && grid >= ctx->L.max_group_items && r.item_hi > r.item_lo && worth_it) {
-        // channel-scale tensors: one pass, x and recon stay in registers across the scale reduction
+    // (a group larger than what the device holds at once would have its first workgroups wait for ones that cannot
+    // start before they leave: correct, they give up and the redo launch does them, but slow: such tensors take two kernels)
+    if (ctx->L.single_pass && grid >= ctx->L.max_group_items && grid >= 1 && r.item_hi > r.item_lo && worth_it) {
+        // channel-scale tensors: one pass, the operands stay in registers across the scale reduction
         e = launch(ctx, s, "k_reset_partials", [&] { return launch_reset_partials(v, r, s); });
         if (e != hipSuccess) return device_fail(ctx, e);
         // measured on [N, 3072] bf16 batches: up to 4 row blocks per tensor a run of consecutive items per XCD is
         // 4-20 % faster (the stripes of a code row meet in one L2), from 6 on dealing them round the XCDs is 8-15 % faster
         r.sp_xcd_major = ctx->L.max_group_items <= 4;
-        const bool one_shot = ctx->L.max_group_items * 8 <= grid;       // an XCD's share of the resident workgroups holds a whole group
-        e = launch(ctx, s, "k_single_pass", [&] { return launch_single_pass(v, r, et, fused, ctx->L.sp_wide, grid, one_shot, s); });
+        r.sp_wait_polls = (ctx->opts.flags & CF_FLAG_TEST_NO_WAIT) ? 0u : kWaitPolls;
+        const bool one_shot = (ctx->opts.flags & CF_FLAG_FIXED_GRID) == 0;
+        e = launch(ctx, s, "k_single_pass", [&] { return launch_single_pass(v, r, ef, et, fused, ctx->L.sp_wide, grid, one_shot, false, s); });
+        if (e != hipSuccess) return device_fail(ctx, e);
+        // the items whose workgroup gave up waiting (normally none: the launch is empty)
+        e = launch(ctx, s, "k_single_pass_redo", [&] { return launch_single_pass(v, r, ef, et, fused, ctx->L.sp_wide, grid, one_shot, true, s); });
         if (e != hipSuccess) return device_fail(ctx, e);
         r.only_group_scale = 1;
         if ((e = run_row_local(ctx, first, count, v, r, fused, false, s)) != hipSuccess) return device_fail(ctx, e);
@@ -757,8 +768,7 @@ cf_status cf_profile_next_call(cf_ctx *ctx, void *const *events, int32_t n_pairs
 cf_status cf_check_device(cf_ctx *ctx, void *stream)
 {
     if (!ctx) return CF_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = hipStreamSynchronize(s);
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
     uint32_t flag = 0;
     if (e == hipSuccess) e = hipMemcpy(&flag, ctx->ws + ctx->L.off_error, sizeof flag, hipMemcpyDeviceToHost);
     if (e != hipSuccess) return device_fail(ctx, e);
@@ -766,6 +776,18 @@ cf_status cf_check_device(cf_ctx *ctx, void *stream)
         ctx->last_hip = 0;
         return CF_ERR_DEVICE;
     }
+    return CF_OK;
+}
+
+cf_status cf_given_up_items(cf_ctx *ctx, void *stream, uint32_t *count)
+{
+    if (!ctx || !count) return CF_ERR_INVALID_ARG;
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+    uint32_t n = 0;
+    if (e == hipSuccess)
+        e = hipMemcpy(&n, ctx->ws + ctx->L.off_error + sizeof(uint32_t) * kGaveUpWord, sizeof n, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return device_fail(ctx, e);
+    *count = n;
     return CF_OK;
 }
 

@@ -5,17 +5,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-// Shape of the single-pass kernel, overridable on the compiler's command line for measurements: rows of
-// bf16 a lane keeps in registers (fp32: half as many; 32, 16, 8 or 4) and waves per SIMD it is compiled for.
-// Measured on 114 x [4096, 3072] bf16 (64-channel stripes): 16 rows at 2 waves 3.28 ms, 8 rows at 3 waves
-// 3.75 ms, 8 rows at 4 waves 4.78 ms (spills), 4 rows at 4 waves 3.89 ms.
-#ifndef CF_SP_RPT
-#define CF_SP_RPT 16
-#endif
-#ifndef CF_SP_WAVES
-#define CF_SP_WAVES 2
-#endif
-
 namespace cf {
 
 // Every tile of the tiled kernels is TILE_ROWS(rb) x TILE_CHANNELS: 128 lanes
@@ -38,12 +27,17 @@ constexpr int kMaxUploadTensors = 64;                       // pointer sets per 
 // context whose tallest channel-scale tensor makes at most 12 items per group
 // with the narrow stripe (bf16: N <= 3072) takes the wide one.
 constexpr int kPersistThreads = 256;
-#ifndef CF_STRIPE_CHANNELS
-#define CF_STRIPE_CHANNELS 128
-#endif
-constexpr int kStripeChannels = CF_STRIPE_CHANNELS;
+constexpr int kStripeChannels = 128;
 constexpr int kStripeChannelsWide = 2 * kStripeChannels;    // 256
-constexpr uint32_t kSpinLimit = 1u << 20;                   // bounded wait (about seconds), then the error flag
+// Rows a lane of the single-pass kernel keeps in registers: 128 VGPRs of raw operands, i.e. 16 rows of bf16 x and
+// recon, half as many of fp32, half as many again when the error buffer is an operand too (CF_EF_LITERAL = 1,
+// CF_EF_OFF = 2).  Measured on 114 x [4096, 3072] bf16 (two waves per SIMD): 16 rows 2.65 ms; 8 rows at three
+// waves per SIMD 2.97 ms, at four (spills) 4.8 ms.  dtype: cf_dtype (CF_F32 = 0).
+constexpr int single_pass_rows_per_lane(int dtype, int ef) { return 16 / (dtype == 0 ? 2 : 1) / ((ef == 1 || ef == 2) ? 2 : 1); }
+// A workgroup polls a missing partial this many times (a microsecond or two each) before it gives its item up.
+constexpr uint32_t kWaitPolls = 4096;
+constexpr int kGaveUpWord = 32;                             // 128 bytes behind the error word: how many items the call's first launch gave up
+constexpr int kRedoGrid = 512;                              // workgroups of the launch that does them
 
 // Static description of one tensor; built at cf_init, lives in the workspace.
 struct alignas(16) TensorDev {
@@ -59,9 +53,9 @@ struct alignas(16) TensorDev {
     uint32_t tile_begin;    // id of this tensor's first tile in the batched grids
     uint32_t fin_begin;     // id of its first finalise block
     uint64_t partial_off;   // byte offset in the workspace of partial[n_rowblocks][C] (channel scales)
-    // single-pass path (channel scales, CF_EF_RECON): items of p_rows x kStripeChannels
+    // single-pass path (channel scales): items of p_rows x kStripeChannels (or kStripeChannelsWide)
     uint64_t p_partial_off; // byte offset of partial[p_n_rb][C]
-    int32_t p_rows;         // rows per item (256 for bf16, 128 for fp32; half of that with the wide stripe); 0 = tensor not on this path
+    int32_t p_rows;         // rows per item (row-lanes x single_pass_rows_per_lane); 0 = tensor not on this path
     int32_t p_n_rb;         // ceil(N / p_rows): items per reduction group
     int32_t p_n_stripes;    // ceil(C / stripe width of the context): reduction groups of this tensor
     uint32_t p_item_begin;  // id of this tensor's first item
@@ -114,7 +108,8 @@ struct BatchView {
     const uint32_t *fin_prefix;     // [n_tensors + 1]
     const uint32_t *item_prefix;    // [n_tensors + 1] items of the single-pass path
     const uint32_t *item_tensor;    // [n_items] tensor of every item: one load where a search over the prefix would be seven
-    uint32_t *error_flag;           // set when a bounded wait expired
+    uint32_t *error_flag;           // set if the redo launch finds a partial missing (cannot happen); kGaveUpWord words on: the give-up counter
+    uint32_t *gave_up_items;        // [n_items] the items the first launch of a call gave up
     uint8_t *workspace;
     int32_t n_tensors;
 };
@@ -127,6 +122,8 @@ struct LaunchRange {
     uint32_t fin_lo, fin_hi;    // finalise blocks
     uint32_t item_lo, item_hi;  // single-pass items
     uint32_t sp_xcd_major;      // single-pass kernel: deal the items XCD-major (a run of consecutive items per XCD)
+    uint32_t sp_wait_polls;     // single-pass kernel: polls of a missing partial before the workgroup gives its item up
+    uint32_t sp_redo;           // single-pass kernel: this is the launch over the given-up items
     uint64_t p_partial_lo, p_partial_hi;    // workspace bytes holding the single-pass partials of the range
     int32_t dts;                // storage dtype of every tensor in the range (cf_dtype), or 2 if mixed
     int32_t only_group_scale;   // tiled encode: skip tensors the single-pass kernel covers
@@ -167,11 +164,12 @@ hipError_t launch_lr_quant_u(const BatchView &v, const LaunchRange &r, hipStream
 hipError_t launch_lr_encode(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, hipStream_t s);
 hipError_t launch_lr_decode(const BatchView &v, const LaunchRange &r, hipStream_t s);
 
-// Single-pass kernel (channel scales, CF_EF_RECON).  `grid` workgroups must be co-resident.
-int persistent_max_blocks_per_cu(int err_dtype, bool fused, bool wide);
-// wide: items of kStripeChannelsWide channels (the layout's choice, fixed at cf_init)
-hipError_t launch_single_pass(const BatchView &v, const LaunchRange &r, int err_dtype, bool fused, bool wide, int grid,
-                             bool one_shot, hipStream_t s);
+// Single-pass kernel (channel scales, every error-feedback mode).
+int persistent_max_blocks_per_cu(int ef, int err_dtype, bool fused, bool wide);
+// wide: items of kStripeChannelsWide channels (the layout's choice, fixed at cf_init); one_shot: a workgroup per
+// item, else `grid` workgroups that loop over the items
+hipError_t launch_single_pass(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, bool fused, bool wide, int grid,
+                             bool one_shot, bool redo, hipStream_t s);
 hipError_t launch_reset_partials(const BatchView &v, const LaunchRange &r, hipStream_t s);
 
 }  // namespace cf

@@ -136,15 +136,105 @@ def test_single_pass_stripe_width_rule_boundaries():
             run_parity(descs, cf.options(flags=cf.CF_FLAG_SINGLE_PASS), xs, mode=mode)
 
 
-def test_single_pass_looping_grid():
-    """Groups of 157 items (N = 40000) are too large for one workgroup per item to be safe, so the
-    single-pass kernel runs as a co-resident grid that loops over the items (cooperative launch)."""
-    say("single pass, looping grid")
+def test_single_pass_long_groups_and_fixed_grid():
+    """Groups of 157 items (N = 40000), as one workgroup per item and as a fixed grid of workgroups that loop
+    over the items (CF_FLAG_FIXED_GRID)."""
+    say("single pass, long groups")
     descs = [cf.desc(40000, 72, cf.CF_BF16, (1, 2, 4)[t % 3], CH) for t in range(6)]
     streams = [drift_stream((d.n_tokens, d.n_channels), d.dtype, steps=3, seed=170 + k, device=DEV)
                for k, d in enumerate(descs)]
     xs = [[streams[t][s] for t in range(len(descs))] for s in range(3)]
     run_parity(descs, cf.options(flags=cf.CF_FLAG_SINGLE_PASS), xs, mode="fused")
+    run_parity(descs, cf.options(flags=cf.CF_FLAG_SINGLE_PASS | cf.CF_FLAG_FIXED_GRID), xs, mode="fused")
+
+
+@pytest.mark.parametrize("ef", [cf.CF_EF_RECON, cf.CF_EF_LITERAL, cf.CF_EF_OFF, cf.CF_EF_NAIVE])
+@pytest.mark.parametrize("err_dtype", [cf.CF_F32, cf.CF_BF16])
+def test_single_pass_every_feedback_mode(ef, err_dtype):
+    """The single-pass kernel in every error-feedback mode (items are 256 rows of bf16 without the error buffer as an
+    operand, 128 with it, half of that for fp32), ragged in both directions, several row blocks and stripes deep,
+    fused and split, also as a fixed grid."""
+    descs = [cf.desc(1500, 1096, cf.CF_BF16, (1, 2, 4)[t % 3], CH) for t in range(3)]
+    descs += [cf.desc(700, 520, cf.CF_F32, (2, 4, 1)[t % 3], CH) for t in range(3)]
+    descs += [cf.desc(130, 72, cf.CF_BF16, 2, CH), cf.desc(1, 8, cf.CF_F32, 1, CH)]
+    streams = [drift_stream((d.n_tokens, d.n_channels), d.dtype, steps=4, seed=370 + 10 * ef + k, device=DEV)
+               for k, d in enumerate(descs)]
+    xs = [[streams[t][s] for t in range(len(descs))] for s in range(4)]
+    for mode in ("fused", "split"):
+        if ef == cf.CF_EF_NAIVE and mode == "split":
+            continue            # naive compression has no separate receiver step in the oracle harness
+        say(f"single pass ef={ef} err_dtype={err_dtype} mode={mode}")
+        run_parity(descs, cf.options(ef=ef, err_dtype=err_dtype, flags=cf.CF_FLAG_SINGLE_PASS), xs, mode=mode)
+    run_parity(descs, cf.options(ef=ef, err_dtype=err_dtype, flags=cf.CF_FLAG_SINGLE_PASS | cf.CF_FLAG_FIXED_GRID), xs, mode="fused")
+
+
+@pytest.mark.parametrize("ef", [cf.CF_EF_RECON, cf.CF_EF_OFF])
+def test_single_pass_gives_up_and_redoes(ef):
+    """CF_FLAG_TEST_NO_WAIT: a workgroup that does not find every partial sum of its stripe at its first look gives
+    its item up, and the second launch of the call does it.  Same bits as ever, and the give-up path did run."""
+    descs = [cf.desc(1500, 1096, cf.CF_BF16, (1, 2, 4)[t % 3], CH) for t in range(4)]
+    descs += [cf.desc(700, 520, cf.CF_F32, (2, 4, 1)[t % 3], CH) for t in range(2)]
+    streams = [drift_stream((d.n_tokens, d.n_channels), d.dtype, steps=3, seed=470 + 10 * ef + k, device=DEV)
+               for k, d in enumerate(descs)]
+    xs = [[streams[t][s] for t in range(len(descs))] for s in range(3)]
+    for extra in (0, cf.CF_FLAG_FIXED_GRID):
+        say(f"single pass without waiting, ef={ef}, flags +{extra}")
+        sess, _ = run_parity(descs, cf.options(ef=ef, flags=cf.CF_FLAG_SINGLE_PASS | cf.CF_FLAG_TEST_NO_WAIT | extra), xs, mode="fused")
+    # the counter of the last call, on a session that is still open
+    sess = CodecSession(descs, cf.options(ef=ef, flags=cf.CF_FLAG_SINGLE_PASS | cf.CF_FLAG_TEST_NO_WAIT), device=DEV)
+    quiet = CodecSession(descs, cf.options(ef=ef, flags=cf.CF_FLAG_SINGLE_PASS), device=DEV)
+    try:
+        for c in (sess, quiet):
+            c.warmup(xs[0])
+            c.step_fused(xs[1])
+        n_gave_up = cf.cf_given_up_items(sess.ctx, sess.stream_handle)
+        say(f"   {n_gave_up} items were given up and redone; {cf.cf_given_up_items(quiet.ctx, quiet.stream_handle)} in the ordinary run")
+        assert n_gave_up > 0, "the give-up path was not exercised"
+        assert cf.cf_given_up_items(quiet.ctx, quiet.stream_handle) == 0
+        for t in range(len(descs)):
+            assert torch.equal(sess.recon[t], quiet.recon[t]) and torch.equal(sess.codes[t], quiet.codes[t])
+    finally:
+        sess.close()
+        quiet.close()
+
+
+def test_single_pass_next_to_other_work_on_the_device():
+    """cf_step_fused on one stream while a second stream of the same priority keeps the device busy with unrelated
+    kernels: the outputs are the bits of a quiet run, and the oracle's."""
+    descs = [cf.desc(4096, 3072, cf.CF_BF16, (1, 2, 4)[t % 3], CH) for t in range(6)]
+    streams = [drift_stream((4096, 3072), cf.CF_BF16, steps=3, seed=570 + k, sigma=0.02, device=DEV) for k in range(len(descs))]
+    xs = [[streams[t][s] for t in range(len(descs))] for s in range(3)]
+    busy, quiet = CodecSession(descs, cf.options(), device=DEV), CodecSession(descs, cf.options(), device=DEV)
+    other = torch.cuda.Stream(device=DEV)           # default priority, like the codec's
+    a = torch.randn(4096, 4096, device=DEV)
+    try:
+        for c in (busy, quiet):
+            c.warmup(xs[0])
+        torch.cuda.synchronize()
+        for s in (1, 2):
+            quiet.step_fused(xs[s])
+            torch.cuda.synchronize()
+            with torch.cuda.stream(other):          # matrix products and element-wise kernels, queued ahead and behind
+                for _ in range(40):
+                    b = a @ a
+                    a = torch.tanh(b * 1e-3)
+            busy.step_fused(xs[s])
+            with torch.cuda.stream(other):
+                for _ in range(40):
+                    b = a @ a
+                    a = torch.tanh(b * 1e-3)
+            cf.cf_check_device(busy.ctx, busy.stream_handle)
+            torch.cuda.synchronize()
+            say(f"step {s} next to a busy stream: {cf.cf_given_up_items(busy.ctx, busy.stream_handle)} items given up and redone")
+            for t in range(len(descs)):
+                assert torch.equal(busy.recon[t], quiet.recon[t]), f"recon[{t}] differs from the quiet run at step {s}"
+                assert torch.equal(busy.err[t], quiet.err[t]) and torch.equal(busy.codes[t], quiet.codes[t])
+                assert torch.equal(busy.scales[t], quiet.scales[t])
+    finally:
+        busy.close()
+        quiet.close()
+    # and the oracle, on the same inputs (one tensor of each width)
+    run_parity(descs[:3], cf.options(), [x[:3] for x in xs], mode="fused")
 
 
 @pytest.mark.parametrize("case", [0, 1, 2, 3])
