@@ -128,7 +128,7 @@ def test_lowrank_int4_factor_sizes():
     assert cf.cf_sizes(d, o)[0] == (4096 + 3072) * 20              # 16 nibble bytes and one fp32 scale per factor row
     assert cf.cf_sizes(d)[0] == (4096 + 3072) * 64
     with pytest.raises(cf.CFError) as ei:
-        cf.cf_sizes(d, cf.options(flags=0x8))
+        cf.cf_sizes(d, cf.options(flags=0x40))                           # not a flag
     assert ei.value.status == cf.CF_ERR_UNSUPPORTED
 
 
