@@ -108,8 +108,10 @@ def bytes_per_element(wl, bits: int, ef: int) -> float:
     err_bytes = ERR_BYTES
     sx = 4 if wl.dtype == "f32" else 2
     b = sx + sx + sx + err_bytes + code_bytes_per_element(wl, bits)     # x, recon read, recon write, err write, codes
-    if ef != 0:
+    if ef in (1, 2):
         b += err_bytes                                  # LITERAL / OFF also read err
+    if ef == 3:
+        b -= sx                                         # naive compression never reads recon
     b += scale_bytes_per_element(wl)
     return b
 
@@ -296,9 +298,11 @@ def kernel_algorithmic_bytes(nm: str, wl, ef: int, split: bool = False) -> float
         bits = wl.bits_of(t)
         scale_b = scale_bytes_per_element(wl)
         if nm == "k_colreduce":
-            per = 2 * sx + (ERR_BYTES if ef else 0)
+            per = (1 if ef == 3 else 2) * sx + (ERR_BYTES if ef in (1, 2) else 0)
         elif nm in ("k_encode", "k_encode_nm"):     # reads x, recon (+err); writes codes, err, recon
-            per = (2 if split else 3) * sx + ERR_BYTES + code_bytes_per_element(wl, bits) + (ERR_BYTES if ef else 0) + scale_b
+            per = (2 if split else 3) * sx + ERR_BYTES + code_bytes_per_element(wl, bits) + (ERR_BYTES if ef in (1, 2) else 0) + scale_b
+            if ef == 3:
+                per -= sx
         elif nm in ("k_lr_project", "k_lr_backproject"):     # re-form A from x and recon
             per = 2 * sx
         elif nm == "k_lr_apply":                            # reads x, recon and the factors; writes err, recon

@@ -180,7 +180,7 @@ typedef struct {
  * cf_given_up_items tells how many items of the last call went that way.
  * CF_FLAG_FIXED_GRID launches as many workgroups as fit the device at once and
  * lets them loop over the items, for callers who want the codec to hold a fixed
- * number of workgroup slots next to other kernels (about 4 % slower when it has
+ * number of workgroup slots next to other kernels (about 15 % slower when it has
  * the device to itself). */
 #define CF_FLAG_SINGLE_PASS 0x1u
 #define CF_FLAG_TWO_KERNEL 0x2u

@@ -368,7 +368,7 @@ hipError_t launch_reset_partials(const BatchView &v, const LaunchRange &r, hipSt
 // one_shot: one workgroup per item instead of a smaller grid whose workgroups loop over the items.
 // A workgroup that loops has to drain its stores before its next loads count as returned (the loads and
 // stores of a wave share one in-order counter); one that exits leaves the draining to the memory system
-// while the next workgroup already loads: measured faster by 4 %.  Neither form needs co-residency to
+// while the next workgroup already loads: measured faster by 15 % (114 x [4096, 3072] bf16: 2.65 against 3.04 ms).  Neither form needs co-residency to
 // finish (see the top of the file); the looping grid is for callers who share the device with other work
 // and want the codec to hold a fixed number of workgroup slots.  redo: the second launch of a call, over
 // the items the first one gave up (kRedoGrid workgroups; all of them leave at once when the list is empty).
