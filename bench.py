@@ -220,8 +220,12 @@ def run_workload(name: str, args, events: HipEvents | None):
 
     sess.warmup(x0)
     k = 0
-    for _ in range(args.warmup):
+    verified = None
+    for w in range(args.warmup):
         step(k); k += 1
+        if w == 0 and not args.no_cpu_baseline and wl.scale != "lowrank":
+            # outside the timed region: the first tensor's outputs of this step against the CPU oracle, bit for bit
+            verified = verify_first_tensor(wl, args, sess, x0[0], ring[order[0]][0])
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for _ in range(args.steps):
@@ -274,10 +278,48 @@ def run_workload(name: str, args, events: HipEvents | None):
                     per_kernel.setdefault(nm, []).append(events.elapsed_ms(sets[s][c][2 * i], sets[s][c][2 * i + 1]))
         res["kernel_ms"] = {nm: sum(v) / len(v) for nm, v in per_kernel.items()}
         res["kernel_launches_per_step"] = {nm: len(v) / n_prof for nm, v in per_kernel.items()}
+    cf.cf_check_device(sess.ctx, sess.stream_handle)           # raises if anything went wrong on the device
+    res["given_up_items_last_step"] = cf.cf_given_up_items(sess.ctx, sess.stream_handle)
+    res["first_step_matches_oracle"] = verified
     sess.close()
     del sess, ring, x0
     torch.cuda.empty_cache()
     return res, wl
+
+
+def verify_first_tensor(wl, args, sess, x0, x1) -> bool:
+    """Tensor 0 after warm-up with x0 and one codec step with x1: codes, scales, error buffer and reconstruction must
+    be the CPU oracle's bits.  Raises on a mismatch (a wrong kernel must not produce a benchmark line)."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from workloads import as_numpy
+
+    torch.cuda.synchronize()
+    scale = {"group": oracle.SCALE_GROUP, "rank1": oracle.SCALE_RANK1, "nm": oracle.SPARSE_NM}.get(wl.scale, oracle.SCALE_CHANNEL)
+    cfg = oracle.Config(wl.n_tokens, wl.n_channels, dtype=oracle.F32 if wl.dtype == "f32" else oracle.BF16, bits=wl.bits_of(0),
+                        scale=scale, group=wl.group, ef=0 if args.ef == 3 else args.ef,
+                        err_dtype=oracle.BF16 if args.err_dtype == "bf16" else oracle.F32)
+    if args.ef == 3:        # naive compression is a function of its own in the oracle: reconstruction, codes, scales
+        recon, codes, scales = oracle.naive(cfg, as_numpy(x1))
+        err = None
+    else:
+        recon, err = oracle.warmup(cfg, as_numpy(x0))
+        codes, scales = oracle.step(cfg, as_numpy(x1), recon, err)
+    got_codes = as_numpy(sess.codes[0]).reshape(-1).copy()
+    if wl.scale == "nm":            # the bytes between the masks and the 16-byte aligned values are never written
+        n_mask = wl.n_tokens * wl.n_channels // 8
+        got_codes[n_mask:(n_mask + 15) // 16 * 16] = 0
+    checks = {"codes": np.array_equal(got_codes, codes.reshape(-1)),
+              "scales": np.array_equal(as_numpy(sess.scales[0]).view(np.uint32).reshape(-1), scales.view(np.uint32).reshape(-1)),
+              "recon": np.array_equal(as_numpy(sess.recon[0]).reshape(-1), recon.reshape(-1))}
+    if err is not None:
+        checks["err"] = np.array_equal(as_numpy(sess.err[0]).reshape(-1), err.reshape(-1))
+    bad = [name for name, ok in checks.items() if not ok]
+    if bad:
+        raise RuntimeError(f"{wl.name}: tensor 0 differs from the CPU oracle after the first step in {bad}")
+    return True
 
 
 def dominant_kernel(res):
@@ -346,15 +388,35 @@ def cpu_baseline(wl, ef: int, budget_s: float = 15.0):
             "seconds_per_tensor_step": spent / done}
 
 
+def source_fingerprint() -> str:
+    """Hash of the library's sources: a recorded profile only describes the kernels it was taken from."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2507_17511_amd", "csrc", "*"))):
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:12]
+
+
 def read_traffic(kernel: str, workload: str):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one for this pair."""
-    path = os.path.join(ROOT, "profiles", f"traffic_{kernel}_{workload}.txt")
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this kernel and workload: a RECORDED value
+    (the counters cannot be read inside this run), used only if it was taken from the sources as they are now.
+    -> (bytes or None, note)"""
+    rel = os.path.join("profiles", f"traffic_{kernel}_{workload}.txt")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
+        return None, "no recorded counter run for this kernel and workload"
+    value, recorded = None, None
     for line in open(path):
         if line.startswith("hbm_bytes_per_launch:"):
-            return float(line.split(":")[1])
-    return None
+            value = float(line.split(":")[1])
+        if line.startswith("source_fingerprint:"):
+            recorded = line.split(":")[1].strip()
+    now = source_fingerprint()
+    if recorded != now:
+        return None, f"{rel} was recorded for sources {recorded}, these are {now}: not used"
+    return value, f"recorded in {rel} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, sources {recorded}); not measured in this run"
 
 
 def main():
@@ -389,8 +451,12 @@ def main():
     if kname is not None:
         kb = kernel_algorithmic_bytes(kname, wl, args.ef, args.split)
         achieved = kb / (kms * 1e-3) / 1e9
+        if args.scale or args.bits or args.tensors or args.ef or args.split or args.flags or args.err_dtype != "f32":
+            traffic, traffic_note = None, "counter runs are recorded for the default options only"
+        else:
+            traffic, traffic_note = read_traffic(kname, head)
         roofline = {"bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBPS, "traffic": None if (args.scale or args.bits or args.tensors or args.ef or args.split or args.err_dtype != "f32") else read_traffic(kname, head),
+                    "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_note,
                     "algorithmic_bytes_per_launch": kb, "avg_launch_ms": kms}
     mfma = None
     if wl.scale == "lowrank" and r.get("kernel_ms"):        # the dense contractions: 2 * 32 flops per element and launch
@@ -416,6 +482,8 @@ def main():
         "roofline": roofline,
         "mfma": mfma,
         "cpu_baseline": cpu,
+        "first_step_matches_oracle": r.get("first_step_matches_oracle"),
+        "source_fingerprint": source_fingerprint(),
     }
     if len(results) > 1:
         out["all_workloads"] = {nm: {k: v for k, v in rr.items() if k != "workload"} for nm, (rr, _) in results.items()}
