@@ -163,10 +163,12 @@ typedef struct {
  * error-feedback mode.  Otherwise one kernel reduces and a second one, which
  * reads the operands again, writes the codes.  Results are bit-identical either
  * way.  By default a call takes the single pass where it applies, every
- * channel-scale tensor of the context has at least 256 tokens and the call covers
- * at least 64 items (it is about 30 % faster on MI355X at the sizes of the paper's
- * models and slower on tiny batches); CF_FLAG_SINGLE_PASS takes it whenever it
- * applies, CF_FLAG_TWO_KERNEL never.
+ * channel-scale tensor of the context has at least 256 tokens and at most 48
+ * items per stripe (12288 tokens of bf16 in the default feedback mode) and the
+ * call covers at least 64 items: it is about 30 % faster on MI355X at the sizes
+ * of the paper's models, slower on tiny batches, and slower than two kernels
+ * where 64 and more workgroups have to agree on a scale (16384 tokens and up).
+ * CF_FLAG_SINGLE_PASS takes it whenever it applies, CF_FLAG_TWO_KERNEL never.
  *
  * Waiting in the single pass.  A workgroup normally finds the partial sums of its
  * stripe within microseconds, because the workgroups of a stripe are launched

@@ -659,7 +659,9 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
     // unless asked for: not for tiny batches (the wait chain costs more than a second read) nor for short tensors
     // (an item is 128 or 256 rows tall: most of its lanes would idle)
     const bool forced = (ctx->opts.flags & CF_FLAG_SINGLE_PASS) != 0;
-    const bool worth_it = forced || (r.item_hi - r.item_lo >= 64u && ctx->L.min_channel_scale_tokens >= 256);
+    // nor for very tall ones (groups of more than 48 items: measured on [N, 3072] bf16 batches of equal size, single pass
+    // against two kernels: N = 8192 1.64 / 1.91 ms, 12288 1.80 / 1.88, 16384 2.04 / 1.91, 32768 2.34 / 1.92)
+    const bool worth_it = forced || (r.item_hi - r.item_lo >= 64u && ctx->L.min_channel_scale_tokens >= 256 && ctx->L.max_group_items <= 48);
     // (a group larger than what the device holds at once would have its first workgroups wait for ones that cannot
     // start before they leave: correct, they give up and the redo launch does them, but slow: such tensors take two kernels)
     if (ctx->L.single_pass && grid >= ctx->L.max_group_items && grid >= 1 && r.item_hi > r.item_lo && worth_it) {
