@@ -244,7 +244,7 @@ __device__ __forceinline__ void lr_backproject_body(const BatchView &v, const Te
     f32x16 acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = (f32x16){};
-    constexpr int U = 4;                                    // token pairs per batch; the next batch is in flight during the MFMAs
+    constexpr int U = (DT == F32) ? 2 : 4;                  // token pairs per batch (fp32 rows take twice the registers); the next batch is in flight during the MFMAs
     Raw8<DT> xr[U], br[U];
     float pv[U];
     auto fetch = [&](int64_t pair0) {
