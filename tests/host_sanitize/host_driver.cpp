@@ -176,6 +176,40 @@ int main()
     }
     cf_destroy(nullptr);
 
+    // ---- which path a call takes by default: the single pass for tensors of 256 tokens and more in calls of 64
+    // items and more, two kernels for tiny ones and for tensors so tall that more than 48 workgroups share a scale
+    {
+        struct Case { int64_t n, c; const char *must, *must_not; uint32_t flags; };
+        const Case cases[] = {
+            {4096, 512, "k_reset_partials k_single_pass k_single_pass_redo", "k_colreduce", 0},       // 16 items per group, 64 in all
+            {16384, 64, "k_colreduce k_finalize k_encode", "k_single_pass", 0},                        // 64 items per group
+            {16384, 64, "k_reset_partials k_single_pass k_single_pass_redo", "k_colreduce", CF_FLAG_SINGLE_PASS},
+            {4096, 256, "k_colreduce k_finalize k_encode", "k_single_pass", 0},                        // 32 items in all: a tiny call
+            {128, 8192, "k_colreduce k_finalize k_encode", "k_single_pass", 0},                        // a short tensor
+            {4096, 512, "k_colreduce k_finalize k_encode", "k_single_pass", CF_FLAG_TWO_KERNEL},
+        };
+        for (const Case &cs : cases) {
+            std::memset(&o, 0, sizeof o);
+            o.flags = cs.flags;
+            cf_tensor_desc d = desc(cs.n, cs.c, CF_BF16, 2, CF_SCALE_CHANNEL);
+            Buffers b(d, &o);
+            const size_t wsb = cf_workspace_bytes(&d, 1, &o);
+            void *ws = nullptr;
+            if (posix_memalign(&ws, 256, wsb) != 0) std::abort();
+            cf_ctx *ctx = nullptr;
+            EXPECT(cf_init(&ctx, &d, 1, &o, ws, wsb, nullptr) == CF_OK);
+            const void *x = b.x;
+            EXPECT(cf_warmup(ctx, 0, 1, &x, &b.recon, &b.err, nullptr) == CF_OK);
+            joined();
+            EXPECT(cf_step_fused(ctx, 0, 1, &x, &b.recon, &b.err, &b.codes, &b.scales, nullptr) == CF_OK);
+            const std::string seq = joined();
+            EXPECT(seq.find(cs.must) != std::string::npos);
+            EXPECT(seq.find(cs.must_not) == std::string::npos);
+            cf_destroy(ctx);
+            std::free(ws);
+        }
+    }
+
     // ---- the entry point that brings no workspace
     {
         std::memset(&o, 0, sizeof o);
