@@ -158,22 +158,19 @@ cf_status make_layout(const cf_tensor_desc *descs, int32_t n, const cf_options &
         if (descs[t].scale == CF_SCALE_RANK1) L.single_pass = false;   // the single-pass kernel knows channel scales only
     // Single-pass item shape: 256 lanes, each with single_pass_rows_per_lane rows, cover kStripeChannels channels by
     // default; when even the tallest channel-scale tensor would make at most 12 items per group that way (bf16:
-    // N <= 3072), items half as tall and twice as wide measure faster (57 x [1024, 3072] bf16: 0.417 -> 0.382 ms;
-    // sweep over [N, 3072]: equal or up to 12 % faster through N = 3072, 2 % slower at N = 4096 with 1-bit codes,
-    // clearly slower from N = 8192 on, where groups get long).
+    // N <= 3072), items half as tall and twice as wide measure equal or faster.  [N, 3072] bf16 batches of equal
+    // size, 128 -> 256 channels, 1- / 2- / 4-bit codes: N = 1024 1.57 / 1.61 / 1.65 -> 1.47 / 1.55 / 1.52 ms,
+    // N = 2048 1.49 / 1.51 / 1.60 -> 1.52 / 1.48 / 1.55, N = 3072 1.47 / 1.52 / 1.61 -> 1.46 / 1.50 / 1.58,
+    // N = 4096 1.50 / 1.55 / 1.62 -> 1.53 / 1.56 / 1.65, N = 6144 1.56 / 1.59 / 1.68 -> 1.62 / 1.66 / 1.77.
     auto narrow_item_rows = [&](int32_t dtype) { return (kPersistThreads / (kStripeChannels / kChunk)) * single_pass_rows_per_lane(dtype, o.ef); };
-    // Up to 16 items per group (N = 4096) the wide stripe still pays for 2- and 4-bit codes, whose code rows
-    // then are whole 64- and 128-byte pieces (4-bit: 7 % faster), but not for 1-bit codes (2 % slower).
     int64_t narrow_max_group = 0;
-    bool one_bit = false;
     for (int32_t t = 0; t < n; ++t)
         if (descs[t].scale == CF_SCALE_CHANNEL) {
             const int64_t rows = narrow_item_rows(descs[t].dtype);
             const int64_t g = (descs[t].n_tokens + rows - 1) / rows;
             if (g > narrow_max_group) narrow_max_group = g;
-            if (descs[t].bits == 1) one_bit = true;
         }
-    L.sp_wide = L.single_pass && narrow_max_group > 0 && (narrow_max_group <= 12 || (narrow_max_group <= 16 && !one_bit));
+    L.sp_wide = L.single_pass && narrow_max_group > 0 && narrow_max_group <= 12;
     const int stripe_channels = L.sp_wide ? kStripeChannelsWide : kStripeChannels;
     for (int32_t t = 0; t < n; ++t) {
         const cf_tensor_desc &d = descs[t];

@@ -120,12 +120,13 @@ def test_single_pass_many_row_blocks_and_stripes():
 
 
 def test_single_pass_stripe_width_rule_boundaries():
-    """The single-pass kernel takes 256-channel stripes for contexts of short tensors and for 4096-token contexts
-    without 1-bit tensors, 128-channel ones otherwise: contexts on both sides of each boundary (N = 3072 / 3328;
-    N = 4096 with and without a 1-bit tensor), ragged in both directions, against the oracle."""
+    """The single-pass kernel takes 256-channel stripes for contexts whose tallest channel-scale tensor makes at most
+    12 items per group with 128-channel ones (bf16: N <= 3072), 128-channel stripes otherwise: contexts on both sides
+    of the boundary (N = 3072 / 3328) and at N = 4096 with and without a 1-bit tensor, ragged in both directions,
+    against the oracle."""
     cases = [[(3072, 264, 1), (1000, 1096, 2)],                 # wide, groups of 24 and 8 items
              [(3328, 264, 1), (1000, 1096, 2)],                 # narrow, groups of 13 and 4
-             [(4096, 264, 4), (4000, 136, 2)],                  # wide (no 1-bit tensor), groups of 32
+             [(4096, 264, 4), (4000, 136, 2)],                  # narrow, groups of 16
              [(4096, 264, 4), (4000, 136, 1)]]                  # narrow, groups of 16
     for k, shapes in enumerate(cases):
         say(f"stripe width boundary case {k}: {shapes}")
