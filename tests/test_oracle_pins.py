@@ -519,6 +519,35 @@ def test_error_feedback_bounds_drift_and_naive_fails(cfo):
     assert naive_err > 20 * with_ef[-1]                                # sigma_a^2 >> sigma_Delta^2 (Prop. 3.1)
 
 
+def test_naive_is_a_step_from_the_zero_state_and_has_closed_forms(cfo):
+    """Sec. 3.1: naive compression quantises the activation itself.  That is one codec step against the zero
+    state (recon = 0, e = 0), which the recursion's own pins cover: same codes, same scales, recon = D, for every
+    code width and both storage types.  And in closed form: a column of constant magnitude a with mixed signs has
+    the 1-bit scale a (N a power of two: the tree sum is exact), so the reconstruction is the input itself."""
+    rng = np.random.default_rng(11)
+    for dtype in (cfo.F32, cfo.BF16):
+        for bits in (1, 2, 4):
+            N, C = 48, 40                                            # N not a power of two: zero padding in the tree
+            cfg = cfo.Config(N, C, dtype=dtype, bits=bits)
+            x = (rng.standard_normal((N, C)) * np.exp(rng.standard_normal((1, C)))).astype(np.float32)
+            if dtype == cfo.BF16:
+                x = cfo.f32_to_bf16(x)
+            rn, cn, sn = cfo.naive(cfg, x)
+            zero = np.zeros((N, C), dtype=cfg.np_dtype)
+            recon, err = cfo.warmup(cfg, zero)
+            cs, ss = cfo.step(cfg, x, recon, err)
+            assert np.array_equal(cn, cs) and np.array_equal(sn.view(np.uint32), ss.view(np.uint32))
+            assert np.array_equal(rn.view(np.uint8), recon.view(np.uint8))
+    N, C = 64, 16
+    a = np.linspace(0.25, 4.0, C, dtype=np.float32)                 # one magnitude per column (exact in fp32)
+    sign = np.where(rng.random((N, C)) < 0.5, -1.0, 1.0).astype(np.float32)
+    x = sign * a[None, :]
+    rn, cn, sn = cfo.naive(cfo.Config(N, C, dtype=cfo.F32, bits=1), x)
+    assert np.array_equal(sn, a) and np.array_equal(rn, x)
+    bits_expected = np.packbits((x < 0).astype(np.uint8), axis=1, bitorder="little")
+    assert np.array_equal(cn.reshape(N, C // 8), bits_expected)
+
+
 def test_literal_mode_is_second_order(cfo):
     """LITERAL adds e on top of a residual that already contains it: x_t - recon_t = e_t - e_{t-1}."""
     cfg = cfo.Config(96, 64, dtype=cfo.F32, bits=2, ef=cfo.EF_LITERAL)
