@@ -531,8 +531,18 @@ struct ProfileScope {      // a profiled call is exactly one entry-point call
 // Brings the workspace pointer table up to date for [first, first+count).
 // Arrays that an entry point does not take are passed as nullptr and keep
 // their last value.  Nothing is launched when no pointer changed.
+// The last batch of pointer sets of a call, left for the call's next kernel to write (see sync_ptrs).
+struct DeferredPtrs {
+    PtrChunk chunk;
+    TensorPtrs *dst = nullptr;
+    int n = 0;
+    DeferredPtrs() { std::memset(&chunk, 0, sizeof chunk); }
+};
+
+// defer: the caller's next launch is a kernel that can write one batch of pointer sets itself (k_reset_partials):
+// the last batch is handed back instead of launched.
 cf_status sync_ptrs(cf_ctx *ctx, int32_t first, int32_t count, const void *const *x, void *const *recon,
-                    void *const *err, void *const *codes, void *const *scales, hipStream_t s)
+                    void *const *err, void *const *codes, void *const *scales, hipStream_t s, DeferredPtrs *defer = nullptr)
 {
     bool changed = false;
     for (int32_t k = 0; k < count; ++k) {
@@ -568,6 +578,12 @@ cf_status sync_ptrs(cf_ctx *ctx, int32_t first, int32_t count, const void *const
         PtrChunk chunk;
         std::memset(&chunk, 0, sizeof chunk);
         for (int k = 0; k < m; ++k) chunk.p[k] = ctx->ptrs[lo + k0 + k];
+        if (defer && k0 + m == n) {     // the caller's next kernel takes this one along
+            defer->chunk = chunk;
+            defer->dst = table + lo + k0;
+            defer->n = m;
+            break;
+        }
         hipError_t e = launch(ctx, s, "k_upload_ptrs", [&] { return launch_upload_ptrs(chunk, table + lo + k0, m, s); });
         if (e != hipSuccess) return device_fail(ctx, e);       // the table counts as unknown: the next call uploads all of it
     }
@@ -647,7 +663,6 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     ProfileScope prof(ctx);
-    if ((st = sync_ptrs(ctx, first, count, x, recon, err, codes, scales, s)) != CF_OK) return st;
     BatchView v = ctx->view();
     LaunchRange r = ctx->range(first, count);
     const int ef = ctx->opts.ef, et = ctx->opts.err_dtype;
@@ -661,10 +676,17 @@ cf_status run_sender(cf_ctx *ctx, int32_t first, int32_t count, const void *cons
     const bool worth_it = forced || (r.item_hi - r.item_lo >= 64u && ctx->L.min_channel_scale_tokens >= 256 && ctx->L.max_group_items <= 48);
     // (a group larger than what the device holds at once would have its first workgroups wait for ones that cannot
     // start before they leave: correct, they give up and the redo launch does them, but slow: such tensors take two kernels)
-    if (ctx->L.single_pass && grid >= ctx->L.max_group_items && grid >= 1 && r.item_hi > r.item_lo && worth_it) {
+    const bool single_pass = ctx->L.single_pass && grid >= ctx->L.max_group_items && grid >= 1 && r.item_hi > r.item_lo && worth_it;
+    // the call's pointers go to the table first; the single pass's first kernel takes the last batch of them along
+    DeferredPtrs defer;
+    if ((st = sync_ptrs(ctx, first, count, x, recon, err, codes, scales, s, single_pass ? &defer : nullptr)) != CF_OK) return st;
+    if (single_pass) {
         // channel-scale tensors: one pass, the operands stay in registers across the scale reduction
-        e = launch(ctx, s, "k_reset_partials", [&] { return launch_reset_partials(v, r, s); });
-        if (e != hipSuccess) return device_fail(ctx, e);
+        e = launch(ctx, s, "k_reset_partials", [&] { return launch_reset_partials(v, r, defer.chunk, defer.dst, defer.n, s); });
+        if (e != hipSuccess) {
+            ctx->ptrs_synced = false;       // the batch that kernel was to write never reached the table
+            return device_fail(ctx, e);
+        }
         // measured on [N, 3072] bf16 batches: up to 4 row blocks per tensor a run of consecutive items per XCD is
         // 4-20 % faster (the stripes of a code row meet in one L2), from 6 on dealing them round the XCDs is 8-15 % faster
         r.sp_xcd_major = ctx->L.max_group_items <= 4;

@@ -170,6 +170,7 @@ int persistent_max_blocks_per_cu(int ef, int err_dtype, bool fused, bool wide);
 // item, else `grid` workgroups that loop over the items
 hipError_t launch_single_pass(const BatchView &v, const LaunchRange &r, int ef, int err_dtype, bool fused, bool wide, int grid,
                              bool one_shot, bool redo, hipStream_t s);
-hipError_t launch_reset_partials(const BatchView &v, const LaunchRange &r, hipStream_t s);
+// also writes `n` pointer sets of the call to the table (dst), which saves the call a launch of k_upload_ptrs; n may be 0
+hipError_t launch_reset_partials(const BatchView &v, const LaunchRange &r, const PtrChunk &chunk, TensorPtrs *dst, int n, hipStream_t s);
 
 }  // namespace cf

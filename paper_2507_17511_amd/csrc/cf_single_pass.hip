@@ -315,10 +315,13 @@ __global__ __launch_bounds__(kPersistThreads, 2) void k_single_pass(BatchView v,
     }
 }
 
-// Every partial starts a call as "unpublished" (a fill kernel, so the call can be captured in a graph).
-__global__ void k_reset_partials(u32x4 *words, uint64_t n_vec, uint32_t *gave_up)
+// Every partial starts a call as "unpublished" (a fill kernel, so the call can be captured in a graph).  The
+// first kernel of a single pass also takes the call's last batch of device pointers to the table (see
+// k_upload_ptrs): one launch fewer per call.
+__global__ void k_reset_partials(u32x4 *words, uint64_t n_vec, uint32_t *gave_up, PtrChunk chunk, TensorPtrs *dst, int n)
 {
     if (blockIdx.x == 0 && threadIdx.x == 0) *gmut<uint32_t>(gave_up) = 0u;        // the list of given-up items is empty
+    if (blockIdx.x == 0 && (int)threadIdx.x < n) dst[threadIdx.x] = chunk.p[threadIdx.x];
     const u32x4 fill = (u32x4)(kUnpublished);
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += (uint64_t)gridDim.x * blockDim.x)
         *gmut<u32x4>(words + i) = fill;
@@ -355,13 +358,15 @@ int persistent_max_blocks_per_cu(int ef, int err_dtype, bool fused, bool wide)
     return n;
 }
 
-hipError_t launch_reset_partials(const BatchView &v, const LaunchRange &r, hipStream_t s)
+hipError_t launch_reset_partials(const BatchView &v, const LaunchRange &r, const PtrChunk &chunk, TensorPtrs *dst, int n, hipStream_t s)
 {
-    if (r.p_partial_hi <= r.p_partial_lo) return hipSuccess;
-    const uint64_t n_vec = (r.p_partial_hi - r.p_partial_lo) / 16;      // offsets are multiples of 256
-    const uint64_t want = (n_vec + 255) / 256;
+    static_assert(kMaxUploadTensors <= 256, "one block of k_reset_partials writes the pointer sets");
+    const bool none = r.p_partial_hi <= r.p_partial_lo;
+    if (none && n == 0) return hipSuccess;
+    const uint64_t n_vec = none ? 0 : (r.p_partial_hi - r.p_partial_lo) / 16;      // offsets are multiples of 256
+    const uint64_t want = n_vec == 0 ? 1 : (n_vec + 255) / 256;
     hipLaunchKernelGGL(k_reset_partials, dim3((unsigned)(want < 2048 ? want : 2048)), dim3(256), 0, s,
-                       reinterpret_cast<u32x4 *>(v.workspace + r.p_partial_lo), n_vec, v.error_flag + kGaveUpWord);
+                       reinterpret_cast<u32x4 *>(v.workspace + r.p_partial_lo), n_vec, v.error_flag + kGaveUpWord, chunk, dst, n);
     return hipGetLastError();
 }
 

@@ -70,7 +70,13 @@ hipError_t launch_single_pass(const BatchView &, const LaunchRange &, int, int, 
     note(redo ? "k_single_pass_redo" : "k_single_pass");
     return hipSuccess;
 }
-hipError_t launch_reset_partials(const BatchView &, const LaunchRange &, hipStream_t) { note("k_reset_partials"); return hipSuccess; }
+hipError_t launch_reset_partials(const BatchView &, const LaunchRange &, const PtrChunk &chunk, TensorPtrs *dst, int n, hipStream_t)
+{
+    if (n > 0) note("ptrs_in_reset");       // the call's last batch of pointer sets rides along
+    note("k_reset_partials");
+    if (n > 0) std::memcpy(dst, chunk.p, sizeof(TensorPtrs) * (size_t)n);
+    return hipSuccess;
+}
 hipError_t static_scratch(void **ptr)
 {
     static void *buf = nullptr;
